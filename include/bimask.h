@@ -1,0 +1,175 @@
+/*
+ * bimask.h -- C ABI of the Bi-Mask N:M sparse-training hot path for AMD MI355X (gfx950).
+ *
+ * Method: "Bi-directional Masks for Efficient N:M Sparse Training" (arXiv 2302.06058).
+ * One training step of one linear / conv-as-GEMM layer (Alg. 1) maps onto the calls
+ * below in this order:
+ *
+ *     bimask_forward_mask      B     = top-N-of-M along the rows of W            Eq. (4), Eq. (2)
+ *     bimask_compress_nm       W_f   = compressed (B .* W)                       operand of Eq. (3)
+ *     bimask_sparse_gemm_fwd   Y     = X * (B .* W)^T                            Eq. (3)
+ *     bimask_perm_search       P     = best of K row permutations               Sec. 3.3, Alg. 1
+ *     bimask_backward_mask     Bbar  = top-N-of-M along the columns of
+ *                                      (B .* W)[P,:], AND-ed with B[P,:]         Eq. (11) / Eq. (9)
+ *     bimask_compress_nm       W_b   = compressed (Bbar .* W[P,:])^T             operand of Eq. (10)
+ *     bimask_sparse_gemm_bwd   dX    = dY[:,P] * (Bbar .* W[P,:])                Eq. (10) / Eq. (8)
+ *
+ * The weight gradient dW = dY^T * X stays dense (straight-through estimator, Sec. 3.1)
+ * and is not part of this library.
+ *
+ * Shapes and layouts (all row-major, zero-based; "ld" = leading dimension in elements):
+ *     W      I x J   weights, I = out features, J = in features          (Sec. 3.1)
+ *     X      T x J   activations, T = tokens; the paper writes X as J x T and Y = W * X
+ *     Y, dY  T x I   output and its gradient g(Y)
+ *     dX     T x J   the approximate input gradient g-bar(X)
+ *     B      I x J   forward mask bits, N:M along each row               (Eq. 2)
+ *     Bbar   I x J   backward mask bits, N:M along each column, rows in PERMUTED order:
+ *                    row r of Bbar belongs to row P[r] of W              (Eq. 7, Eq. 11)
+ *     P      I       row permutation in gather form: (W[P,:])[r] = W[P[r]]
+ *
+ * Bit matrices: ceil(cols/32) uint32 words per row; entry j is bit (j % 32) of word
+ * (j / 32); unused high bits of the last word of a row are written as zero.
+ *
+ * Compressed N:M operand (this library's format; the paper only names the sparse
+ * tensor core as consumer):
+ *   for (N, M) = (2, 4):
+ *     values  rows x (cols/2) elements: per group of 4 the two slot values in ascending
+ *             position order
+ *     index   rows x ceil(cols/32) uint32: per group one nibble p0 | (p1 << 2), p0 < p1,
+ *             group g of a row at bits [4g+3 : 4g] of that row's little-endian bit stream
+ *     The slot positions are the mask's ones; a group whose mask holds fewer than two
+ *     ones is completed with its lowest-index zero positions, which carry value 0.
+ *   for every other (N, M): values is the dense masked matrix rows x cols (zeros where the
+ *     mask is 0) and index is not written (may be NULL).
+ *   transposed = 0: rows = I, cols = J (groups along J).
+ *   transposed = 1: rows = J, cols = I (groups along the permuted row index r).
+ *
+ * Conventions:
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library allocates
+ *     nothing, keeps no state between calls, and never synchronises: every call only
+ *     enqueues work on `stream` (a hipStream_t passed as void*, NULL = default stream).
+ *   - Return value: BIMASK_OK or a bimask_status error.  Argument errors are detected on
+ *     the host before anything is launched and leave all outputs untouched.  Nothing
+ *     aborts or throws across this boundary.
+ *   - I and J must be multiples of M; M is 4, 8 or 16; 1 <= N < M.  Callers pad ragged
+ *     shapes with zero columns (a zero never displaces a real weight because the lowest
+ *     index wins ties and padding sits at the highest indices).
+ *   - Magnitudes are compared on the stored dtype's bit pattern with the sign cleared,
+ *     so the order is total: ties keep the lowest index, +0 = -0, and inputs are assumed
+ *     finite.  Exactly N entries are kept per forward group.
+ *   - Permutations are not validated (each must hold every value of 0..I-1 once).
+ */
+#ifndef BIMASK_H
+#define BIMASK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BIMASK_API __attribute__((visibility("default")))
+
+typedef enum {
+    BIMASK_OK = 0,
+    BIMASK_ERR_NULL = 1,        /* a required pointer is NULL */
+    BIMASK_ERR_SHAPE = 2,       /* size <= 0, I % M, J % M, ld < cols, K <= 0 */
+    BIMASK_ERR_NM = 3,          /* M not in {4, 8, 16} or not 1 <= N < M */
+    BIMASK_ERR_DTYPE = 4,       /* dtype is neither BIMASK_F32 nor BIMASK_BF16 */
+    BIMASK_ERR_UNSUPPORTED = 5, /* a combination this build has no kernel for */
+    BIMASK_ERR_WORKSPACE = 6,   /* workspace NULL or smaller than bimask_workspace_bytes says */
+    BIMASK_ERR_ALIGN = 7,       /* a pointer or leading dimension breaks a stated alignment */
+    BIMASK_ERR_HIP = 8          /* the HIP runtime reported an error at launch */
+} bimask_status;
+
+typedef enum { BIMASK_F32 = 0, BIMASK_BF16 = 1 } bimask_dtype;
+
+typedef enum {
+    BIMASK_WS_PERM_SEARCH = 0,
+    BIMASK_WS_GEMM_FWD = 1,
+    BIMASK_WS_GEMM_BWD = 2
+} bimask_ws_kind;
+
+/* Forward mask, Eq. (4) under the constraint of Eq. (2): in every group of M consecutive
+ * columns of every row keep the N largest magnitudes.
+ *   W       in   I x J, leading dimension ldw >= J, dtype `dtype`
+ *   B_bits  out  I x ceil(J/32) words                                                  */
+BIMASK_API int bimask_forward_mask(const void *W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
+                        uint32_t *B_bits, void *stream);
+
+/* Forward mask and the compressed forward operand in one pass over W (same results as
+ * bimask_forward_mask followed by bimask_compress_nm(transposed = 0)).
+ *   values  out  I x (J/2) elements for 2:4, else I x J            (row stride = that width)
+ *   index   out  I x ceil(J/32) words for 2:4, else ignored                            */
+BIMASK_API int bimask_forward_mask_compress(const void *W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
+                                 uint32_t *B_bits, void *values, uint32_t *index, void *stream);
+
+/* Row-permutation search, Sec. 3.3 and Alg. 1: scores[c] = number of (block, column)
+ * pairs of (B .* W)[perms[c],:] -- a block being M consecutive permuted rows -- that hold
+ * at most N ones of B ("eligible N:M blocks"); best = the lowest c with the highest score.
+ *   B_bits     in   forward mask
+ *   perms      in   K x I int32, candidate c at perms + c*I; 16-byte aligned
+ *   scores     out  K int32 (fits: the maximum is (I/M)*J)
+ *   best       out  1 int32
+ *   best_perm  out  I int32, a copy of perms[best]; may be NULL
+ *   workspace  scratch of bimask_workspace_bytes(BIMASK_WS_PERM_SEARCH, ...) bytes       */
+BIMASK_API int bimask_perm_search(const uint32_t *B_bits, int64_t I, int64_t J, int N, int M,
+                       const int32_t *perms, int K, int32_t *scores, int32_t *best, int32_t *best_perm,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* Backward mask, Eq. (11); with perm = NULL (identity) it is Eq. (9).  For every column
+ * and every block of M consecutive permuted rows: rank the magnitudes of
+ * (B .* W)[P[r], l], select the top N (lowest r first among equals) and AND the selection
+ * with B[P[r], l], so Bbar <= B[P,:] and every block holds at most N ones (Eq. 7).
+ *   perm       in   I int32 or NULL
+ *   Bbar_bits  out  I x ceil(J/32) words, rows in permuted order                        */
+BIMASK_API int bimask_backward_mask(const void *W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
+                         const uint32_t *B_bits, const int32_t *perm, uint32_t *Bbar_bits, void *stream);
+
+/* Backward mask and the transposed compressed backward operand in one pass (same results
+ * as bimask_backward_mask followed by bimask_compress_nm(transposed = 1)).
+ *   values  out  J x (I/2) elements for 2:4, else J x I
+ *   index   out  J x ceil(I/32) words for 2:4, else ignored                             */
+BIMASK_API int bimask_backward_mask_compress(const void *W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
+                                  const uint32_t *B_bits, const int32_t *perm, uint32_t *Bbar_bits,
+                                  void *values, uint32_t *index, void *stream);
+
+/* Compress a masked weight matrix into the operand format described at the top.
+ *   transposed = 0: mask_bits = B (rows of W), perm must be NULL; output rows = I.
+ *   transposed = 1: mask_bits = Bbar (permuted rows), perm = P or NULL; output row l is
+ *                   column l of (Bbar .* W[P,:]); output rows = J.
+ * The mask must hold at most N ones per group.                                          */
+BIMASK_API int bimask_compress_nm(const void *W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
+                       const uint32_t *mask_bits, const int32_t *perm, int transposed,
+                       void *values, uint32_t *index, void *stream);
+
+/* Forward GEMM, Eq. (3):  Y[t][i] = sum_j X[t][j] * (B .* W)[i][j], with (B .* W) given in
+ * compressed form (transposed = 0).  bf16: fp32 accumulation, bf16 output, 2:4 on the
+ * sparse matrix cores, other ratios on the dense matrix cores; f32: fp32 throughout.
+ *   X  in  T x J (ldx >= J);   Y  out  T x I (ldy >= I);   same dtype as the values.
+ *   Pointers at least 4-byte aligned and, for bf16, even leading dimensions (else
+ *   BIMASK_ERR_ALIGN); 16-byte aligned pointers and row pitches take the fast path.     */
+BIMASK_API int bimask_sparse_gemm_fwd(const void *X, int64_t T, int64_t ldx, const void *Wf_values, const uint32_t *Wf_index,
+                           int64_t I, int64_t J, int dtype, int N, int M, void *Y, int64_t ldy,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* Backward GEMM, Eq. (10):  dX[t][j] = sum_r dY[t][P[r]] * (Bbar .* W[P,:])[r][j], with the
+ * weight operand given in transposed compressed form (transposed = 1); perm = NULL is Eq. (8).
+ *   dY  in  T x I (lddy >= I);   dX  out  T x J (lddx >= J).
+ *   workspace: bimask_workspace_bytes(BIMASK_WS_GEMM_BWD, ...) bytes (holds dY[:,P]).     */
+BIMASK_API int bimask_sparse_gemm_bwd(const void *dY, int64_t T, int64_t lddy, const int32_t *perm,
+                           const void *Wb_values, const uint32_t *Wb_index, int64_t I, int64_t J,
+                           int dtype, int N, int M, void *dX, int64_t lddx,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* Scratch bytes a call needs (0 if none).  kind is a bimask_ws_kind.                     */
+BIMASK_API size_t bimask_workspace_bytes(int kind, int64_t I, int64_t J, int64_t T, int K, int dtype, int N, int M);
+
+/* Static, never NULL.                                                                    */
+BIMASK_API const char *bimask_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BIMASK_H */

@@ -103,23 +103,37 @@ void oracle_backward_mask(const double *W, const uint8_t *B, int64_t I, int64_t 
         }
 }
 
-/* Compressed forward operand: per row and group the N kept values in ascending
- * position order plus their positions.  val: I x (J/M*N), idx: same shape. */
+/* Slot positions of one group given its mask bits: the ones (lowest first, at most N),
+ * completed with the lowest-index zeros until N positions are chosen. */
+static void slots_of_mask(const uint8_t *bits, int M, int N, uint8_t *chosen)
+{
+    int n = 0;
+    memset(chosen, 0, (size_t)M);
+    for (int m = 0; m < M && n < N; ++m)
+        if (bits[m]) { chosen[m] = 1; ++n; }
+    for (int m = 0; m < M && n < N; ++m)
+        if (!bits[m]) { chosen[m] = 1; ++n; }
+}
+
+/* Compressed forward operand: per row and group N slots in ascending position order
+ * with their positions.  A slot whose mask bit is 0 (only possible when the mask holds
+ * fewer than N ones in that group) carries the value 0.  val: I x (J/M*N), idx: same. */
 void oracle_compress_fwd(const double *W, const uint8_t *B, int64_t I, int64_t J, int N, int M,
                          double *val, uint8_t *idx)
 {
+    uint8_t chosen[64];
     int64_t S = J / M * N;
     for (int64_t i = 0; i < I; ++i)
         for (int64_t g = 0; g < J / M; ++g) {
+            const uint8_t *bits = B + i * J + g * M;
+            slots_of_mask(bits, M, N, chosen);
             int n = 0;
-            for (int m = 0; m < M && n < N; ++m)
-                if (B[i * J + g * M + m]) {
-                    val[i * S + g * N + n] = W[i * J + g * M + m];
+            for (int m = 0; m < M; ++m)
+                if (chosen[m]) {
+                    val[i * S + g * N + n] = bits[m] ? W[i * J + g * M + m] : 0.0;
                     idx[i * S + g * N + n] = (uint8_t)m;
                     ++n;
                 }
-            /* a forward mask always holds exactly N per group */
-            for (; n < N; ++n) { val[i * S + g * N + n] = 0.0; idx[i * S + g * N + n] = 0xFF; }
         }
 }
 

@@ -1,0 +1,96 @@
+// Shared host/device helpers of the Bi-Mask HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/bimask.h"
+
+namespace bimask {
+
+constexpr int kThreads = 256;   // 4 wavefronts of 64 lanes per workgroup
+
+// Storage types: weights travel as raw bit patterns, magnitudes are compared as
+// unsigned integers with the sign bit cleared (total order, +0 == -0).
+struct BF16 { using raw = uint16_t; static constexpr uint32_t kAbs = 0x7FFFu; };
+struct F32  { using raw = uint32_t; static constexpr uint32_t kAbs = 0x7FFFFFFFu; };
+
+__host__ __device__ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+__host__ __device__ inline int ilog2(int m) { int b = 0; while ((1 << b) < m) ++b; return b; }
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+
+inline int check_launch() {
+    return hipGetLastError() == hipSuccess ? BIMASK_OK : BIMASK_ERR_HIP;
+}
+
+// Top-N of M by key; the lower position wins among equal keys.  Returns the
+// selected positions as a bit set (exactly N bits).
+template <int M>
+__device__ __forceinline__ uint32_t select_top_n(const uint32_t (&key)[M], int N) {
+    int rank[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) rank[m] = 0;
+#pragma unroll
+    for (int a = 0; a < M; ++a)
+#pragma unroll
+        for (int b = a + 1; b < M; ++b) {
+            const int a_first = key[a] >= key[b];   // a has the lower index: it wins ties
+            rank[b] += a_first;
+            rank[a] += 1 - a_first;
+        }
+    uint32_t sel = 0;
+#pragma unroll
+    for (int m = 0; m < M; ++m) sel |= (rank[m] < N ? 1u : 0u) << m;
+    return sel;
+}
+
+// Slot positions of a group given its mask bits: the ones (at most N are used, lowest
+// first) completed with the lowest-index zeros up to N positions.
+template <int M>
+__device__ __forceinline__ uint32_t complete_slots(uint32_t bits, int N) {
+    uint32_t sel = 0;
+    int n = 0;
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        const bool take = ((bits >> m) & 1u) && n < N;
+        sel |= (take ? 1u : 0u) << m;
+        n += take;
+    }
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        const bool take = !((bits >> m) & 1u) && n < N;
+        sel |= (take ? 1u : 0u) << m;
+        n += take;
+    }
+    return sel;
+}
+
+// launchers implemented in the .hip files -------------------------------------------
+int launch_forward(const void* W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
+                   const uint32_t* mask_in, uint32_t* B_bits, void* values, uint32_t* index,
+                   bool want_values, hipStream_t s);
+int launch_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
+                    const uint32_t* B_bits, const uint32_t* Bbar_in, const int32_t* perm,
+                    uint32_t* Bbar_bits, void* values, uint32_t* index, bool want_values, hipStream_t s);
+
+struct PermPlan {
+    int word_bytes;      // 8 or 4: width of one LDS column word
+    int ctw;             // column words per tile
+    int ntiles;          // column tiles
+    int kc;              // candidate chunks (grid = ntiles * kc)
+    size_t lds_bytes;    // dynamic LDS per workgroup
+    size_t ws_bytes;     // partial-score scratch
+    bool ok;
+};
+PermPlan plan_perm_search(int64_t I, int64_t J, int K);
+int launch_perm_search(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perms, int K,
+                       int32_t* scores, int32_t* best, int32_t* best_perm, void* ws, hipStream_t s);
+
+int launch_gather_cols(const void* dY, int64_t T, int64_t ld, const int32_t* perm, int64_t I, int dtype,
+                       void* out, hipStream_t s);
+// C[t][a] = sum_k Bm[t][k] * A[a][k];  A sparse 2:4 (values + index) or dense.
+int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int64_t K, bool sparse24,
+                const void* Bm, int64_t T, int64_t ldb, void* C, int64_t ldc, int dtype, hipStream_t s);
+
+}  // namespace bimask

@@ -1,0 +1,392 @@
+// N:M-sparse GEMMs of Bi-Mask (Eq. 3 and Eq. 10 of arXiv 2302.06058) on gfx950.
+//
+// Both directions are the same contraction   C[t][a] = sum_k Bm[t][k] * A[a][k]
+//   forward : A = (B .* W)       (a = out feature i, k = in feature j),  Bm = X,      C = Y
+//   backward: A = (Bbar.*W[P,:])^T (a = in feature j, k = permuted row r), Bm = dY[:,P], C = dX
+// A is the weight operand: only the A side of a sparse matrix instruction may be 2:4
+// compressed, so the weights sit on the A side and the product is formed transposed
+// (rows of the accumulator tile are weight rows, columns are tokens).
+//
+// bf16, 2:4  : v_smfmac_f32_32x32x32_bf16, A read in compressed form (values + 2-bit indices)
+// bf16, other: v_mfma_f32_32x32x16_bf16 on the dense masked weights
+// fp32       : plain fp32 FMA kernel (small problems only)
+#include "common.hpp"
+
+namespace bimask {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(__bf16)))) __bf16 bf16x16;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int BK = 64;                // dense k per pipeline stage
+constexpr int kRowB = 144;            // LDS bytes per 64-k row of a dense operand (128 + 16 pad)
+constexpr int kRowAs = 80;            // LDS bytes per 64-k row of compressed values (64 + 16 pad)
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// 8 consecutive bf16 of a row starting at element k (zero beyond kend).
+__device__ __forceinline__ uint4 load_granule(const uint16_t* row, int64_t k, int64_t kend, bool vec) {
+    if (k + 8 <= kend) {
+        if (vec) return *reinterpret_cast<const uint4*>(row + k);
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(row + k);
+        return make_uint4(p[0], p[1], p[2], p[3]);
+    }
+    uint32_t w[4] = {0, 0, 0, 0};
+    for (int e = 0; e < 8; ++e)
+        if (k + e < kend) w[e >> 1] |= static_cast<uint32_t>(row[k + e]) << (16 * (e & 1));
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+template <bool SPARSE, int BM, int BN>
+struct Smem {
+    static constexpr int kA = SPARSE ? BM * kRowAs : BM * kRowB;
+    static constexpr int kMeta = SPARSE ? BM * 8 : 0;
+    static constexpr int kB = BN * kRowB;
+    static constexpr int kStage = kA + kMeta + kB;
+    static constexpr int kCRow = BM * 2 + 16;
+    static constexpr int kC = BN * kCRow;
+    static constexpr int kTotal = (2 * kStage > kC) ? 2 * kStage : kC;
+};
+
+// Workgroup tile BM (weight rows a) x BN (tokens t); WAVES_M x WAVES_N wavefronts.
+template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N>
+__global__ void __launch_bounds__(kThreads)
+k_gemm_bf16(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int64_t K,
+            const uint16_t* __restrict__ Bm, int64_t T, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
+            int tiles_a, bool vecA, bool vecB, bool vecC) {
+    static_assert(WAVES_M * WAVES_N == kThreads / 64, "four wavefronts");
+    using S = Smem<SPARSE, BM, BN>;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    extern __shared__ uint4 smem_u4[];
+    uint8_t* smem = reinterpret_cast<uint8_t*>(smem_u4);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+    const int64_t a0 = static_cast<int64_t>(blockIdx.x % tiles_a) * BM;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x / tiles_a) * BN;
+    const int64_t lda = SPARSE ? K / 2 : K;              // elements per row of A values
+    const int64_t wprA = ceil_div(K, 32);                // index words per row
+    const int nk = static_cast<int>(ceil_div(K, BK));
+
+    constexpr int NB_ = BN * 8 / kThreads;               // 16-byte granules per thread, B tile
+    constexpr int NA_ = (SPARSE ? BM * 4 : BM * 8) / kThreads;
+    constexpr int NM_ = SPARSE ? (BM * 2 + kThreads - 1) / kThreads : 0;
+    uint4 rb[NB_], ra[NA_];
+    uint32_t rm[NM_ > 0 ? NM_ : 1];
+
+    auto load_tile = [&](int kt) {
+        const int64_t k0 = static_cast<int64_t>(kt) * BK;
+#pragma unroll
+        for (int it = 0; it < NB_; ++it) {
+            const int q = tid + kThreads * it, row = q >> 3, g = q & 7;
+            int64_t t = t0 + row; t = t < T ? t : T - 1;
+            rb[it] = load_granule(Bm + t * ldb, k0 + 8 * g, K, vecB);
+        }
+        if constexpr (SPARSE) {
+#pragma unroll
+            for (int it = 0; it < NA_; ++it) {
+                const int q = tid + kThreads * it, row = q >> 2, g = q & 3;
+                int64_t a = a0 + row; a = a < Adim ? a : Adim - 1;
+                ra[it] = load_granule(A + a * lda, k0 / 2 + 8 * g, lda, vecA);
+            }
+#pragma unroll
+            for (int it = 0; it < NM_; ++it) {
+                const int q = tid + kThreads * it, row = q >> 1, w = q & 1;
+                int64_t a = a0 + row; a = a < Adim ? a : Adim - 1;
+                const int64_t wi = k0 / 32 + w;
+                rm[it] = (q < BM * 2 && wi < wprA) ? Ameta[a * wprA + wi] : 0u;
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < NA_; ++it) {
+                const int q = tid + kThreads * it, row = q >> 3, g = q & 7;
+                int64_t a = a0 + row; a = a < Adim ? a : Adim - 1;
+                ra[it] = load_granule(A + a * lda, k0 + 8 * g, K, vecA);
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+        uint8_t* sA = smem + buf * S::kStage;
+        uint8_t* sM = sA + S::kA;
+        uint8_t* sB = sM + S::kMeta;
+#pragma unroll
+        for (int it = 0; it < NB_; ++it) {
+            const int q = tid + kThreads * it, row = q >> 3, g = q & 7;
+            *reinterpret_cast<uint4*>(sB + row * kRowB + g * 16) = rb[it];
+        }
+        if constexpr (SPARSE) {
+#pragma unroll
+            for (int it = 0; it < NA_; ++it) {
+                const int q = tid + kThreads * it, row = q >> 2, g = q & 3;
+                *reinterpret_cast<uint4*>(sA + row * kRowAs + g * 16) = ra[it];
+            }
+#pragma unroll
+            for (int it = 0; it < NM_; ++it) {
+                const int q = tid + kThreads * it;
+                if (q < BM * 2) reinterpret_cast<uint32_t*>(sM)[q] = rm[it];
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < NA_; ++it) {
+                const int q = tid + kThreads * it, row = q >> 3, g = q & 7;
+                *reinterpret_cast<uint4*>(sA + row * kRowB + g * 16) = ra[it];
+            }
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+
+    const int l32 = lane & 31, h = lane >> 5;
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) load_tile(kt + 1);
+        const uint8_t* sA = smem + (kt & 1) * S::kStage;
+        const uint8_t* sM = sA + S::kA;
+        const uint8_t* sB = sM + S::kMeta;
+        if constexpr (SPARSE) {
+            // One stage = 64 dense k.  Lane half h owns compressed values [16h, 16h+16) of
+            // its weight row (= dense k [32h, 32h+32)) and the matching 32 index bits; the
+            // first instruction consumes the low 16 index bits (ABID 0), the second the
+            // high 16 (ABID 1).  Each token lane supplies dense k {8h..8h+7, 32+8h..} to
+            // the first and {16+8h.., 48+8h..} to the second instruction.
+            bf16x8 af[TM][2];
+            int ai[TM];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int row = wm * WM + i * 32 + l32;
+                af[i][0] = *reinterpret_cast<const bf16x8*>(sA + row * kRowAs + h * 32);
+                af[i][1] = *reinterpret_cast<const bf16x8*>(sA + row * kRowAs + h * 32 + 16);
+                ai[i] = reinterpret_cast<const int*>(sM)[row * 2 + h];
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int row = wn * WN + j * 32 + l32;
+                const uint8_t* p = sB + row * kRowB + h * 16;
+                union { bf16x16 v; bf16x8 half[2]; } b0, b1;
+                b0.half[0] = *reinterpret_cast<const bf16x8*>(p);
+                b0.half[1] = *reinterpret_cast<const bf16x8*>(p + 64);
+                b1.half[0] = *reinterpret_cast<const bf16x8*>(p + 32);
+                b1.half[1] = *reinterpret_cast<const bf16x8*>(p + 96);
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af[i][0], b0.v, acc[i][j], ai[i], 0, 0);
+                    acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af[i][1], b1.v, acc[i][j], ai[i], 0, 1);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                bf16x8 af[TM];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    af[i] = *reinterpret_cast<const bf16x8*>(sA + (wm * WM + i * 32 + l32) * kRowB + c * 32 + h * 16);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const bf16x8 bf = *reinterpret_cast<const bf16x8*>(sB + (wn * WN + j * 32 + l32) * kRowB + c * 32 + h * 16);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf, acc[i][j], 0, 0, 0);
+                }
+            }
+        }
+        if (kt + 1 < nk) store_tile((kt + 1) & 1);
+        __syncthreads();
+    }
+
+    // Epilogue: accumulators -> bf16 tile [t][a] in LDS -> 16-byte row-contiguous stores.
+    uint8_t* sC = smem;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int t = wn * WN + j * 32 + l32;
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                const int a = wm * WM + i * 32 + 8 * qq + 4 * h;
+                uint2 v;
+                v.x = f32_to_bf16_rne(acc[i][j][4 * qq + 0]) | (f32_to_bf16_rne(acc[i][j][4 * qq + 1]) << 16);
+                v.y = f32_to_bf16_rne(acc[i][j][4 * qq + 2]) | (f32_to_bf16_rne(acc[i][j][4 * qq + 3]) << 16);
+                *reinterpret_cast<uint2*>(sC + t * S::kCRow + a * 2) = v;
+            }
+        }
+    __syncthreads();
+    constexpr int GPR = BM / 8;                          // 16-byte granules per output row
+    for (int q = tid; q < BN * GPR; q += kThreads) {
+        const int row = q / GPR, g = q % GPR;
+        const int64_t t = t0 + row, a = a0 + 8 * g;
+        if (t >= T || a >= Adim) continue;
+        const uint4 v = *reinterpret_cast<const uint4*>(sC + row * S::kCRow + g * 16);
+        uint16_t* dst = C + t * ldc + a;
+        if (vecC && a + 8 <= Adim) {
+            *reinterpret_cast<uint4*>(dst) = v;
+        } else {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            for (int e = 0; e < 8; ++e)
+                if (a + e < Adim) dst[e] = static_cast<uint16_t>(w[e >> 1] >> (16 * (e & 1)));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// fp32: 64 x 64 tile, 16 x 16 threads, 4 x 4 outputs per thread, plain FMA.
+// ---------------------------------------------------------------------------------
+template <bool SPARSE>
+__global__ void __launch_bounds__(kThreads)
+k_gemm_f32(const float* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int64_t K,
+           const float* __restrict__ Bm, int64_t T, int64_t ldb, float* __restrict__ C, int64_t ldc) {
+    constexpr int TS = 64, KS = 32;
+    __shared__ float sA[TS][KS + 1];
+    __shared__ float sB[TS][KS + 1];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int64_t a0 = static_cast<int64_t>(blockIdx.x) * TS, t0 = static_cast<int64_t>(blockIdx.y) * TS;
+    const int64_t wprA = ceil_div(K, 32);
+    float acc[4][4] = {};
+    for (int64_t k0 = 0; k0 < K; k0 += KS) {
+        for (int idx = threadIdx.x; idx < TS * KS; idx += kThreads) {
+            const int r = idx / KS, k = idx % KS;
+            const int64_t gk = k0 + k;
+            float va = 0.f, vb = 0.f;
+            if (gk < K) {
+                const int64_t a = a0 + r, t = t0 + r;
+                if (t < T) vb = Bm[t * ldb + gk];
+                if (a < Adim) {
+                    if constexpr (SPARSE) {
+                        const int64_t g = gk >> 2;
+                        const int pos = static_cast<int>(gk & 3);
+                        const uint32_t nib = (Ameta[a * wprA + (g >> 3)] >> (4 * (g & 7))) & 15u;
+                        const int p0 = nib & 3, p1 = nib >> 2;
+                        if (pos == p0) va = A[a * (K / 2) + 2 * g];
+                        else if (pos == p1) va = A[a * (K / 2) + 2 * g + 1];
+                    } else {
+                        va = A[a * K + gk];
+                    }
+                }
+            }
+            sA[r][k] = va;
+            sB[r][k] = vb;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int k = 0; k < KS; ++k) {
+            float av[4], bv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { av[u] = sA[tx * 4 + u][k]; bv[u] = sB[ty * 4 + u][k]; }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[u][v] = fmaf(bv[u], av[v], acc[u][v]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int64_t t = t0 + ty * 4 + u, a = a0 + tx * 4 + v;
+            if (t < T && a < Adim) C[t * ldc + a] = acc[u][v];
+        }
+}
+
+// out[t][r] = in[t][perm[r]]   (the column permutation of g(Y) in Eq. 10)
+template <typename raw>
+__global__ void __launch_bounds__(kThreads)
+k_gather_cols(const raw* __restrict__ in, int64_t T, int64_t ld, const int32_t* __restrict__ perm, int64_t I,
+              raw* __restrict__ out, bool vec) {
+    constexpr int E = 16 / sizeof(raw);
+    const int64_t chunks = ceil_div(I, E);
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (id >= T * chunks) return;
+    const int64_t t = id / chunks, r0 = (id - t * chunks) * E;
+    const raw* src = in + t * ld;
+    raw v[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) v[e] = (r0 + e < I) ? src[perm[r0 + e]] : static_cast<raw>(0);
+    raw* dst = out + t * I + r0;
+    if (vec && r0 + E <= I) {
+        uint4 pk;
+        if constexpr (sizeof(raw) == 2) {
+            pk.x = v[0] | (static_cast<uint32_t>(v[1]) << 16); pk.y = v[2] | (static_cast<uint32_t>(v[3]) << 16);
+            pk.z = v[4] | (static_cast<uint32_t>(v[5]) << 16); pk.w = v[6] | (static_cast<uint32_t>(v[7]) << 16);
+        } else {
+            pk.x = v[0]; pk.y = v[1]; pk.z = v[2]; pk.w = v[3];
+        }
+        *reinterpret_cast<uint4*>(dst) = pk;
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+            if (r0 + e < I) dst[e] = v[e];
+    }
+}
+
+template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N>
+int run_gemm_bf16(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
+                  int64_t ldb, void* C, int64_t ldc, hipStream_t s) {
+    using S = Smem<SPARSE, BM, BN>;
+    auto kern = k_gemm_bf16<SPARSE, BM, BN, WAVES_M, WAVES_N>;
+    if (S::kTotal > 48 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                S::kTotal) != hipSuccess) return BIMASK_ERR_HIP;
+    }
+    const int64_t lda = SPARSE ? K / 2 : K;
+    const bool vecA = aligned16(A) && (lda * 2) % 16 == 0;
+    const bool vecB = aligned16(Bm) && (ldb * 2) % 16 == 0;
+    const bool vecC = aligned16(C) && (ldc * 2) % 16 == 0;
+    const int tiles_a = static_cast<int>(ceil_div(Adim, BM));
+    const int64_t tiles_t = ceil_div(T, BN);
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(tiles_a * tiles_t)), dim3(kThreads), S::kTotal, s,
+                       static_cast<const uint16_t*>(A), meta, Adim, K, static_cast<const uint16_t*>(Bm), T, ldb,
+                       static_cast<uint16_t*>(C), ldc, tiles_a, vecA, vecB, vecC);
+    return check_launch();
+}
+
+}  // namespace
+
+int launch_gather_cols(const void* dY, int64_t T, int64_t ld, const int32_t* perm, int64_t I, int dtype,
+                       void* out, hipStream_t s) {
+    if (dtype == BIMASK_BF16) {
+        const int64_t total = T * ceil_div(I, 8);
+        const bool vec = aligned16(out) && (I * 2) % 16 == 0;
+        hipLaunchKernelGGL(k_gather_cols<uint16_t>, dim3(static_cast<unsigned>(ceil_div(total, kThreads))),
+                           dim3(kThreads), 0, s, static_cast<const uint16_t*>(dY), T, ld, perm, I,
+                           static_cast<uint16_t*>(out), vec);
+    } else {
+        const int64_t total = T * ceil_div(I, 4);
+        const bool vec = aligned16(out) && (I * 4) % 16 == 0;
+        hipLaunchKernelGGL(k_gather_cols<uint32_t>, dim3(static_cast<unsigned>(ceil_div(total, kThreads))),
+                           dim3(kThreads), 0, s, static_cast<const uint32_t*>(dY), T, ld, perm, I,
+                           static_cast<uint32_t*>(out), vec);
+    }
+    return check_launch();
+}
+
+int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int64_t K, bool sparse24,
+                const void* Bm, int64_t T, int64_t ldb, void* C, int64_t ldc, int dtype, hipStream_t s) {
+    if (dtype == BIMASK_F32) {
+        dim3 grid(static_cast<unsigned>(ceil_div(Adim, 64)), static_cast<unsigned>(ceil_div(T, 64)));
+        if (sparse24)
+            hipLaunchKernelGGL(k_gemm_f32<true>, grid, dim3(kThreads), 0, s, static_cast<const float*>(A_values),
+                               A_index, Adim, K, static_cast<const float*>(Bm), T, ldb, static_cast<float*>(C), ldc);
+        else
+            hipLaunchKernelGGL(k_gemm_f32<false>, grid, dim3(kThreads), 0, s, static_cast<const float*>(A_values),
+                               A_index, Adim, K, static_cast<const float*>(Bm), T, ldb, static_cast<float*>(C), ldc);
+        return check_launch();
+    }
+    if (sparse24) return run_gemm_bf16<true, 128, 128, 2, 2>(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, s);
+    return run_gemm_bf16<false, 128, 128, 2, 2>(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, s);
+}
+
+}  // namespace bimask

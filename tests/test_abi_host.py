@@ -1,0 +1,101 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2302_06058_amd as bm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x1000)      # never dereferenced: every call below fails validation first
+
+
+def test_header_symbols_are_exported():
+    text = open(os.path.join(ROOT, "include", "bimask.h")).read()
+    declared = set(re.findall(r"BIMASK_API[^;(]*?\b(bimask_\w+)\s*\(", text))
+    assert declared == set(bm.EXPORTS)
+    l = bm.lib()
+    for name in declared:
+        assert hasattr(l, name), name
+
+
+def test_status_strings():
+    assert bm.status_string(0) == "ok"
+    seen = {bm.status_string(s) for s in range(0, 9)}
+    assert len(seen) == 9 and "unknown status" not in seen
+    assert bm.status_string(99) == "unknown status"
+
+
+def test_workspace_bytes():
+    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 256, 2304, 12544, 0, bm.BF16, 2, 4) == 12544 * 256 * 2
+    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 64, 128, 32, 0, bm.F32, 2, 4) == 32 * 64 * 4
+    assert bm.workspace_bytes(bm.WS_GEMM_FWD, 256, 2304, 12544, 0, bm.BF16, 2, 4) == 0
+    ws = bm.workspace_bytes(bm.WS_PERM_SEARCH, 256, 2304, 0, 100, bm.BF16, 2, 4)
+    assert ws > 0 and ws % (100 * 4) == 0
+    assert bm.workspace_bytes(bm.WS_PERM_SEARCH, 1 << 20, 64, 0, 100, bm.BF16, 2, 4) == 0   # too many rows for LDS
+
+
+@pytest.mark.parametrize("call,args,want", [
+    # forward mask
+    ("bimask_forward_mask", (None, 64, 128, 128, bm.BF16, 2, 4, FAKE, None), 1),
+    ("bimask_forward_mask", (FAKE, 64, 128, 128, bm.BF16, 2, 4, None, None), 1),
+    ("bimask_forward_mask", (FAKE, 64, 130, 130, bm.BF16, 2, 4, FAKE, None), 2),      # J % M
+    ("bimask_forward_mask", (FAKE, 62, 128, 128, bm.BF16, 2, 4, FAKE, None), 2),      # I % M
+    ("bimask_forward_mask", (FAKE, 64, 128, 100, bm.BF16, 2, 4, FAKE, None), 2),      # ld < J
+    ("bimask_forward_mask", (FAKE, 0, 128, 128, bm.BF16, 2, 4, FAKE, None), 2),
+    ("bimask_forward_mask", (FAKE, 64, 128, 128, bm.BF16, 4, 4, FAKE, None), 3),      # N == M
+    ("bimask_forward_mask", (FAKE, 64, 128, 128, bm.BF16, 0, 4, FAKE, None), 3),
+    ("bimask_forward_mask", (FAKE, 60, 120, 120, bm.BF16, 2, 5, FAKE, None), 3),      # M not 4/8/16
+    ("bimask_forward_mask", (FAKE, 64, 128, 128, 7, 2, 4, FAKE, None), 4),
+    ("bimask_forward_mask", (ctypes.c_void_p(0x1001), 64, 128, 128, bm.BF16, 2, 4, FAKE, None), 7),
+    # fused forward
+    ("bimask_forward_mask_compress", (FAKE, 64, 128, 128, bm.BF16, 2, 4, FAKE, None, FAKE, None), 1),
+    ("bimask_forward_mask_compress", (FAKE, 64, 128, 128, bm.BF16, 2, 4, FAKE, FAKE, None, None), 1),
+    # perm search
+    ("bimask_perm_search", (FAKE, 64, 128, 2, 4, None, 4, FAKE, FAKE, None, FAKE, 1 << 20, None), 1),
+    ("bimask_perm_search", (FAKE, 64, 128, 2, 4, FAKE, 0, FAKE, FAKE, None, FAKE, 1 << 20, None), 2),
+    ("bimask_perm_search", (FAKE, 64, 128, 2, 4, FAKE, 4, FAKE, FAKE, None, None, 0, None), 6),
+    ("bimask_perm_search", (FAKE, 64, 128, 2, 4, FAKE, 4, FAKE, FAKE, None, FAKE, 8, None), 6),
+    ("bimask_perm_search", (FAKE, 64, 128, 2, 4, ctypes.c_void_p(0x1004), 4, FAKE, FAKE, None, FAKE, 1 << 20, None), 7),
+    ("bimask_perm_search", (FAKE, 1 << 20, 64, 2, 4, FAKE, 4, FAKE, FAKE, None, FAKE, 1 << 20, None), 5),
+    # backward mask
+    ("bimask_backward_mask", (FAKE, 64, 128, 128, bm.F32, 2, 4, None, None, FAKE, None), 1),
+    ("bimask_backward_mask", (FAKE, 64, 128, 128, bm.F32, 2, 4, FAKE, None, None, None), 1),
+    ("bimask_backward_mask_compress", (FAKE, 64, 128, 128, bm.F32, 2, 4, FAKE, None, FAKE, None, FAKE, None), 1),
+    # compress
+    ("bimask_compress_nm", (FAKE, 64, 128, 128, bm.BF16, 2, 4, None, None, 0, FAKE, FAKE, None), 1),
+    ("bimask_compress_nm", (FAKE, 64, 128, 128, bm.BF16, 2, 4, FAKE, None, 2, FAKE, FAKE, None), 2),
+    ("bimask_compress_nm", (FAKE, 64, 128, 128, bm.BF16, 2, 4, FAKE, FAKE, 0, FAKE, FAKE, None), 5),
+    ("bimask_compress_nm", (FAKE, 64, 128, 128, bm.BF16, 2, 4, FAKE, None, 0, FAKE, None, None), 1),
+    # GEMMs
+    ("bimask_sparse_gemm_fwd", (None, 32, 128, FAKE, FAKE, 64, 128, bm.BF16, 2, 4, FAKE, 64, None, 0, None), 1),
+    ("bimask_sparse_gemm_fwd", (FAKE, 32, 100, FAKE, FAKE, 64, 128, bm.BF16, 2, 4, FAKE, 64, None, 0, None), 2),
+    ("bimask_sparse_gemm_fwd", (FAKE, 32, 128, FAKE, FAKE, 64, 128, bm.BF16, 2, 4, FAKE, 60, None, 0, None), 2),
+    ("bimask_sparse_gemm_fwd", (FAKE, 32, 128, FAKE, None, 64, 128, bm.BF16, 2, 4, FAKE, 64, None, 0, None), 1),
+    ("bimask_sparse_gemm_fwd", (FAKE, 32, 129, FAKE, FAKE, 64, 128, bm.BF16, 2, 4, FAKE, 64, None, 0, None), 7),
+    ("bimask_sparse_gemm_fwd", (FAKE, 0, 128, FAKE, FAKE, 64, 128, bm.BF16, 2, 4, FAKE, 64, None, 0, None), 2),
+    ("bimask_sparse_gemm_bwd", (FAKE, 32, 64, FAKE, FAKE, FAKE, 64, 128, bm.BF16, 2, 4, FAKE, 128, None, 0, None), 6),
+    ("bimask_sparse_gemm_bwd", (FAKE, 32, 64, FAKE, FAKE, FAKE, 64, 128, bm.BF16, 2, 4, FAKE, 128, FAKE, 16, None), 6),
+    ("bimask_sparse_gemm_bwd", (FAKE, 32, 60, None, FAKE, FAKE, 64, 128, bm.BF16, 2, 4, FAKE, 128, None, 0, None), 2),
+])
+def test_argument_errors_are_reported_before_any_launch(call, args, want):
+    assert getattr(bm.lib(), call)(*args) == want
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(bm, "_lib", None)
+    monkeypatch.setattr(bm, "LIB_PATH", "/nonexistent/libbimask.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        bm.lib()
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2302_06058_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(import|from)\s+oracle\b", text, flags=re.M), f
+                assert "oracle/" not in text and "liboracle" not in text, f

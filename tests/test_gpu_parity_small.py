@@ -1,0 +1,199 @@
+"""GPU parity, small sizes: every entry point of the C-ABI library against the CPU
+oracle on the same seeded inputs.  Shapes span several tiles and ragged tails.
+Masks, scores, permutation choice and compressed operands are compared bit for bit;
+GEMM outputs within 2e-2 (bf16 in, fp32 accumulate) / 1e-5 (fp32) of the float64
+oracle in max|err| / max|ref|."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2302_06058_amd as bm
+from paper_2302_06058_amd import synth
+from helpers import to_dev, i32_dev, words, from_dev_f64, raw_bits, f64_to_raw, rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = {synth.BF16: 2e-2, synth.F32: 1e-5}
+NMS = [(2, 4), (1, 4), (4, 8), (2, 8), (1, 16)]
+
+
+def make_w(I, J, dtype, seed, kind="normal"):
+    r = np.random.default_rng(seed)
+    if kind == "normal":
+        w = r.standard_normal((I, J), dtype=np.float32)
+    elif kind == "integers":                      # ties everywhere
+        w = r.integers(-3, 4, size=(I, J)).astype(np.float32)
+    elif kind == "special":
+        w = r.standard_normal((I, J), dtype=np.float32)
+        w[0] = 0.0
+        w[1 % I] = 1.0
+        w[2 % I] = -w[2 % I]
+        w[3 % I, ::2] = -0.0
+        w[3 % I, 1::2] = 0.0
+        w[:, :4] = np.array([0.5, -0.5, 0.5, -0.5], dtype=np.float32)
+    return synth.store(w, dtype)
+
+
+def perms_of(I, K, seed, identity_first=False):
+    r = np.random.default_rng(seed)
+    p = np.stack([r.permutation(I) for _ in range(K)]).astype(np.int32)
+    if identity_first:
+        p[0] = np.arange(I)
+    return p
+
+
+def check_layer(I, J, N, M, dtype, K, seed, kind="normal", T=0):
+    """Runs every call on one synthetic layer and compares with the oracle."""
+    Wh = make_w(I, J, dtype, seed, kind)
+    W64 = synth.to_f64(Wh, dtype)
+    perms = perms_of(I, K, seed + 1, identity_first=(seed % 2 == 0))
+    W = to_dev(Wh, dtype)
+    s24 = (N, M) == (2, 4)
+
+    # ---- forward mask (+ fused compress, + stand-alone compress)
+    B_o = oracle.forward_mask(W64, N, M)
+    Bw_o = oracle.pack_bits(B_o)
+    B = bm.bimask_forward_mask(W, N, M)
+    assert (words(B) == Bw_o).all(), "forward mask"
+    B2, vals, index = bm.bimask_forward_mask_compress(W, N, M)
+    assert (words(B2) == Bw_o).all(), "fused forward mask"
+    vals_s, index_s = bm.bimask_compress_nm(W, N, M, B, None, 0)
+    if s24:
+        val_o, idx_o = oracle.compress_fwd(W64, B_o, N, M)
+        want_v, want_i = f64_to_raw(val_o, dtype), oracle.pack_index(idx_o, M)
+        assert (words(index) == want_i).all() and (words(index_s) == want_i).all(), "forward index"
+    else:
+        want_v = f64_to_raw(W64 * B_o, dtype)
+    # -0.0 weights: a kept -0 stays -0, a dropped slot is +0 -> compare bit patterns of the oracle's
+    # exact values, treating +-0 alike
+    def same_bits(a, b):
+        za = (a & (0x7FFF if dtype == synth.BF16 else 0x7FFFFFFF)) == 0
+        zb = (b & (0x7FFF if dtype == synth.BF16 else 0x7FFFFFFF)) == 0
+        return ((a == b) | (za & zb)).all()
+    assert same_bits(raw_bits(vals, dtype), want_v), "fused forward values"
+    assert same_bits(raw_bits(vals_s, dtype), want_v), "stand-alone forward values"
+
+    # ---- permutation search
+    sc_o = oracle.perm_scores(B_o, perms, N, M)
+    best_o = oracle.argmax_first(sc_o)
+    Pd = i32_dev(perms)
+    scores, best, best_perm = bm.bimask_perm_search(B, I, J, N, M, Pd)
+    assert (scores.cpu().numpy().astype(np.int64) == sc_o).all(), "scores"
+    assert int(best.item()) == best_o, "best"
+    assert (best_perm.cpu().numpy() == perms[best_o]).all(), "best_perm"
+
+    # ---- backward mask (+ fused / stand-alone transposed compress), with P and with identity
+    for P_h, P_d in ((perms[best_o], best_perm), (None, None)):
+        Bbar_o, _ = oracle.backward_mask(W64, B_o, P_h, N, M)
+        Bbw_o = oracle.pack_bits(Bbar_o)
+        Bbar = bm.bimask_backward_mask(W, N, M, B, P_d)
+        assert (words(Bbar) == Bbw_o).all(), "backward mask"
+        Bbar2, vb, ib = bm.bimask_backward_mask_compress(W, N, M, B, P_d)
+        assert (words(Bbar2) == Bbw_o).all(), "fused backward mask"
+        vb_s, ib_s = bm.bimask_compress_nm(W, N, M, Bbar, P_d, 1)
+        if s24:
+            valb_o, idxb_o = oracle.compress_bwd(W64, B_o, P_h, N, M)
+            want_vb, want_ib = f64_to_raw(valb_o, dtype), oracle.pack_index(idxb_o, M)
+            assert (words(ib) == want_ib).all() and (words(ib_s) == want_ib).all(), "backward index"
+        else:
+            Wp = W64 if P_h is None else W64[P_h, :]
+            want_vb = f64_to_raw(np.ascontiguousarray((Wp * Bbar_o).T), dtype)
+        assert same_bits(raw_bits(vb, dtype), want_vb), "fused backward values"
+        assert same_bits(raw_bits(vb_s, dtype), want_vb), "stand-alone backward values"
+
+        # ---- GEMMs
+        if T > 0:
+            r = np.random.default_rng(seed + 7)
+            Xh = synth.store(r.standard_normal((T, J), dtype=np.float32), dtype)
+            dYh = synth.store(r.standard_normal((T, I), dtype=np.float32), dtype)
+            X, dY = to_dev(Xh, dtype), to_dev(dYh, dtype)
+            Y = bm.bimask_sparse_gemm_fwd(X, vals, index, I, J, N, M)
+            Y_o = oracle.gemm_fwd(synth.to_f64(Xh, dtype), W64, B_o)
+            assert rel_err(from_dev_f64(Y, dtype), Y_o) <= TOL[dtype], "forward GEMM"
+            dX = bm.bimask_sparse_gemm_bwd(dY, P_d, vb, ib, I, J, N, M)
+            dX_o = oracle.gemm_bwd(synth.to_f64(dYh, dtype), W64, Bbar_o, P_h)
+            assert rel_err(from_dev_f64(dX, dtype), dX_o) <= TOL[dtype], "backward GEMM"
+
+
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F32])
+@pytest.mark.parametrize("N,M", NMS)
+def test_small_layers_all_calls(dtype, N, M):
+    # several tiles + ragged tails in every dimension (I, J multiples of M only)
+    check_layer(I=9 * 16, J=13 * 16 + M, N=N, M=M, dtype=dtype, K=7, seed=100 + M + N, T=77)
+    check_layer(I=272, J=144, N=N, M=M, dtype=dtype, K=11, seed=200 + M + N, T=130)
+
+
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F32])
+@pytest.mark.parametrize("kind", ["integers", "special"])
+def test_adversarial_values(dtype, kind):
+    for (N, M) in [(2, 4), (4, 8)]:
+        check_layer(I=64, J=160, N=N, M=M, dtype=dtype, K=5, seed=300 + N, kind=kind, T=33)
+
+
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F32])
+def test_degenerate_shapes(dtype):
+    check_layer(I=4, J=4, N=2, M=4, dtype=dtype, K=1, seed=401, T=1)          # one group, one block
+    check_layer(I=4, J=148, N=2, M=4, dtype=dtype, K=3, seed=402, T=5)        # single row block, ragged J
+    check_layer(I=1000, J=64, N=2, M=4, dtype=dtype, K=9, seed=403, T=64)     # ragged I (fc-like)
+    check_layer(I=16, J=16, N=1, M=16, dtype=dtype, K=2, seed=404, T=3)
+
+
+def test_duplicate_candidates_pick_the_first():
+    I, J, N, M = 64, 128, 2, 4
+    Wh = make_w(I, J, synth.BF16, 501)
+    B_o = oracle.forward_mask(synth.to_f64(Wh, synth.BF16), N, M)
+    base = perms_of(I, 3, 502)
+    perms = np.concatenate([base, base, base[::-1]])
+    B = bm.bimask_forward_mask(to_dev(Wh, synth.BF16), N, M)
+    scores, best, best_perm = bm.bimask_perm_search(B, I, J, N, M, i32_dev(perms))
+    sc_o = oracle.perm_scores(B_o, perms, N, M)
+    assert (scores.cpu().numpy() == sc_o).all()
+    assert int(best.item()) == oracle.argmax_first(sc_o) < 3
+
+
+def test_identical_rows_closed_form_score():
+    # every row has the same pattern -> each column is all ones or all zeros ->
+    # score = (I/M) * J * (1 - N/M) for every permutation
+    I, J, N, M = 128, 256, 2, 4
+    row = np.random.default_rng(601).standard_normal((1, J), dtype=np.float32)
+    Wh = synth.store(np.repeat(row, I, axis=0), synth.BF16)
+    B = bm.bimask_forward_mask(to_dev(Wh, synth.BF16), N, M)
+    scores, _, _ = bm.bimask_perm_search(B, I, J, N, M, i32_dev(perms_of(I, 6, 602)))
+    assert (scores.cpu().numpy() == (I // M) * J // 2).all()
+
+
+def test_config1_whole_step_fp32():
+    layer = synth.get_config(1)[0]
+    d = synth.gen_layer(layer)
+    ref = oracle.bimask_step(synth.to_f64(d.W, layer.dtype), synth.to_f64(d.X, layer.dtype),
+                             synth.to_f64(d.dY, layer.dtype), d.perms, layer.N, layer.M)
+    W, X, dY = to_dev(d.W, layer.dtype), to_dev(d.X, layer.dtype), to_dev(d.dY, layer.dtype)
+    B, vals, index = bm.bimask_forward_mask_compress(W, 2, 4)
+    Y = bm.bimask_sparse_gemm_fwd(X, vals, index, layer.I, layer.J, 2, 4)
+    scores, best, P = bm.bimask_perm_search(B, layer.I, layer.J, 2, 4, i32_dev(d.perms))
+    Bbar, vb, ib = bm.bimask_backward_mask_compress(W, 2, 4, B, P)
+    dX = bm.bimask_sparse_gemm_bwd(dY, P, vb, ib, layer.I, layer.J, 2, 4)
+    assert (words(B) == oracle.pack_bits(ref["B"])).all()
+    assert (scores.cpu().numpy() == ref["scores"]).all() and int(best.item()) == ref["best"]
+    assert (words(Bbar) == oracle.pack_bits(ref["Bbar"])).all()
+    assert rel_err(from_dev_f64(Y, layer.dtype), ref["Y"]) <= 1e-5
+    assert rel_err(from_dev_f64(dX, layer.dtype), ref["dX"]) <= 1e-5
+    # loops-based oracle GEMM as well (independent of the library matmul)
+    Yl = oracle.gemm_fwd_loops(synth.to_f64(d.X, layer.dtype), synth.to_f64(d.W, layer.dtype), ref["B"])
+    assert rel_err(from_dev_f64(Y, layer.dtype), Yl) <= 1e-5
+
+
+def test_results_are_reproducible_bit_for_bit():
+    I, J, N, M, K = 256, 512, 2, 4, 16
+    Wh = make_w(I, J, synth.BF16, 701)
+    W = to_dev(Wh, synth.BF16)
+    Pd = i32_dev(perms_of(I, K, 702))
+    outs = []
+    for _ in range(2):
+        B, v, ix = bm.bimask_forward_mask_compress(W, N, M)
+        s, b, P = bm.bimask_perm_search(B, I, J, N, M, Pd)
+        Bb, vb, ib = bm.bimask_backward_mask_compress(W, N, M, B, P)
+        outs.append([words(B), raw_bits(v, synth.BF16), words(ix), s.cpu().numpy(), b.cpu().numpy(),
+                     words(Bb), raw_bits(vb, synth.BF16), words(ib)])
+    for a, b in zip(*outs):
+        assert (a == b).all()

@@ -429,3 +429,28 @@ def test_whole_step_is_consistent():
     out = oracle.bimask_step(W, X, dY, perms, N, M)
     assert out["best"] == int(np.argmax(brute_scores(out["B"], perms, N, M)))
     assert (out["P"] == perms[out["best"]]).all()
+
+
+def test_compress_completes_short_groups_with_lowest_zero_positions():
+    # hand-worked: mask 0010 -> slots {0, 2}; mask 0000 -> {0, 1}; mask 1000 -> {0, 1}; 0001 -> {0, 3}
+    W = np.array([[5.0, 6.0, 7.0, 8.0] * 4])
+    B = np.array([[0, 0, 1, 0, 0, 0, 0, 0, 1, 0, 0, 0, 0, 0, 0, 1]], dtype=np.uint8)
+    val, idx = oracle.compress_fwd(W, B, 2, 4)
+    assert idx.tolist() == [[0, 2, 0, 1, 0, 1, 0, 3]]
+    assert val.tolist() == [[0.0, 7.0, 0.0, 0.0, 5.0, 0.0, 0.0, 8.0]]
+
+
+@pytest.mark.parametrize("N,M", NMS)
+def test_backward_compress_equals_generic_rule_on_bbar(N, M):
+    # the slots of the transposed backward operand (selection before the AND) are exactly
+    # the ones of Bbar completed with the lowest zero positions
+    r = rng_of(44)
+    I, J = 8 * M, 3 * M
+    W = np.round(r.standard_normal((I, J)) * 2) / 2
+    W[r.random((I, J)) < 0.2] = 0.0
+    B = oracle.forward_mask(W, N, M)
+    P = r.permutation(I).astype(np.int32)
+    Bbar, _ = oracle.backward_mask(W, B, P, N, M)
+    valb, idxb = oracle.compress_bwd(W, B, P, N, M)
+    val2, idx2 = oracle.compress_fwd(np.ascontiguousarray(W[P, :].T), np.ascontiguousarray(Bbar.T), N, M)
+    assert (idxb == idx2).all() and (valb == val2).all()
