@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Benchmark of the Bi-Mask per-layer hot path on one MI355X.
+
+One "step" is one pass of the whole path over one synthetic layer (Alg. 1 of the paper,
+search included): forward mask + compression, forward sparse GEMM, K-candidate
+permutation search, backward mask + transposed compression, backward sparse GEMM.
+Default workload: the ResNet-50 layer3 3x3 convolution as an im2col GEMM
+(W 256x2304, 12544 tokens, bf16, 2:4, K = 100).
+
+Prints ONE JSON line.  All inputs are resident in HBM before the timed region; the
+activation / gradient / output buffers rotate over several copies so that successive
+steps do not find them in the 256 MB last-level cache.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X published dense bf16 matrix peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="workload configuration (2 = headline)")
+    ap.add_argument("--layer", type=int, default=0, help="layer index inside the configuration")
+    ap.add_argument("--copies", type=int, default=0, help="rotating buffer copies (0 = enough for 1 GiB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown-reps", type=int, default=30)
+    return ap.parse_args()
+
+
+class LayerRun:
+    """Device buffers of one layer and the calls of one step (no allocation per step)."""
+
+    def __init__(self, layer, data, copies):
+        import torch
+        import paper_2302_06058_amd as bm
+        from helpers import to_dev, i32_dev
+        self.bm, self.layer, self.torch = bm, layer, torch
+        L = layer
+        self.dt = bm.BF16 if L.dtype == "bf16" else bm.F32
+        tdt = torch.bfloat16 if L.dtype == "bf16" else torch.float32
+        self.W = to_dev(data.W, L.dtype)
+        self.perms = i32_dev(data.perms)
+        X0, dY0 = to_dev(data.X, L.dtype), to_dev(data.dY, L.dtype)
+        self.X = [X0] + [X0.clone() for _ in range(copies - 1)]
+        self.dY = [dY0] + [dY0.clone() for _ in range(copies - 1)]
+        dev = self.W.device
+        self.Y = [torch.empty((L.T, L.I), dtype=tdt, device=dev) for _ in range(copies)]
+        self.dX = [torch.empty((L.T, L.J), dtype=tdt, device=dev) for _ in range(copies)]
+        s24 = (L.N, L.M) == (2, 4)
+        wj, wi = bm.mask_words(L.J), bm.mask_words(L.I)
+        self.B = torch.empty((L.I, wj), dtype=torch.int32, device=dev)
+        self.Bbar = torch.empty((L.I, wj), dtype=torch.int32, device=dev)
+        self.vf = torch.empty((L.I, L.J // 2 if s24 else L.J), dtype=tdt, device=dev)
+        self.xf = torch.empty((L.I, wj), dtype=torch.int32, device=dev) if s24 else None
+        self.vb = torch.empty((L.J, L.I // 2 if s24 else L.I), dtype=tdt, device=dev)
+        self.xb = torch.empty((L.J, wi), dtype=torch.int32, device=dev) if s24 else None
+        self.scores = torch.empty((L.K,), dtype=torch.int32, device=dev)
+        self.best = torch.empty((1,), dtype=torch.int32, device=dev)
+        self.P = torch.empty((L.I,), dtype=torch.int32, device=dev)
+        self.ws_perm = torch.empty((max(16, bm.workspace_bytes(bm.WS_PERM_SEARCH, L.I, L.J, 0, L.K, self.dt, L.N, L.M)),),
+                                   dtype=torch.uint8, device=dev)
+        self.ws_bwd = torch.empty((max(16, bm.workspace_bytes(bm.WS_GEMM_BWD, L.I, L.J, L.T, 0, self.dt, L.N, L.M)),),
+                                  dtype=torch.uint8, device=dev)
+        self.copies = copies
+        self.stages = [
+            ("forward_mask_compress", self.s_fwd_mask),
+            ("sparse_gemm_fwd", self.s_gemm_fwd),
+            ("perm_search", self.s_perm),
+            ("backward_mask_compress", self.s_bwd_mask),
+            ("sparse_gemm_bwd", self.s_gemm_bwd),
+        ]
+
+    def s_fwd_mask(self, r):
+        L = self.layer
+        self.bm.bimask_forward_mask_compress(self.W, L.N, L.M, self.B, self.vf, self.xf)
+
+    def s_gemm_fwd(self, r):
+        L = self.layer
+        self.bm.bimask_sparse_gemm_fwd(self.X[r], self.vf, self.xf, L.I, L.J, L.N, L.M, self.Y[r])
+
+    def s_perm(self, r):
+        L = self.layer
+        self.bm.bimask_perm_search(self.B, L.I, L.J, L.N, L.M, self.perms, self.scores, self.best, self.P, self.ws_perm)
+
+    def s_bwd_mask(self, r):
+        L = self.layer
+        self.bm.bimask_backward_mask_compress(self.W, L.N, L.M, self.B, self.P, self.Bbar, self.vb, self.xb)
+
+    def s_gemm_bwd(self, r):
+        L = self.layer
+        self.bm.bimask_sparse_gemm_bwd(self.dY[r], self.P, self.vb, self.xb, L.I, L.J, L.N, L.M, self.dX[r], self.ws_bwd)
+
+    def step(self, i):
+        r = i % self.copies
+        for _, fn in self.stages:
+            fn(r)
+
+
+def algorithmic(layer):
+    """Algorithmic bytes / flops per call of each stage (what the method itself must move)."""
+    L = layer
+    e = 2 if L.dtype == "bf16" else 4
+    s24 = (L.N, L.M) == (2, 4)
+    wbytes = L.I * L.J * ((e * L.N / L.M + 1 / 8) if s24 else e)       # compressed (or dense masked) operand
+    mask = L.I * L.J / 8
+    return {
+        "forward_mask_compress": {"bytes": L.I * L.J * e + mask + wbytes, "flops": 0},
+        "sparse_gemm_fwd": {"bytes": e * L.T * L.J + e * L.T * L.I + wbytes, "flops": 2 * L.T * L.I * L.J},
+        "perm_search": {"bytes": mask + 4 * L.K * L.I + 4 * L.K, "flops": 0},
+        "backward_mask_compress": {"bytes": L.I * L.J * e + mask + mask + wbytes, "flops": 0},
+        "sparse_gemm_bwd": {"bytes": e * L.T * L.I + e * L.T * L.J + wbytes, "flops": 2 * L.T * L.I * L.J},
+    }
+
+
+def cpu_baseline(layer, data):
+    """The oracle as it stands, timed once on this machine's host cores for one full step."""
+    import numpy as np
+    import oracle
+    from paper_2302_06058_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    f64 = lambda a: synth.to_f64(a, layer.dtype)
+    W, X, dY = f64(data.W), f64(data.X), f64(data.dY)
+    t0 = time.perf_counter()
+    oracle.bimask_step(W, X, dY, data.perms, layer.N, layer.M)
+    ms = (time.perf_counter() - t0) * 1e3
+    return {"value": round(ms, 1), "unit": "ms", "cores": int(threads), "kind": "oracle",
+            "sample": "one full step of the same layer (masks, K-candidate search and both float64 GEMMs); "
+                      "the C loops run on 1 thread, the float64 matmuls on `cores` BLAS threads"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures the single-GPU hot path only: this build has no multi-GPU path "
+              "(run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2302_06058_amd as bm
+    from paper_2302_06058_amd import synth
+    bm.lib()                                   # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    layer = synth.get_config(args.config)[args.layer]
+    data = synth.gen_layer(layer)
+    e = 2 if layer.dtype == "bf16" else 4
+    per_copy = e * layer.T * (layer.I + layer.J) * 2
+    copies = args.copies or max(2, min(16, -(-(1 << 30) // per_copy)))
+    run = LayerRun(layer, data, copies)
+    alg = algorithmic(layer)
+
+    # -- untimed warm-up
+    for i in range(args.warmup):
+        run.step(i)
+    torch.cuda.synchronize()
+
+    # -- per-stage breakdown (HIP events on the launch stream), outside the timed region
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    stage_us = {}
+    for name, fn in run.stages:
+        pairs = []
+        for i in range(args.breakdown_reps):
+            a, b = ev(), ev()
+            a.record(); fn(i % copies); b.record()
+            pairs.append((a, b))
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)
+        stage_us[name] = {"avg": sum(ts) / len(ts), "min": ts[0], "median": ts[len(ts) // 2]}
+    dominant = max(stage_us, key=lambda k: stage_us[k]["avg"])
+
+    # -- timed region: exactly `steps` steps, events only around the dominant stage
+    dom_pairs = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        r = i % copies
+        for name, fn in run.stages:
+            if name == dominant:
+                a, b = ev(), ev()
+                a.record(); fn(r); b.record()
+                dom_pairs.append((a, b))
+            else:
+                fn(r)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    dom_us = sum(a.elapsed_time(b) for a, b in dom_pairs) * 1e3 / len(dom_pairs)
+
+    dom_bytes, dom_flops = alg[dominant]["bytes"], alg[dominant]["flops"]
+    gbs = dom_bytes / (dom_us * 1e-6) / 1e9
+    tfl = dom_flops / (dom_us * 1e-6) / 1e12
+    t_hbm, t_mfma = dom_bytes / (HBM_PEAK_GBS * 1e9), dom_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if t_hbm >= t_mfma:
+        roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(gbs / HBM_PEAK_GBS, 4)}
+    else:
+        roof = {"bound": "mfma", "achieved": round(tfl, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(tfl / MFMA_BF16_PEAK_TFLOPS, 4)}
+    roof.update({"traffic": None, "kernel": dominant, "avg_us": round(dom_us, 2),
+                 "algorithmic_bytes": int(dom_bytes), "dense_equiv_tflops": round(tfl, 1)})
+
+    out = {
+        "metric": "Bi-Mask per-layer step time (mask+perm+fwd/bwd GEMM)",
+        "value": round(ms_per_step, 5), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": layer.dtype, "data": "synthetic",
+        "config": {"workload": f"config{args.config}:{layer.name} W {layer.I}x{layer.J}, T={layer.T}, "
+                               f"{layer.N}:{layer.M}, K={layer.K}, {layer.dtype}",
+                   "rotating_copies": copies},
+        "roofline": roof,
+        "stages_us": {k: {kk: round(vv, 2) for kk, vv in v.items()} for k, v in stage_us.items()},
+        "stages_sum_us": round(sum(v["avg"] for v in stage_us.values()), 2),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layer, data)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

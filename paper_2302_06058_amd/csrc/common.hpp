@@ -93,4 +93,7 @@ int launch_gather_cols(const void* dY, int64_t T, int64_t ld, const int32_t* per
 int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int64_t K, bool sparse24,
                 const void* Bm, int64_t T, int64_t ldb, void* C, int64_t ldc, int dtype, hipStream_t s);
 
+int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
+                     int64_t ldb, void* C, int64_t ldc, int variant, hipStream_t s);
+
 }  // namespace bimask

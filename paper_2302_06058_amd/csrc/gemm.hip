@@ -11,6 +11,7 @@
 // bf16, other: v_mfma_f32_32x32x16_bf16 on the dense masked weights
 // fp32       : plain fp32 FMA kernel (small problems only)
 #include "common.hpp"
+#include <cstdlib>
 
 namespace bimask {
 namespace {
@@ -18,6 +19,7 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(__bf16)))) __bf16 bf16x16;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // native 16-byte register vector
 
 constexpr int BK = 64;                // dense k per pipeline stage
 constexpr int kRowB = 144;            // LDS bytes per 64-k row of a dense operand (128 + 16 pad)
@@ -30,16 +32,18 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
 }
 
 // 8 consecutive bf16 of a row starting at element k (zero beyond kend).
-__device__ __forceinline__ uint4 load_granule(const uint16_t* row, int64_t k, int64_t kend, bool vec) {
+__device__ __forceinline__ u32x4 load_granule(const uint16_t* row, int64_t k, int64_t kend, bool vec) {
     if (k + 8 <= kend) {
-        if (vec) return *reinterpret_cast<const uint4*>(row + k);
+        if (vec) return *reinterpret_cast<const u32x4*>(row + k);
         const uint32_t* p = reinterpret_cast<const uint32_t*>(row + k);
-        return make_uint4(p[0], p[1], p[2], p[3]);
+        u32x4 r = {p[0], p[1], p[2], p[3]};
+        return r;
     }
-    uint32_t w[4] = {0, 0, 0, 0};
+    u32x4 r = {0u, 0u, 0u, 0u};
+#pragma unroll
     for (int e = 0; e < 8; ++e)
-        if (k + e < kend) w[e >> 1] |= static_cast<uint32_t>(row[k + e]) << (16 * (e & 1));
-    return make_uint4(w[0], w[1], w[2], w[3]);
+        if (k + e < kend) r[e >> 1] |= static_cast<uint32_t>(row[k + e]) << (16 * (e & 1));
+    return r;
 }
 
 template <bool SPARSE, int BM, int BN>
@@ -54,7 +58,9 @@ struct Smem {
 };
 
 // Workgroup tile BM (weight rows a) x BN (tokens t); WAVES_M x WAVES_N wavefronts.
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N>
+// FAST: K is a multiple of BK and every row of A, Bm starts 16-byte aligned, so all tile
+// loads are unconditional 16-byte loads (rows beyond the edge are clamped, never skipped).
+template <bool SPARSE, bool FAST, int BM, int BN, int WAVES_M, int WAVES_N>
 __global__ void __launch_bounds__(kThreads)
 k_gemm_bf16(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int64_t K,
             const uint16_t* __restrict__ Bm, int64_t T, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
@@ -77,7 +83,7 @@ k_gemm_bf16(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
     constexpr int NB_ = BN * 8 / kThreads;               // 16-byte granules per thread, B tile
     constexpr int NA_ = (SPARSE ? BM * 4 : BM * 8) / kThreads;
     constexpr int NM_ = SPARSE ? (BM * 2 + kThreads - 1) / kThreads : 0;
-    uint4 rb[NB_], ra[NA_];
+    u32x4 rb[NB_], ra[NA_];
     uint32_t rm[NM_ > 0 ? NM_ : 1];
 
     auto load_tile = [&](int kt) {
@@ -86,28 +92,32 @@ k_gemm_bf16(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
         for (int it = 0; it < NB_; ++it) {
             const int q = tid + kThreads * it, row = q >> 3, g = q & 7;
             int64_t t = t0 + row; t = t < T ? t : T - 1;
-            rb[it] = load_granule(Bm + t * ldb, k0 + 8 * g, K, vecB);
+            if constexpr (FAST) rb[it] = *reinterpret_cast<const u32x4*>(Bm + t * ldb + k0 + 8 * g);
+            else rb[it] = load_granule(Bm + t * ldb, k0 + 8 * g, K, vecB);
         }
         if constexpr (SPARSE) {
 #pragma unroll
             for (int it = 0; it < NA_; ++it) {
                 const int q = tid + kThreads * it, row = q >> 2, g = q & 3;
                 int64_t a = a0 + row; a = a < Adim ? a : Adim - 1;
-                ra[it] = load_granule(A + a * lda, k0 / 2 + 8 * g, lda, vecA);
+                if constexpr (FAST) ra[it] = *reinterpret_cast<const u32x4*>(A + a * lda + k0 / 2 + 8 * g);
+                else ra[it] = load_granule(A + a * lda, k0 / 2 + 8 * g, lda, vecA);
             }
 #pragma unroll
             for (int it = 0; it < NM_; ++it) {
                 const int q = tid + kThreads * it, row = q >> 1, w = q & 1;
                 int64_t a = a0 + row; a = a < Adim ? a : Adim - 1;
                 const int64_t wi = k0 / 32 + w;
-                rm[it] = (q < BM * 2 && wi < wprA) ? Ameta[a * wprA + wi] : 0u;
+                if constexpr (FAST && (BM * 2) % kThreads == 0) rm[it] = Ameta[a * wprA + wi];
+                else rm[it] = (q < BM * 2 && wi < wprA) ? Ameta[a * wprA + wi] : 0u;
             }
         } else {
 #pragma unroll
             for (int it = 0; it < NA_; ++it) {
                 const int q = tid + kThreads * it, row = q >> 3, g = q & 7;
                 int64_t a = a0 + row; a = a < Adim ? a : Adim - 1;
-                ra[it] = load_granule(A + a * lda, k0 + 8 * g, K, vecA);
+                if constexpr (FAST) ra[it] = *reinterpret_cast<const u32x4*>(A + a * lda + k0 + 8 * g);
+                else ra[it] = load_granule(A + a * lda, k0 + 8 * g, K, vecA);
             }
         }
     };
@@ -118,13 +128,13 @@ k_gemm_bf16(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
 #pragma unroll
         for (int it = 0; it < NB_; ++it) {
             const int q = tid + kThreads * it, row = q >> 3, g = q & 7;
-            *reinterpret_cast<uint4*>(sB + row * kRowB + g * 16) = rb[it];
+            *reinterpret_cast<u32x4*>(sB + row * kRowB + g * 16) = rb[it];
         }
         if constexpr (SPARSE) {
 #pragma unroll
             for (int it = 0; it < NA_; ++it) {
                 const int q = tid + kThreads * it, row = q >> 2, g = q & 3;
-                *reinterpret_cast<uint4*>(sA + row * kRowAs + g * 16) = ra[it];
+                *reinterpret_cast<u32x4*>(sA + row * kRowAs + g * 16) = ra[it];
             }
 #pragma unroll
             for (int it = 0; it < NM_; ++it) {
@@ -135,7 +145,7 @@ k_gemm_bf16(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
 #pragma unroll
             for (int it = 0; it < NA_; ++it) {
                 const int q = tid + kThreads * it, row = q >> 3, g = q & 7;
-                *reinterpret_cast<uint4*>(sA + row * kRowB + g * 16) = ra[it];
+                *reinterpret_cast<u32x4*>(sA + row * kRowB + g * 16) = ra[it];
             }
         }
     };
@@ -229,14 +239,14 @@ k_gemm_bf16(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
         const int row = q / GPR, g = q % GPR;
         const int64_t t = t0 + row, a = a0 + 8 * g;
         if (t >= T || a >= Adim) continue;
-        const uint4 v = *reinterpret_cast<const uint4*>(sC + row * S::kCRow + g * 16);
+        const u32x4 v = *reinterpret_cast<const u32x4*>(sC + row * S::kCRow + g * 16);
         uint16_t* dst = C + t * ldc + a;
         if (vecC && a + 8 <= Adim) {
-            *reinterpret_cast<uint4*>(dst) = v;
+            *reinterpret_cast<u32x4*>(dst) = v;
         } else {
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
             for (int e = 0; e < 8; ++e)
-                if (a + e < Adim) dst[e] = static_cast<uint16_t>(w[e >> 1] >> (16 * (e & 1)));
+                if (a + e < Adim) dst[e] = static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1)));
         }
     }
 }
@@ -332,11 +342,11 @@ k_gather_cols(const raw* __restrict__ in, int64_t T, int64_t ld, const int32_t* 
     }
 }
 
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N>
-int run_gemm_bf16(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
+template <bool SPARSE, bool FAST, int BM, int BN, int WAVES_M, int WAVES_N>
+int run_gemm_bf16_t(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
                   int64_t ldb, void* C, int64_t ldc, hipStream_t s) {
     using S = Smem<SPARSE, BM, BN>;
-    auto kern = k_gemm_bf16<SPARSE, BM, BN, WAVES_M, WAVES_N>;
+    auto kern = k_gemm_bf16<SPARSE, FAST, BM, BN, WAVES_M, WAVES_N>;
     if (S::kTotal > 48 * 1024) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 S::kTotal) != hipSuccess) return BIMASK_ERR_HIP;
@@ -351,6 +361,15 @@ int run_gemm_bf16(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, 
                        static_cast<const uint16_t*>(A), meta, Adim, K, static_cast<const uint16_t*>(Bm), T, ldb,
                        static_cast<uint16_t*>(C), ldc, tiles_a, vecA, vecB, vecC);
     return check_launch();
+}
+
+template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N>
+int run_gemm_bf16(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
+                  int64_t ldb, void* C, int64_t ldc, hipStream_t s) {
+    const int64_t lda = SPARSE ? K / 2 : K;
+    const bool fast = K % BK == 0 && aligned16(A) && (lda * 2) % 16 == 0 && aligned16(Bm) && (ldb * 2) % 16 == 0;
+    if (fast) return run_gemm_bf16_t<SPARSE, true, BM, BN, WAVES_M, WAVES_N>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+    return run_gemm_bf16_t<SPARSE, false, BM, BN, WAVES_M, WAVES_N>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
 }
 
 }  // namespace
@@ -385,7 +404,16 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
                                A_index, Adim, K, static_cast<const float*>(Bm), T, ldb, static_cast<float*>(C), ldc);
         return check_launch();
     }
-    if (sparse24) return run_gemm_bf16<true, 128, 128, 2, 2>(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, s);
+    if (sparse24) {
+        // tuning hook: BIMASK_GEMM_VARIANT picks a tile shape / prefetch depth of the streaming kernel
+        static const int forced = [] { const char* e = getenv("BIMASK_GEMM_VARIANT"); return e ? atoi(e) : -2; }();
+        const int variant = forced != -2 ? forced : (K <= 256 ? 3 : 0);   // short contractions: shallow prefetch
+        if (variant >= 0) {
+            const int rc = launch_gemm_sp24(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, variant, s);
+            if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
+        }
+        return run_gemm_bf16<true, 128, 128, 2, 2>(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, s);
+    }
     return run_gemm_bf16<false, 128, 128, 2, 2>(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, s);
 }
 

@@ -1,0 +1,236 @@
+// 2:4-sparse bf16 GEMM for gfx950, streaming variant:  C[t][a] = sum_k Bm[t][k] * A[a][k]
+// with A given as compressed values + 2-bit indices (the operand of Eq. 3 / Eq. 10 of
+// arXiv 2302.06058).
+//
+// Design (one stage = 128 dense k):
+//   * the compressed weight rows never touch LDS: every lane of a 32x32x32 sparse matrix
+//     instruction owns one weight row and one half of the stage, which is 64 contiguous
+//     bytes of values + 8 contiguous bytes of indices in memory, so the A fragments are
+//     loaded straight from global memory (L2-resident) into the operand registers;
+//   * the token operand is loaded 256 bytes per row with 16-byte lanes, staged through a
+//     double-buffered XOR-swizzled LDS tile and read back as 16-byte fragments;
+//   * PF stages of both operands are kept in flight in registers, so a workgroup has
+//     PF * (BM*72 + BN*256) bytes outstanding to hide HBM latency;
+//   * fp32 accumulators are rounded to bf16, transposed through LDS and written as
+//     16-byte row-contiguous stores.
+// Lane/operand mapping of v_smfmac_f32_32x32x32_bf16 (checked on the device): lane l holds
+// weight row l%32; with h = l/32, compressed element e of the A register pairs with slot
+// 8h + 4((e%4)/2) + idx_e of the B register of token lane half e/4, and idx_e sits in bits
+// [2e+1:2e] of the 16-bit index set selected by ABID.
+#include "common.hpp"
+
+namespace bimask {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(__bf16)))) __bf16 bf16x16;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // native 16-byte register vector
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int SK = 128;                 // dense k per stage
+constexpr int kRowBytes = SK * 2;       // LDS bytes per token row per stage (16 granules)
+
+__device__ __forceinline__ uint32_t to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+union BFrag { bf16x16 v; u32x4 q[2]; };
+union AFrag { bf16x8 v; u32x4 q; };
+
+template <int BM, int BN>
+struct SpSmem {
+    static constexpr int kStage = BN * kRowBytes;
+    static constexpr int kCRow = BM * 2 + 16;
+    static constexpr int kC = BN * kCRow;
+    static constexpr int kTotal = (2 * kStage > kC) ? 2 * kStage : kC;
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF>
+__global__ void __launch_bounds__(kThreads)
+k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int64_t K,
+            const uint16_t* __restrict__ Bm, int64_t T, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
+            int tiles_a, bool vecC) {
+    static_assert(WAVES_M * WAVES_N == kThreads / 64, "four wavefronts");
+    using S = SpSmem<BM, BN>;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int NBUF = PF + 1;
+    constexpr int NB_ = BN * 16 / kThreads;             // 16-byte granules of Bm per thread per stage
+    static_assert(NB_ >= 1 && (BN * 16) % kThreads == 0, "token tile too small");
+    extern __shared__ u32x4 smem_u4[];
+    uint8_t* smem = reinterpret_cast<uint8_t*>(smem_u4);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int64_t a0 = static_cast<int64_t>(blockIdx.x % tiles_a) * BM;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x / tiles_a) * BN;
+    const int64_t lda = K / 2, wprA = K / 32;
+    const int nk = static_cast<int>(K / SK);
+
+    // per-lane source pointers (rows clamped at the edges: loaded, never stored)
+    const uint16_t* pa[TM];
+    const uint32_t* pm[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        int64_t a = a0 + wm * WM + i * 32 + l32;
+        a = a < Adim ? a : Adim - 1;
+        pa[i] = A + a * lda + 32 * h;
+        pm[i] = Ameta + a * wprA + 2 * h;
+    }
+    const uint16_t* pb[NB_];
+    int sb_off[NB_];
+#pragma unroll
+    for (int it = 0; it < NB_; ++it) {
+        const int q = tid + kThreads * it, row = q >> 4, g = q & 15;
+        int64_t t = t0 + row;
+        t = t < T ? t : T - 1;
+        pb[it] = Bm + t * ldb + 8 * g;
+        sb_off[it] = row * kRowBytes + ((g ^ (row & 15)) << 4);
+    }
+
+    u32x4 ra[NBUF][TM][4];
+    u32x2 rmeta[NBUF][TM];
+    u32x4 rb[NBUF][NB_];
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+
+#define BIMASK_LOAD_STAGE(slot, kt)                                                              \
+    {                                                                                            \
+        const int64_t kk = static_cast<int64_t>(kt) * SK;                                        \
+        _Pragma("unroll") for (int it = 0; it < NB_; ++it)                                       \
+            rb[slot][it] = *reinterpret_cast<const u32x4*>(pb[it] + kk);                         \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                         \
+            _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                     \
+                ra[slot][i][s4] = *reinterpret_cast<const u32x4*>(pa[i] + kk / 2 + 8 * s4);      \
+            rmeta[slot][i] = *reinterpret_cast<const u32x2*>(pm[i] + kk / 32);                   \
+        }                                                                                        \
+    }
+
+#pragma unroll
+    for (int s = 0; s < PF; ++s)
+        if (s < nk) BIMASK_LOAD_STAGE(s, s)
+
+#pragma unroll 1
+    for (int kt0 = 0; kt0 < nk; kt0 += NBUF) {
+#pragma unroll
+        for (int u = 0; u < NBUF; ++u) {
+            const int kt = kt0 + u;
+            if (kt < nk) {
+                uint8_t* sB = smem + (kt & 1) * S::kStage;
+#pragma unroll
+                for (int it = 0; it < NB_; ++it) *reinterpret_cast<u32x4*>(sB + sb_off[it]) = rb[u][it];
+                if (kt + PF < nk) BIMASK_LOAD_STAGE((u + PF) % NBUF, kt + PF)
+                __syncthreads();
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4) {
+                    BFrag bf[TN];
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const int row = wn * WN + j * 32 + l32;
+                        const uint8_t* base = sB + row * kRowBytes;
+                        const int g1 = 2 * s4 + h, g2 = 8 + 2 * s4 + h;
+                        bf[j].q[0] = *reinterpret_cast<const u32x4*>(base + ((g1 ^ (row & 15)) << 4));
+                        bf[j].q[1] = *reinterpret_cast<const u32x4*>(base + ((g2 ^ (row & 15)) << 4));
+                    }
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) {
+                        AFrag af;
+                        af.q = ra[u][i][s4];
+                        const int idx = static_cast<int>(s4 < 2 ? rmeta[u][i].x : rmeta[u][i].y);
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            if (s4 & 1)
+                                acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[j].v, acc[i][j], idx, 0, 1);
+                            else
+                                acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[j].v, acc[i][j], idx, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+    }
+#undef BIMASK_LOAD_STAGE
+
+    // Epilogue: accumulators -> bf16 tile [t][a] in LDS -> 16-byte row-contiguous stores.
+    __syncthreads();
+    uint8_t* sC = smem;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int t = wn * WN + j * 32 + l32;
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                const int a = wm * WM + i * 32 + 8 * qq + 4 * h;
+                u32x2 v;
+                v.x = to_bf16(acc[i][j][4 * qq + 0]) | (to_bf16(acc[i][j][4 * qq + 1]) << 16);
+                v.y = to_bf16(acc[i][j][4 * qq + 2]) | (to_bf16(acc[i][j][4 * qq + 3]) << 16);
+                *reinterpret_cast<u32x2*>(sC + t * S::kCRow + a * 2) = v;
+            }
+        }
+    __syncthreads();
+    constexpr int GPR = BM / 8;                          // 16-byte granules per output row
+    for (int q = tid; q < BN * GPR; q += kThreads) {
+        const int row = q / GPR, g = q % GPR;
+        const int64_t t = t0 + row, a = a0 + 8 * g;
+        if (t >= T || a >= Adim) continue;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(sC + row * S::kCRow + g * 16);
+        uint16_t* dst = C + t * ldc + a;
+        if (vecC && a + 8 <= Adim) {
+            *reinterpret_cast<u32x4*>(dst) = v;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (a + e < Adim) dst[e] = static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1)));
+        }
+    }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF>
+int run_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb,
+             void* C, int64_t ldc, hipStream_t s) {
+    using S = SpSmem<BM, BN>;
+    auto kern = k_gemm_sp24<BM, BN, WAVES_M, WAVES_N, PF>;
+    if (S::kTotal > 48 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                S::kTotal) != hipSuccess) return BIMASK_ERR_HIP;
+    }
+    const bool vecC = aligned16(C) && (ldc * 2) % 16 == 0;
+    const int tiles_a = static_cast<int>(ceil_div(Adim, BM));
+    const int64_t tiles_t = ceil_div(T, BN);
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(tiles_a * tiles_t)), dim3(kThreads), S::kTotal, s,
+                       static_cast<const uint16_t*>(A), meta, Adim, K, static_cast<const uint16_t*>(Bm), T, ldb,
+                       static_cast<uint16_t*>(C), ldc, tiles_a, vecC);
+    return check_launch();
+}
+
+}  // namespace
+
+// Streaming 2:4 GEMM; returns BIMASK_ERR_UNSUPPORTED when the shape needs the generic kernel.
+int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
+                     int64_t ldb, void* C, int64_t ldc, int variant, hipStream_t s) {
+    const bool ok = K % SK == 0 && aligned16(A) && aligned16(Bm) && (ldb * 2) % 16 == 0 &&
+                    (reinterpret_cast<uintptr_t>(meta) & 7u) == 0;
+    if (!ok) return BIMASK_ERR_UNSUPPORTED;
+    switch (variant) {
+        case 0: return run_sp24<256, 64, 4, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 1: return run_sp24<256, 64, 4, 1, 3>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 2: return run_sp24<128, 128, 2, 2, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 3: return run_sp24<256, 64, 4, 1, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 4: return run_sp24<128, 64, 4, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 5: return run_sp24<256, 128, 2, 2, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        default: return BIMASK_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace bimask

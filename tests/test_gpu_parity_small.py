@@ -197,3 +197,10 @@ def test_results_are_reproducible_bit_for_bit():
                      words(Bb), raw_bits(vb, synth.BF16), words(ib)])
     for a, b in zip(*outs):
         assert (a == b).all()
+
+
+@pytest.mark.parametrize("I,J,T", [(256, 384, 200), (384, 256, 130), (128, 1152, 64), (640, 128, 333)])
+def test_streaming_gemm_shapes(I, J, T):
+    # contraction lengths that are multiples of 128 take the streaming 2:4 kernel in both
+    # directions; ragged token counts and weight-row counts exercise its edge tiles
+    check_layer(I=I, J=J, N=2, M=4, dtype=synth.BF16, K=6, seed=800 + I + J, T=T)
