@@ -63,10 +63,10 @@ class LayerRun:
         wj, wi = bm.mask_words(L.J), bm.mask_words(L.I)
         self.B = torch.empty((L.I, wj), dtype=torch.int32, device=dev)
         self.Bbar = torch.empty((L.I, wj), dtype=torch.int32, device=dev)
-        self.vf = torch.empty((L.I, L.J // 2 if s24 else L.J), dtype=tdt, device=dev)
-        self.xf = torch.empty((L.I, wj), dtype=torch.int32, device=dev) if s24 else None
-        self.vb = torch.empty((L.J, L.I // 2 if s24 else L.I), dtype=tdt, device=dev)
-        self.xb = torch.empty((L.J, wi), dtype=torch.int32, device=dev) if s24 else None
+        self.vf = torch.empty((bm.operand_elems(L.I, L.J, L.N, L.M),), dtype=tdt, device=dev)
+        self.xf = torch.empty((bm.operand_index_words(L.I, L.J, L.N, L.M),), dtype=torch.int32, device=dev) if s24 else None
+        self.vb = torch.empty((bm.operand_elems(L.J, L.I, L.N, L.M),), dtype=tdt, device=dev)
+        self.xb = torch.empty((bm.operand_index_words(L.J, L.I, L.N, L.M),), dtype=torch.int32, device=dev) if s24 else None
         self.scores = torch.empty((L.K,), dtype=torch.int32, device=dev)
         self.best = torch.empty((1,), dtype=torch.int32, device=dev)
         self.P = torch.empty((L.I,), dtype=torch.int32, device=dev)

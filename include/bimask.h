@@ -31,18 +31,26 @@
  * (j / 32); unused high bits of the last word of a row are written as zero.
  *
  * Compressed N:M operand (this library's format; the paper only names the sparse
- * tensor core as consumer):
- *   for (N, M) = (2, 4):
- *     values  rows x (cols/2) elements: per group of 4 the two slot values in ascending
- *             position order
- *     index   rows x ceil(cols/32) uint32: per group one nibble p0 | (p1 << 2), p0 < p1,
- *             group g of a row at bits [4g+3 : 4g] of that row's little-endian bit stream
- *     The slot positions are the mask's ones; a group whose mask holds fewer than two
- *     ones is completed with its lowest-index zero positions, which carry value 0.
- *   for every other (N, M): values is the dense masked matrix rows x cols (zeros where the
- *     mask is 0) and index is not written (may be NULL).
- *   transposed = 0: rows = I, cols = J (groups along J).
- *   transposed = 1: rows = J, cols = I (groups along the permuted row index r).
+ * tensor core as consumer).  Let the operand have `rows` x `cols` logical entries:
+ *   transposed = 0: rows = I, cols = J (groups of M along J);
+ *   transposed = 1: rows = J, cols = I (groups of M along the permuted row index r).
+ *   for (N, M) = (2, 4), "fragment-major" layout, laid out so that one wavefront of a
+ *   32x32x32 sparse matrix instruction fetches its whole A operand with contiguous
+ *   16-byte lanes.  Rp = rows rounded up to 32, Cp = cols rounded up to 128, KS = Cp/128.
+ *     Logical content per row: slot s = 2g + n (n = 0, 1) of group g holds the n-th slot
+ *     value of that group, slots in ascending position order; the group's index nibble is
+ *     p0 | (p1 << 2), p0 < p1.  The slot positions are the mask's ones; a group whose
+ *     mask holds fewer than two ones is completed with its lowest-index zero positions,
+ *     which carry value 0.  Rows >= rows and columns >= cols are zero padding.
+ *     values  Rp * Cp/2 elements.  Slot s of row r: with st = s / 64, c = s % 64,
+ *             element (((r/32 * KS + st) * 4 + (c%32)/8) * 64 + r%32 + 32*(c/32)) * 8 + c%8.
+ *     index   Rp * Cp/32 uint32.  Group g of row r: with st = g / 32, q = g % 32, nibble
+ *             q%8 (bits [4(q%8)+3 : 4(q%8)]) of word
+ *             ((r/32 * KS + st) * 64 + r%32 + 32*(q/16)) * 2 + (q/8)%2.
+ *     Both buffers must be 16-byte aligned.
+ *   for every other (N, M): values is the dense masked matrix rows x cols, row-major
+ *     (zeros where the mask is 0), and index is not written (may be NULL).
+ *   bimask_operand_elems / bimask_operand_index_words give the buffer sizes.
  *
  * Conventions:
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library allocates
@@ -100,8 +108,8 @@ BIMASK_API int bimask_forward_mask(const void *W, int64_t I, int64_t J, int64_t 
 
 /* Forward mask and the compressed forward operand in one pass over W (same results as
  * bimask_forward_mask followed by bimask_compress_nm(transposed = 0)).
- *   values  out  I x (J/2) elements for 2:4, else I x J            (row stride = that width)
- *   index   out  I x ceil(J/32) words for 2:4, else ignored                            */
+ *   values  out  bimask_operand_elems(I, J, N, M) elements
+ *   index   out  bimask_operand_index_words(I, J, N, M) words for 2:4, else ignored      */
 BIMASK_API int bimask_forward_mask_compress(const void *W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
                                  uint32_t *B_bits, void *values, uint32_t *index, void *stream);
 
@@ -129,8 +137,8 @@ BIMASK_API int bimask_backward_mask(const void *W, int64_t I, int64_t J, int64_t
 
 /* Backward mask and the transposed compressed backward operand in one pass (same results
  * as bimask_backward_mask followed by bimask_compress_nm(transposed = 1)).
- *   values  out  J x (I/2) elements for 2:4, else J x I
- *   index   out  J x ceil(I/32) words for 2:4, else ignored                             */
+ *   values  out  bimask_operand_elems(J, I, N, M) elements
+ *   index   out  bimask_operand_index_words(J, I, N, M) words for 2:4, else ignored      */
 BIMASK_API int bimask_backward_mask_compress(const void *W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
                                   const uint32_t *B_bits, const int32_t *perm, uint32_t *Bbar_bits,
                                   void *values, uint32_t *index, void *stream);
@@ -157,11 +165,17 @@ BIMASK_API int bimask_sparse_gemm_fwd(const void *X, int64_t T, int64_t ldx, con
 /* Backward GEMM, Eq. (10):  dX[t][j] = sum_r dY[t][P[r]] * (Bbar .* W[P,:])[r][j], with the
  * weight operand given in transposed compressed form (transposed = 1); perm = NULL is Eq. (8).
  *   dY  in  T x I (lddy >= I);   dX  out  T x J (lddx >= J).
- *   workspace: bimask_workspace_bytes(BIMASK_WS_GEMM_BWD, ...) bytes (holds dY[:,P]).     */
+ *   workspace: bimask_workspace_bytes(BIMASK_WS_GEMM_BWD, ...) bytes (holds dY[:,P] when the
+ *   gather is not fused into the GEMM; 0 = none needed).                                 */
 BIMASK_API int bimask_sparse_gemm_bwd(const void *dY, int64_t T, int64_t lddy, const int32_t *perm,
                            const void *Wb_values, const uint32_t *Wb_index, int64_t I, int64_t J,
                            int dtype, int N, int M, void *dX, int64_t lddx,
                            void *workspace, size_t workspace_bytes, void *stream);
+
+/* Buffer sizes of a compressed operand with `rows` x `cols` logical entries: number of
+ * elements of `values` and of uint32 words of `index` (0 when no index is written).     */
+BIMASK_API int64_t bimask_operand_elems(int64_t rows, int64_t cols, int N, int M);
+BIMASK_API int64_t bimask_operand_index_words(int64_t rows, int64_t cols, int N, int M);
 
 /* Scratch bytes a call needs (0 if none).  kind is a bimask_ws_kind.                     */
 BIMASK_API size_t bimask_workspace_bytes(int kind, int64_t I, int64_t J, int64_t T, int K, int dtype, int N, int M);

@@ -29,6 +29,8 @@ _SIGNATURES = {
     "bimask_compress_nm": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR, _INT, _PTR, _PTR, _PTR]),
     "bimask_sparse_gemm_fwd": (_INT, [_PTR, _I64, _I64, _PTR, _PTR, _I64, _I64, _INT, _INT, _INT, _PTR, _I64, _PTR, _SZ, _PTR]),
     "bimask_sparse_gemm_bwd": (_INT, [_PTR, _I64, _I64, _PTR, _PTR, _PTR, _I64, _I64, _INT, _INT, _INT, _PTR, _I64, _PTR, _SZ, _PTR]),
+    "bimask_operand_elems": (_I64, [_I64, _I64, _INT, _INT]),
+    "bimask_operand_index_words": (_I64, [_I64, _I64, _INT, _INT]),
     "bimask_workspace_bytes": (_SZ, [_INT, _I64, _I64, _I64, _INT, _INT, _INT, _INT]),
     "bimask_status_string": (ctypes.c_char_p, [_INT]),
 }
@@ -110,8 +112,21 @@ def _empty(shape, dtype, like):
     return torch.empty(shape, dtype=dtype, device=like.device)
 
 
+def operand_elems(rows: int, cols: int, N: int, M: int) -> int:
+    return int(lib().bimask_operand_elems(rows, cols, N, M))
+
+
+def operand_index_words(rows: int, cols: int, N: int, M: int) -> int:
+    return int(lib().bimask_operand_index_words(rows, cols, N, M))
+
+
 def _values_shape(rows: int, cols: int, N: int, M: int):
-    return (rows, cols // 2) if (N, M) == (2, 4) else (rows, cols)
+    """2:4: flat fragment-major buffer (see include/bimask.h); else the dense rows x cols matrix."""
+    return (operand_elems(rows, cols, N, M),) if (N, M) == (2, 4) else (rows, cols)
+
+
+def _index_shape(rows: int, cols: int, N: int, M: int):
+    return (operand_index_words(rows, cols, N, M),)
 
 
 # -- the calls of include/bimask.h -----------------------------------------------------
@@ -137,7 +152,7 @@ def bimask_forward_mask_compress(W, N: int, M: int, B_bits=None, values=None, in
     if values is None:
         values = _empty(_values_shape(I, J, N, M), W.dtype, W)
     if index is None and (N, M) == (2, 4):
-        index = _empty((I, mask_words(J)), torch.int32, W)
+        index = _empty(_index_shape(I, J, N, M), torch.int32, W)
     _check("bimask_forward_mask_compress",
            lib().bimask_forward_mask_compress(_ptr(W), I, J, ldw, _dtype_code(W), N, M, _ptr(B_bits),
                                               _ptr(values), _ptr(index), _stream()))
@@ -190,7 +205,7 @@ def bimask_backward_mask_compress(W, N: int, M: int, B_bits, perm=None, Bbar_bit
     if values is None:
         values = _empty(_values_shape(J, I, N, M), W.dtype, W)
     if index is None and (N, M) == (2, 4):
-        index = _empty((J, mask_words(I)), torch.int32, W)
+        index = _empty(_index_shape(J, I, N, M), torch.int32, W)
     _check("bimask_backward_mask_compress",
            lib().bimask_backward_mask_compress(_ptr(W), I, J, ldw, _dtype_code(W), N, M, _ptr(B_bits), _ptr(perm),
                                                _ptr(Bbar_bits), _ptr(values), _ptr(index), _stream()))
@@ -206,7 +221,7 @@ def bimask_compress_nm(W, N: int, M: int, mask_bits, perm=None, transposed: int 
     if values is None:
         values = _empty(_values_shape(rows, cols, N, M), W.dtype, W)
     if index is None and (N, M) == (2, 4):
-        index = _empty((rows, mask_words(cols)), torch.int32, W)
+        index = _empty(_index_shape(rows, cols, N, M), torch.int32, W)
     _check("bimask_compress_nm",
            lib().bimask_compress_nm(_ptr(W), I, J, ldw, _dtype_code(W), N, M, _ptr(mask_bits), _ptr(perm),
                                     int(transposed), _ptr(values), _ptr(index), _stream()))

@@ -1,6 +1,7 @@
 // extern "C" boundary of the Bi-Mask library: argument validation on the host, then
 // kernel launches on the caller's stream.  See include/bimask.h for the contract.
 #include "common.hpp"
+#include <cstdlib>
 
 using namespace bimask;
 
@@ -37,6 +38,7 @@ int check_gemm(const void* act, int64_t T, int64_t ldact, int64_t kdim, const vo
     if (int rc = check_nm(N, M)) return rc;
     if (T <= 0 || I <= 0 || J <= 0 || I % M || J % M || ldact < kdim || ldout < outdim) return BIMASK_ERR_SHAPE;
     if (N == 2 && M == 4 && !index) return BIMASK_ERR_NULL;
+    if (N == 2 && M == 4 && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
     if (dtype == BIMASK_BF16) {
         // rows are read in 4-byte units at least
         if (ldact % 2 || ldout % 2) return BIMASK_ERR_ALIGN;
@@ -64,6 +66,7 @@ int bimask_forward_mask_compress(const void* W, int64_t I, int64_t J, int64_t ld
     if (!B_bits || !values) return BIMASK_ERR_NULL;
     if (N == 2 && M == 4 && !index) return BIMASK_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(values) % esize(dtype)) return BIMASK_ERR_ALIGN;
+    if (N == 2 && M == 4 && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
     return launch_forward(W, I, J, ldw, dtype, N, M, nullptr, B_bits, values, index, true, as_stream(stream));
 }
 
@@ -97,6 +100,7 @@ int bimask_backward_mask_compress(const void* W, int64_t I, int64_t J, int64_t l
     if (!B_bits || !Bbar_bits || !values) return BIMASK_ERR_NULL;
     if (N == 2 && M == 4 && !index) return BIMASK_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(values) % esize(dtype)) return BIMASK_ERR_ALIGN;
+    if (N == 2 && M == 4 && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
     return launch_backward(W, I, J, ldw, dtype, N, M, B_bits, nullptr, perm, Bbar_bits, values, index, true,
                            as_stream(stream));
 }
@@ -108,6 +112,7 @@ int bimask_compress_nm(const void* W, int64_t I, int64_t J, int64_t ldw, int dty
     if (!mask_bits || !values) return BIMASK_ERR_NULL;
     if (N == 2 && M == 4 && !index) return BIMASK_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(values) % esize(dtype)) return BIMASK_ERR_ALIGN;
+    if (N == 2 && M == 4 && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
     if (transposed != 0 && transposed != 1) return BIMASK_ERR_SHAPE;
     if (!transposed) {
         if (perm) return BIMASK_ERR_UNSUPPORTED;                     // rows of the forward operand are not permuted
@@ -133,6 +138,11 @@ int bimask_sparse_gemm_bwd(const void* dY, int64_t T, int64_t lddy, const int32_
     const bool sp = (N == 2 && M == 4);
     const void* act = dY;
     int64_t ldact = lddy;
+    if (perm && !gemm_bwd_needs_gather(I, dtype, N, M)) {
+        // short contraction: the column gather is fused into the GEMM's token-tile load
+        static const int resvar = [] { const char* e = getenv("BIMASK_RES_VARIANT"); return e ? atoi(e) : 0; }();
+        return launch_gemm_sp24_resident(Wb_values, Wb_index, J, I, dY, lddy, perm, T, dX, lddx, resvar, as_stream(stream));
+    }
     if (perm) {
         const size_t need = bimask_workspace_bytes(BIMASK_WS_GEMM_BWD, I, J, T, 0, dtype, N, M);
         if (!workspace || workspace_bytes < need) return BIMASK_ERR_WORKSPACE;
@@ -142,6 +152,17 @@ int bimask_sparse_gemm_bwd(const void* dY, int64_t T, int64_t lddy, const int32_
         ldact = I;
     }
     return launch_gemm(Wb_values, Wb_index, J, I, sp, act, T, ldact, dX, lddx, dtype, as_stream(stream));
+}
+
+int64_t bimask_operand_elems(int64_t rows, int64_t cols, int N, int M) {
+    if (rows <= 0 || cols <= 0) return 0;
+    if (N == 2 && M == 4) return round_up(rows, 32) * (round_up(cols, 128) / 2);
+    return rows * cols;
+}
+
+int64_t bimask_operand_index_words(int64_t rows, int64_t cols, int N, int M) {
+    if (rows <= 0 || cols <= 0 || !(N == 2 && M == 4)) return 0;
+    return round_up(rows, 32) * (round_up(cols, 128) / 32);
 }
 
 size_t bimask_workspace_bytes(int kind, int64_t I, int64_t J, int64_t T, int K, int dtype, int N, int M) {
@@ -156,6 +177,7 @@ size_t bimask_workspace_bytes(int kind, int64_t I, int64_t J, int64_t T, int K, 
         case BIMASK_WS_GEMM_FWD:
             return 0;
         case BIMASK_WS_GEMM_BWD:
+            if (!gemm_bwd_needs_gather(I, dtype, N, M)) return 0;
             return T > 0 ? static_cast<size_t>(T) * static_cast<size_t>(I) * esize(dtype) : 0;
         default:
             return 0;

@@ -66,6 +66,20 @@ __device__ __forceinline__ uint32_t complete_slots(uint32_t bits, int N) {
     return sel;
 }
 
+// Fragment-major layout of a 2:4 compressed operand (see include/bimask.h): element
+// offsets of slot s / index word of group g of logical row r; ks = padded cols / 128.
+__host__ __device__ inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+__host__ __device__ inline int64_t tiled_val_off(int64_t r, int64_t s, int64_t ks) {
+    const int64_t st = s >> 6;
+    const int c = static_cast<int>(s & 63);
+    return ((((r >> 5) * ks + st) * 4 + ((c & 31) >> 3)) * 64 + (r & 31) + 32 * (c >> 5)) * 8 + (c & 7);
+}
+__host__ __device__ inline int64_t tiled_idx_word(int64_t r, int64_t g, int64_t ks) {
+    const int64_t st = g >> 5;
+    const int q = static_cast<int>(g & 31);
+    return (((r >> 5) * ks + st) * 64 + (r & 31) + 32 * (q >> 4)) * 2 + ((q >> 3) & 1);
+}
+
 // launchers implemented in the .hip files -------------------------------------------
 int launch_forward(const void* W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
                    const uint32_t* mask_in, uint32_t* B_bits, void* values, uint32_t* index,
@@ -95,5 +109,11 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
 
 int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
                      int64_t ldb, void* C, int64_t ldc, int variant, hipStream_t s);
+
+int launch_gemm_sp24_resident(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc,
+                              int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, int variant,
+                              hipStream_t s);
+// true when the backward GEMM needs the gathered copy of g(Y) in the workspace
+bool gemm_bwd_needs_gather(int64_t I, int dtype, int N, int M);
 
 }  // namespace bimask

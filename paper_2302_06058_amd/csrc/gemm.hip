@@ -7,9 +7,9 @@
 // compressed, so the weights sit on the A side and the product is formed transposed
 // (rows of the accumulator tile are weight rows, columns are tokens).
 //
-// bf16, 2:4  : v_smfmac_f32_32x32x32_bf16, A read in compressed form (values + 2-bit indices)
-// bf16, other: v_mfma_f32_32x32x16_bf16 on the dense masked weights
-// fp32       : plain fp32 FMA kernel (small problems only)
+// bf16, 2:4  : v_smfmac_f32_32x32x32_bf16 on the fragment-major compressed operand (gemm_sp24.hip)
+// bf16, other: v_mfma_f32_32x32x16_bf16 on the dense masked weights (this file)
+// fp32       : plain fp32 FMA kernel, small problems only (this file)
 #include "common.hpp"
 #include <cstdlib>
 
@@ -20,10 +20,10 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(__bf16)))) __bf16 bf16x16;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // native 16-byte register vector
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int BK = 64;                // dense k per pipeline stage
-constexpr int kRowB = 144;            // LDS bytes per 64-k row of a dense operand (128 + 16 pad)
-constexpr int kRowAs = 80;            // LDS bytes per 64-k row of compressed values (64 + 16 pad)
+constexpr int kRowB = 144;            // LDS bytes per 64-k row (128 + 16 pad: conflict-free 16-byte reads)
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
@@ -46,109 +46,76 @@ __device__ __forceinline__ u32x4 load_granule(const uint16_t* row, int64_t k, in
     return r;
 }
 
-template <bool SPARSE, int BM, int BN>
+template <int BM, int BN>
 struct Smem {
-    static constexpr int kA = SPARSE ? BM * kRowAs : BM * kRowB;
-    static constexpr int kMeta = SPARSE ? BM * 8 : 0;
+    static constexpr int kA = BM * kRowB;
     static constexpr int kB = BN * kRowB;
-    static constexpr int kStage = kA + kMeta + kB;
+    static constexpr int kStage = kA + kB;
     static constexpr int kCRow = BM * 2 + 16;
     static constexpr int kC = BN * kCRow;
     static constexpr int kTotal = (2 * kStage > kC) ? 2 * kStage : kC;
 };
 
-// Workgroup tile BM (weight rows a) x BN (tokens t); WAVES_M x WAVES_N wavefronts.
-// FAST: K is a multiple of BK and every row of A, Bm starts 16-byte aligned, so all tile
-// loads are unconditional 16-byte loads (rows beyond the edge are clamped, never skipped).
-template <bool SPARSE, bool FAST, int BM, int BN, int WAVES_M, int WAVES_N>
+// Dense bf16 GEMM on masked weights (N:M ratios other than 2:4).  Workgroup tile BM (weight
+// rows a) x BN (tokens t); both operands go global -> registers -> padded LDS -> MFMA
+// fragments, one stage prefetched in registers.
+// FAST: K is a multiple of BK and all rows start 16-byte aligned: unconditional 16-byte loads.
+template <bool FAST, int BM, int BN, int WAVES_M, int WAVES_N>
 __global__ void __launch_bounds__(kThreads)
-k_gemm_bf16(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int64_t K,
-            const uint16_t* __restrict__ Bm, int64_t T, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
-            int tiles_a, bool vecA, bool vecB, bool vecC) {
+k_gemm_dense_bf16(const uint16_t* __restrict__ A, int64_t Adim, int64_t K, const uint16_t* __restrict__ Bm,
+                  int64_t T, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc, int tiles_a, bool vecA,
+                  bool vecB, bool vecC) {
     static_assert(WAVES_M * WAVES_N == kThreads / 64, "four wavefronts");
-    using S = Smem<SPARSE, BM, BN>;
+    using S = Smem<BM, BN>;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
-    extern __shared__ uint4 smem_u4[];
+    extern __shared__ u32x4 smem_u4[];
     uint8_t* smem = reinterpret_cast<uint8_t*>(smem_u4);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+    const int l32 = lane & 31, h = lane >> 5;
     const int64_t a0 = static_cast<int64_t>(blockIdx.x % tiles_a) * BM;
     const int64_t t0 = static_cast<int64_t>(blockIdx.x / tiles_a) * BN;
-    const int64_t lda = SPARSE ? K / 2 : K;              // elements per row of A values
-    const int64_t wprA = ceil_div(K, 32);                // index words per row
     const int nk = static_cast<int>(ceil_div(K, BK));
 
-    constexpr int NB_ = BN * 8 / kThreads;               // 16-byte granules per thread, B tile
-    constexpr int NA_ = (SPARSE ? BM * 4 : BM * 8) / kThreads;
-    constexpr int NM_ = SPARSE ? (BM * 2 + kThreads - 1) / kThreads : 0;
+    constexpr int NB_ = BN * 8 / kThreads, NA_ = BM * 8 / kThreads;   // 16-byte granules per thread
     u32x4 rb[NB_], ra[NA_];
-    uint32_t rm[NM_ > 0 ? NM_ : 1];
+    const uint16_t* pb[NB_];
+    const uint16_t* pa[NA_];
+#pragma unroll
+    for (int it = 0; it < NB_; ++it) {
+        int64_t t = t0 + ((tid + kThreads * it) >> 3);
+        pb[it] = Bm + (t < T ? t : T - 1) * ldb;
+    }
+#pragma unroll
+    for (int it = 0; it < NA_; ++it) {
+        int64_t a = a0 + ((tid + kThreads * it) >> 3);
+        pa[it] = A + (a < Adim ? a : Adim - 1) * K;
+    }
+    const int g8 = (tid & 7) * 8;                        // this thread's k offset inside a stage
 
-    auto load_tile = [&](int kt) {
-        const int64_t k0 = static_cast<int64_t>(kt) * BK;
-#pragma unroll
-        for (int it = 0; it < NB_; ++it) {
-            const int q = tid + kThreads * it, row = q >> 3, g = q & 7;
-            int64_t t = t0 + row; t = t < T ? t : T - 1;
-            if constexpr (FAST) rb[it] = *reinterpret_cast<const u32x4*>(Bm + t * ldb + k0 + 8 * g);
-            else rb[it] = load_granule(Bm + t * ldb, k0 + 8 * g, K, vecB);
-        }
-        if constexpr (SPARSE) {
-#pragma unroll
-            for (int it = 0; it < NA_; ++it) {
-                const int q = tid + kThreads * it, row = q >> 2, g = q & 3;
-                int64_t a = a0 + row; a = a < Adim ? a : Adim - 1;
-                if constexpr (FAST) ra[it] = *reinterpret_cast<const u32x4*>(A + a * lda + k0 / 2 + 8 * g);
-                else ra[it] = load_granule(A + a * lda, k0 / 2 + 8 * g, lda, vecA);
-            }
-#pragma unroll
-            for (int it = 0; it < NM_; ++it) {
-                const int q = tid + kThreads * it, row = q >> 1, w = q & 1;
-                int64_t a = a0 + row; a = a < Adim ? a : Adim - 1;
-                const int64_t wi = k0 / 32 + w;
-                if constexpr (FAST && (BM * 2) % kThreads == 0) rm[it] = Ameta[a * wprA + wi];
-                else rm[it] = (q < BM * 2 && wi < wprA) ? Ameta[a * wprA + wi] : 0u;
-            }
-        } else {
-#pragma unroll
-            for (int it = 0; it < NA_; ++it) {
-                const int q = tid + kThreads * it, row = q >> 3, g = q & 7;
-                int64_t a = a0 + row; a = a < Adim ? a : Adim - 1;
-                if constexpr (FAST) ra[it] = *reinterpret_cast<const u32x4*>(A + a * lda + k0 + 8 * g);
-                else ra[it] = load_granule(A + a * lda, k0 + 8 * g, K, vecA);
-            }
-        }
-    };
-    auto store_tile = [&](int buf) {
-        uint8_t* sA = smem + buf * S::kStage;
-        uint8_t* sM = sA + S::kA;
-        uint8_t* sB = sM + S::kMeta;
-#pragma unroll
-        for (int it = 0; it < NB_; ++it) {
-            const int q = tid + kThreads * it, row = q >> 3, g = q & 7;
-            *reinterpret_cast<u32x4*>(sB + row * kRowB + g * 16) = rb[it];
-        }
-        if constexpr (SPARSE) {
-#pragma unroll
-            for (int it = 0; it < NA_; ++it) {
-                const int q = tid + kThreads * it, row = q >> 2, g = q & 3;
-                *reinterpret_cast<u32x4*>(sA + row * kRowAs + g * 16) = ra[it];
-            }
-#pragma unroll
-            for (int it = 0; it < NM_; ++it) {
-                const int q = tid + kThreads * it;
-                if (q < BM * 2) reinterpret_cast<uint32_t*>(sM)[q] = rm[it];
-            }
-        } else {
-#pragma unroll
-            for (int it = 0; it < NA_; ++it) {
-                const int q = tid + kThreads * it, row = q >> 3, g = q & 7;
-                *reinterpret_cast<u32x4*>(sA + row * kRowB + g * 16) = ra[it];
-            }
-        }
-    };
+#define BIMASK_DENSE_LOAD(kt)                                                                     \
+    {                                                                                             \
+        const int64_t k = static_cast<int64_t>(kt) * BK + g8;                                     \
+        _Pragma("unroll") for (int it = 0; it < NB_; ++it) {                                      \
+            if constexpr (FAST) rb[it] = *reinterpret_cast<const u32x4*>(pb[it] + k);             \
+            else rb[it] = load_granule(pb[it], k, K, vecB);                                       \
+        }                                                                                         \
+        _Pragma("unroll") for (int it = 0; it < NA_; ++it) {                                      \
+            if constexpr (FAST) ra[it] = *reinterpret_cast<const u32x4*>(pa[it] + k);             \
+            else ra[it] = load_granule(pa[it], k, K, vecA);                                       \
+        }                                                                                         \
+    }
+#define BIMASK_DENSE_STORE(buf)                                                                   \
+    {                                                                                             \
+        uint8_t* sA_ = smem + (buf) * S::kStage;                                                  \
+        uint8_t* sB_ = sA_ + S::kA;                                                               \
+        _Pragma("unroll") for (int it = 0; it < NB_; ++it)                                        \
+            *reinterpret_cast<u32x4*>(sB_ + ((tid + kThreads * it) >> 3) * kRowB + (tid & 7) * 16) = rb[it]; \
+        _Pragma("unroll") for (int it = 0; it < NA_; ++it)                                        \
+            *reinterpret_cast<u32x4*>(sA_ + ((tid + kThreads * it) >> 3) * kRowB + (tid & 7) * 16) = ra[it]; \
+    }
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -158,64 +125,33 @@ k_gemm_bf16(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
 #pragma unroll
             for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
-    const int l32 = lane & 31, h = lane >> 5;
-    load_tile(0);
-    store_tile(0);
+    BIMASK_DENSE_LOAD(0)
+    BIMASK_DENSE_STORE(0)
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) load_tile(kt + 1);
+        const bool more = kt + 1 < nk;
+        if (more) BIMASK_DENSE_LOAD(kt + 1)
         const uint8_t* sA = smem + (kt & 1) * S::kStage;
-        const uint8_t* sM = sA + S::kA;
-        const uint8_t* sB = sM + S::kMeta;
-        if constexpr (SPARSE) {
-            // One stage = 64 dense k.  Lane half h owns compressed values [16h, 16h+16) of
-            // its weight row (= dense k [32h, 32h+32)) and the matching 32 index bits; the
-            // first instruction consumes the low 16 index bits (ABID 0), the second the
-            // high 16 (ABID 1).  Each token lane supplies dense k {8h..8h+7, 32+8h..} to
-            // the first and {16+8h.., 48+8h..} to the second instruction.
-            bf16x8 af[TM][2];
-            int ai[TM];
+        const uint8_t* sB = sA + S::kA;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int row = wm * WM + i * 32 + l32;
-                af[i][0] = *reinterpret_cast<const bf16x8*>(sA + row * kRowAs + h * 32);
-                af[i][1] = *reinterpret_cast<const bf16x8*>(sA + row * kRowAs + h * 32 + 16);
-                ai[i] = reinterpret_cast<const int*>(sM)[row * 2 + h];
-            }
+        for (int c = 0; c < 4; ++c) {                    // four 16-k MFMA steps per stage
+            bf16x8 af[TM];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                af[i] = *reinterpret_cast<const bf16x8*>(sA + (wm * WM + i * 32 + l32) * kRowB + c * 32 + h * 16);
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int row = wn * WN + j * 32 + l32;
-                const uint8_t* p = sB + row * kRowB + h * 16;
-                union { bf16x16 v; bf16x8 half[2]; } b0, b1;
-                b0.half[0] = *reinterpret_cast<const bf16x8*>(p);
-                b0.half[1] = *reinterpret_cast<const bf16x8*>(p + 64);
-                b1.half[0] = *reinterpret_cast<const bf16x8*>(p + 32);
-                b1.half[1] = *reinterpret_cast<const bf16x8*>(p + 96);
-#pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af[i][0], b0.v, acc[i][j], ai[i], 0, 0);
-                    acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af[i][1], b1.v, acc[i][j], ai[i], 0, 1);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                bf16x8 af[TM];
+                const bf16x8 bf = *reinterpret_cast<const bf16x8*>(sB + (wn * WN + j * 32 + l32) * kRowB + c * 32 + h * 16);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
-                    af[i] = *reinterpret_cast<const bf16x8*>(sA + (wm * WM + i * 32 + l32) * kRowB + c * 32 + h * 16);
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const bf16x8 bf = *reinterpret_cast<const bf16x8*>(sB + (wn * WN + j * 32 + l32) * kRowB + c * 32 + h * 16);
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf, acc[i][j], 0, 0, 0);
-                }
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf, acc[i][j], 0, 0, 0);
             }
         }
-        if (kt + 1 < nk) store_tile((kt + 1) & 1);
+        if (more) BIMASK_DENSE_STORE((kt + 1) & 1)
         __syncthreads();
     }
+#undef BIMASK_DENSE_LOAD
+#undef BIMASK_DENSE_STORE
 
     // Epilogue: accumulators -> bf16 tile [t][a] in LDS -> 16-byte row-contiguous stores.
     uint8_t* sC = smem;
@@ -227,10 +163,10 @@ k_gemm_bf16(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
 #pragma unroll
             for (int qq = 0; qq < 4; ++qq) {
                 const int a = wm * WM + i * 32 + 8 * qq + 4 * h;
-                uint2 v;
+                u32x2 v;
                 v.x = f32_to_bf16_rne(acc[i][j][4 * qq + 0]) | (f32_to_bf16_rne(acc[i][j][4 * qq + 1]) << 16);
                 v.y = f32_to_bf16_rne(acc[i][j][4 * qq + 2]) | (f32_to_bf16_rne(acc[i][j][4 * qq + 3]) << 16);
-                *reinterpret_cast<uint2*>(sC + t * S::kCRow + a * 2) = v;
+                *reinterpret_cast<u32x2*>(sC + t * S::kCRow + a * 2) = v;
             }
         }
     __syncthreads();
@@ -263,7 +199,7 @@ k_gemm_f32(const float* __restrict__ A, const uint32_t* __restrict__ Ameta, int6
     __shared__ float sB[TS][KS + 1];
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     const int64_t a0 = static_cast<int64_t>(blockIdx.x) * TS, t0 = static_cast<int64_t>(blockIdx.y) * TS;
-    const int64_t wprA = ceil_div(K, 32);
+    const int64_t ks = ceil_div(K, 128);                 // stages of the fragment-major operand
     float acc[4][4] = {};
     for (int64_t k0 = 0; k0 < K; k0 += KS) {
         for (int idx = threadIdx.x; idx < TS * KS; idx += kThreads) {
@@ -277,10 +213,10 @@ k_gemm_f32(const float* __restrict__ A, const uint32_t* __restrict__ Ameta, int6
                     if constexpr (SPARSE) {
                         const int64_t g = gk >> 2;
                         const int pos = static_cast<int>(gk & 3);
-                        const uint32_t nib = (Ameta[a * wprA + (g >> 3)] >> (4 * (g & 7))) & 15u;
+                        const uint32_t nib = (Ameta[tiled_idx_word(a, g, ks)] >> (4 * (g & 7))) & 15u;
                         const int p0 = nib & 3, p1 = nib >> 2;
-                        if (pos == p0) va = A[a * (K / 2) + 2 * g];
-                        else if (pos == p1) va = A[a * (K / 2) + 2 * g + 1];
+                        if (pos == p0) va = A[tiled_val_off(a, 2 * g, ks)];
+                        else if (pos == p1) va = A[tiled_val_off(a, 2 * g + 1, ks)];
                     } else {
                         va = A[a * K + gk];
                     }
@@ -342,34 +278,31 @@ k_gather_cols(const raw* __restrict__ in, int64_t T, int64_t ld, const int32_t* 
     }
 }
 
-template <bool SPARSE, bool FAST, int BM, int BN, int WAVES_M, int WAVES_N>
-int run_gemm_bf16_t(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
-                  int64_t ldb, void* C, int64_t ldc, hipStream_t s) {
-    using S = Smem<SPARSE, BM, BN>;
-    auto kern = k_gemm_bf16<SPARSE, FAST, BM, BN, WAVES_M, WAVES_N>;
+template <bool FAST, int BM, int BN, int WAVES_M, int WAVES_N>
+int run_dense_t(const void* A, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb, void* C,
+                int64_t ldc, hipStream_t s) {
+    using S = Smem<BM, BN>;
+    auto kern = k_gemm_dense_bf16<FAST, BM, BN, WAVES_M, WAVES_N>;
     if (S::kTotal > 48 * 1024) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 S::kTotal) != hipSuccess) return BIMASK_ERR_HIP;
     }
-    const int64_t lda = SPARSE ? K / 2 : K;
-    const bool vecA = aligned16(A) && (lda * 2) % 16 == 0;
+    const bool vecA = aligned16(A) && (K * 2) % 16 == 0;
     const bool vecB = aligned16(Bm) && (ldb * 2) % 16 == 0;
     const bool vecC = aligned16(C) && (ldc * 2) % 16 == 0;
     const int tiles_a = static_cast<int>(ceil_div(Adim, BM));
     const int64_t tiles_t = ceil_div(T, BN);
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(tiles_a * tiles_t)), dim3(kThreads), S::kTotal, s,
-                       static_cast<const uint16_t*>(A), meta, Adim, K, static_cast<const uint16_t*>(Bm), T, ldb,
+                       static_cast<const uint16_t*>(A), Adim, K, static_cast<const uint16_t*>(Bm), T, ldb,
                        static_cast<uint16_t*>(C), ldc, tiles_a, vecA, vecB, vecC);
     return check_launch();
 }
 
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N>
-int run_gemm_bf16(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
-                  int64_t ldb, void* C, int64_t ldc, hipStream_t s) {
-    const int64_t lda = SPARSE ? K / 2 : K;
-    const bool fast = K % BK == 0 && aligned16(A) && (lda * 2) % 16 == 0 && aligned16(Bm) && (ldb * 2) % 16 == 0;
-    if (fast) return run_gemm_bf16_t<SPARSE, true, BM, BN, WAVES_M, WAVES_N>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-    return run_gemm_bf16_t<SPARSE, false, BM, BN, WAVES_M, WAVES_N>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+int run_dense(const void* A, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb, void* C,
+              int64_t ldc, hipStream_t s) {
+    const bool fast = K % BK == 0 && aligned16(A) && aligned16(Bm) && (ldb * 2) % 16 == 0;
+    if (fast) return run_dense_t<true, 128, 128, 2, 2>(A, Adim, K, Bm, T, ldb, C, ldc, s);
+    return run_dense_t<false, 128, 128, 2, 2>(A, Adim, K, Bm, T, ldb, C, ldc, s);
 }
 
 }  // namespace
@@ -392,6 +325,11 @@ int launch_gather_cols(const void* dY, int64_t T, int64_t ld, const int32_t* per
     return check_launch();
 }
 
+bool gemm_bwd_needs_gather(int64_t I, int dtype, int N, int M) {
+    static const int resvar = [] { const char* e = getenv("BIMASK_RES_VARIANT"); return e ? atoi(e) : 0; }();
+    return !(dtype == BIMASK_BF16 && N == 2 && M == 4 && I <= 512 && resvar >= 0);
+}
+
 int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int64_t K, bool sparse24,
                 const void* Bm, int64_t T, int64_t ldb, void* C, int64_t ldc, int dtype, hipStream_t s) {
     if (dtype == BIMASK_F32) {
@@ -405,16 +343,17 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
         return check_launch();
     }
     if (sparse24) {
-        // tuning hook: BIMASK_GEMM_VARIANT picks a tile shape / prefetch depth of the streaming kernel
-        static const int forced = [] { const char* e = getenv("BIMASK_GEMM_VARIANT"); return e ? atoi(e) : -2; }();
-        const int variant = forced != -2 ? forced : (K <= 256 ? 3 : 0);   // short contractions: shallow prefetch
-        if (variant >= 0) {
-            const int rc = launch_gemm_sp24(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, variant, s);
+        // tuning hooks: tile shape / prefetch depth of the streaming kernel, wave count of the resident one
+        static const int forced = [] { const char* e = getenv("BIMASK_GEMM_VARIANT"); return e ? atoi(e) : -1; }();
+        static const int resvar = [] { const char* e = getenv("BIMASK_RES_VARIANT"); return e ? atoi(e) : 0; }();
+        if (K <= 512 && resvar >= 0) {
+            const int rc = launch_gemm_sp24_resident(A_values, A_index, Adim, K, Bm, ldb, nullptr, T, C, ldc, resvar, s);
             if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
         }
-        return run_gemm_bf16<true, 128, 128, 2, 2>(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, s);
+        const int variant = forced >= 0 ? forced : 0;
+        return launch_gemm_sp24(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, variant, s);
     }
-    return run_gemm_bf16<false, 128, 128, 2, 2>(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, s);
+    return run_dense(A_values, Adim, K, Bm, T, ldb, C, ldc, s);
 }
 
 }  // namespace bimask

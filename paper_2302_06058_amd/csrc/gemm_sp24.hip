@@ -3,10 +3,11 @@
 // arXiv 2302.06058).
 //
 // Design (one stage = 128 dense k):
-//   * the compressed weight rows never touch LDS: every lane of a 32x32x32 sparse matrix
-//     instruction owns one weight row and one half of the stage, which is 64 contiguous
-//     bytes of values + 8 contiguous bytes of indices in memory, so the A fragments are
-//     loaded straight from global memory (L2-resident) into the operand registers;
+//   * the compressed weights never touch LDS: they are stored fragment-major (see
+//     include/bimask.h), i.e. the 16 bytes of values lane l needs for instruction s of a
+//     stage sit at [row tile][stage][s][l], so a wavefront fetches each A operand as one
+//     fully contiguous 1 KB load (and its indices as one 512-byte load) straight into the
+//     operand registers;
 //   * the token operand is loaded 256 bytes per row with 16-byte lanes, staged through a
 //     double-buffered XOR-swizzled LDS tile and read back as 16-byte fragments;
 //   * PF stages of both operands are kept in flight in registers, so a workgroup has
@@ -48,18 +49,35 @@ struct SpSmem {
     static constexpr int kTotal = (2 * kStage > kC) ? 2 * kStage : kC;
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int PF>
-__global__ void __launch_bounds__(kThreads)
+// 8 consecutive bf16 of a token row starting at element k, zero beyond kend; 4-byte loads
+// only (rows that are not 16-byte aligned, or the ragged last stage).
+__device__ __forceinline__ u32x4 load_guarded(const uint16_t* row, int64_t k, int64_t kend) {
+    u32x4 r = {0u, 0u, 0u, 0u};
+    if (k + 8 <= kend) {
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(row + k);
+        r.x = p[0]; r.y = p[1]; r.z = p[2]; r.w = p[3];
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (k + e < kend) r[e >> 1] |= static_cast<uint32_t>(row[k + e]) << (16 * (e & 1));
+    }
+    return r;
+}
+
+// BGUARD: token rows are not 16-byte aligned or K is not a multiple of 128; every token
+// load is then bounds-checked against K (the weight operand is zero-padded by its format).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int64_t K,
             const uint16_t* __restrict__ Bm, int64_t T, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
             int tiles_a, bool vecC) {
-    static_assert(WAVES_M * WAVES_N == kThreads / 64, "four wavefronts");
+    constexpr int NT = 64 * WAVES_M * WAVES_N;          // threads per workgroup
     using S = SpSmem<BM, BN>;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int NBUF = PF + 1;
-    constexpr int NB_ = BN * 16 / kThreads;             // 16-byte granules of Bm per thread per stage
-    static_assert(NB_ >= 1 && (BN * 16) % kThreads == 0, "token tile too small");
+    constexpr int NB_ = BN * 16 / NT;                   // 16-byte granules of Bm per thread per stage
+    static_assert(NB_ >= 1 && (BN * 16) % NT == 0, "token tile too small");
     extern __shared__ u32x4 smem_u4[];
     uint8_t* smem = reinterpret_cast<uint8_t*>(smem_u4);
 
@@ -68,27 +86,31 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
     const int l32 = lane & 31, h = lane >> 5;
     const int64_t a0 = static_cast<int64_t>(blockIdx.x % tiles_a) * BM;
     const int64_t t0 = static_cast<int64_t>(blockIdx.x / tiles_a) * BN;
-    const int64_t lda = K / 2, wprA = K / 32;
-    const int nk = static_cast<int>(K / SK);
+    const int nk = static_cast<int>(ceil_div(K, SK));   // = stages of the padded weight operand
+    // Workgroups walk the contraction in rotated order: at any instant they touch different
+    // k offsets, which spreads the concurrent token-row reads (same row pitch for everyone)
+    // over all memory channels and the weight reads over all L2 lines.
+    const int koff = static_cast<int>((blockIdx.x / tiles_a) % nk);
+    const int64_t rt_last = ceil_div(Adim, 32) - 1;
 
-    // per-lane source pointers (rows clamped at the edges: loaded, never stored)
+    // per-lane source pointers (row tiles / rows clamped at the edges: loaded, never stored)
     const uint16_t* pa[TM];
     const uint32_t* pm[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        int64_t a = a0 + wm * WM + i * 32 + l32;
-        a = a < Adim ? a : Adim - 1;
-        pa[i] = A + a * lda + 32 * h;
-        pm[i] = Ameta + a * wprA + 2 * h;
+        int64_t rt = (a0 + wm * WM + i * 32) >> 5;
+        rt = rt < rt_last ? rt : rt_last;
+        pa[i] = A + (rt * nk * 256 + lane) * 8;
+        pm[i] = Ameta + (rt * nk * 64 + lane) * 2;
     }
     const uint16_t* pb[NB_];
     int sb_off[NB_];
 #pragma unroll
     for (int it = 0; it < NB_; ++it) {
-        const int q = tid + kThreads * it, row = q >> 4, g = q & 15;
+        const int q = tid + NT * it, row = q >> 4, g = q & 15;
         int64_t t = t0 + row;
         t = t < T ? t : T - 1;
-        pb[it] = Bm + t * ldb + 8 * g;
+        pb[it] = Bm + t * ldb + (BGUARD ? 0 : 8 * g);
         sb_off[it] = row * kRowBytes + ((g ^ (row & 15)) << 4);
     }
 
@@ -106,59 +128,75 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
 
 #define BIMASK_LOAD_STAGE(slot, kt)                                                              \
     {                                                                                            \
-        const int64_t kk = static_cast<int64_t>(kt) * SK;                                        \
-        _Pragma("unroll") for (int it = 0; it < NB_; ++it)                                       \
-            rb[slot][it] = *reinterpret_cast<const u32x4*>(pb[it] + kk);                         \
+        const int64_t kk = static_cast<int64_t>(((kt) + koff) % nk) * SK;                        \
+        _Pragma("unroll") for (int it = 0; it < NB_; ++it) {                                     \
+            if constexpr (BGUARD)                                                                \
+                rb[slot][it] = load_guarded(pb[it], kk + 8 * ((tid + NT * it) & 15), K);        \
+            else                                                                                 \
+                rb[slot][it] = *reinterpret_cast<const u32x4*>(pb[it] + kk);                     \
+        }                                                                                        \
         _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                         \
             _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                     \
-                ra[slot][i][s4] = *reinterpret_cast<const u32x4*>(pa[i] + kk / 2 + 8 * s4);      \
-            rmeta[slot][i] = *reinterpret_cast<const u32x2*>(pm[i] + kk / 32);                   \
+                ra[slot][i][s4] = *reinterpret_cast<const u32x4*>(pa[i] + (kk * 4 + s4 * SK) * 4); \
+            rmeta[slot][i] = *reinterpret_cast<const u32x2*>(pm[i] + kk);                        \
+        }                                                                                        \
+    }
+
+    // One pipeline step: stage kt leaves its registers for LDS / the matrix cores while stage
+    // kt+PF is requested.  Kept free of control flow (loads past the end are clamped to the
+    // last stage, never skipped) so that the outstanding-load bookkeeping stays exact and a
+    // step only ever waits for the stage it consumes.
+#define BIMASK_STEP(u, kt, DO_LOAD)                                                              \
+    {                                                                                            \
+        uint8_t* sB = smem + ((kt) & 1) * S::kStage;                                             \
+        _Pragma("unroll") for (int it = 0; it < NB_; ++it)                                       \
+            *reinterpret_cast<u32x4*>(sB + sb_off[it]) = rb[u][it];                              \
+        if (DO_LOAD) {                                                                           \
+            const int ktl = (kt) + PF < nk ? (kt) + PF : nk - 1;                                 \
+            BIMASK_LOAD_STAGE(((u) + PF) % NBUF, ktl)                                            \
+        }                                                                                        \
+        __syncthreads();                                                                         \
+        _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) {                                       \
+            BFrag bf[TN];                                                                        \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                     \
+                const int row = wn * WN + j * 32 + l32;                                          \
+                const uint8_t* base = sB + row * kRowBytes;                                      \
+                const int g1 = 2 * s4 + h, g2 = 8 + 2 * s4 + h;                                  \
+                bf[j].q[0] = *reinterpret_cast<const u32x4*>(base + ((g1 ^ (row & 15)) << 4));   \
+                bf[j].q[1] = *reinterpret_cast<const u32x4*>(base + ((g2 ^ (row & 15)) << 4));   \
+            }                                                                                    \
+            _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                     \
+                AFrag af;                                                                        \
+                af.q = ra[u][i][s4];                                                             \
+                const int idx = static_cast<int>(s4 < 2 ? rmeta[u][i].x : rmeta[u][i].y);        \
+                _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                 \
+                    if (s4 & 1)                                                                  \
+                        acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[j].v, acc[i][j], idx, 0, 1); \
+                    else                                                                         \
+                        acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[j].v, acc[i][j], idx, 0, 0); \
+                }                                                                                \
+            }                                                                                    \
         }                                                                                        \
     }
 
 #pragma unroll
-    for (int s = 0; s < PF; ++s)
-        if (s < nk) BIMASK_LOAD_STAGE(s, s)
-
-#pragma unroll 1
-    for (int kt0 = 0; kt0 < nk; kt0 += NBUF) {
-#pragma unroll
-        for (int u = 0; u < NBUF; ++u) {
-            const int kt = kt0 + u;
-            if (kt < nk) {
-                uint8_t* sB = smem + (kt & 1) * S::kStage;
-#pragma unroll
-                for (int it = 0; it < NB_; ++it) *reinterpret_cast<u32x4*>(sB + sb_off[it]) = rb[u][it];
-                if (kt + PF < nk) BIMASK_LOAD_STAGE((u + PF) % NBUF, kt + PF)
-                __syncthreads();
-#pragma unroll
-                for (int s4 = 0; s4 < 4; ++s4) {
-                    BFrag bf[TN];
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        const int row = wn * WN + j * 32 + l32;
-                        const uint8_t* base = sB + row * kRowBytes;
-                        const int g1 = 2 * s4 + h, g2 = 8 + 2 * s4 + h;
-                        bf[j].q[0] = *reinterpret_cast<const u32x4*>(base + ((g1 ^ (row & 15)) << 4));
-                        bf[j].q[1] = *reinterpret_cast<const u32x4*>(base + ((g2 ^ (row & 15)) << 4));
-                    }
-#pragma unroll
-                    for (int i = 0; i < TM; ++i) {
-                        AFrag af;
-                        af.q = ra[u][i][s4];
-                        const int idx = static_cast<int>(s4 < 2 ? rmeta[u][i].x : rmeta[u][i].y);
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) {
-                            if (s4 & 1)
-                                acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[j].v, acc[i][j], idx, 0, 1);
-                            else
-                                acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[j].v, acc[i][j], idx, 0, 0);
-                        }
-                    }
-                }
-            }
-        }
+    for (int s = 0; s < PF; ++s) {
+        const int ktl = s < nk ? s : nk - 1;
+        BIMASK_LOAD_STAGE(s, ktl)
     }
+
+    int kt0 = 0;
+#pragma unroll 1
+    for (; kt0 + NBUF <= nk; kt0 += NBUF) {
+#pragma unroll
+        for (int u = 0; u < NBUF; ++u) BIMASK_STEP(u, kt0 + u, true)
+    }
+    // fewer than NBUF stages remain: everything they need is already in flight
+#pragma unroll
+    for (int u = 0; u < NBUF - 1; ++u) {
+        if (kt0 + u < nk) BIMASK_STEP(u, kt0 + u, false)
+    }
+#undef BIMASK_STEP
 #undef BIMASK_LOAD_STAGE
 
     // Epilogue: accumulators -> bf16 tile [t][a] in LDS -> 16-byte row-contiguous stores.
@@ -180,7 +218,7 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
         }
     __syncthreads();
     constexpr int GPR = BM / 8;                          // 16-byte granules per output row
-    for (int q = tid; q < BN * GPR; q += kThreads) {
+    for (int q = tid; q < BN * GPR; q += NT) {
         const int row = q / GPR, g = q % GPR;
         const int64_t t = t0 + row, a = a0 + 8 * g;
         if (t >= T || a >= Adim) continue;
@@ -196,11 +234,11 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int PF>
-int run_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb,
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD>
+int run_sp24_t(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb,
              void* C, int64_t ldc, hipStream_t s) {
     using S = SpSmem<BM, BN>;
-    auto kern = k_gemm_sp24<BM, BN, WAVES_M, WAVES_N, PF>;
+    auto kern = k_gemm_sp24<BM, BN, WAVES_M, WAVES_N, PF, BGUARD>;
     if (S::kTotal > 48 * 1024) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 S::kTotal) != hipSuccess) return BIMASK_ERR_HIP;
@@ -208,27 +246,39 @@ int run_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const
     const bool vecC = aligned16(C) && (ldc * 2) % 16 == 0;
     const int tiles_a = static_cast<int>(ceil_div(Adim, BM));
     const int64_t tiles_t = ceil_div(T, BN);
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(tiles_a * tiles_t)), dim3(kThreads), S::kTotal, s,
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(tiles_a * tiles_t)), dim3(64 * WAVES_M * WAVES_N), S::kTotal, s,
                        static_cast<const uint16_t*>(A), meta, Adim, K, static_cast<const uint16_t*>(Bm), T, ldb,
                        static_cast<uint16_t*>(C), ldc, tiles_a, vecC);
     return check_launch();
 }
 
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF>
+int run_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb,
+             void* C, int64_t ldc, hipStream_t s) {
+    const bool fastb = K % SK == 0 && aligned16(Bm) && (ldb * 2) % 16 == 0;
+    if (fastb) return run_sp24_t<BM, BN, WAVES_M, WAVES_N, PF, false>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+    return run_sp24_t<BM, BN, WAVES_M, WAVES_N, 1, true>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+}
+
 }  // namespace
 
-// Streaming 2:4 GEMM; returns BIMASK_ERR_UNSUPPORTED when the shape needs the generic kernel.
+// 2:4 GEMM on the fragment-major weight operand.  `variant` picks tile shape / prefetch depth.
 int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
                      int64_t ldb, void* C, int64_t ldc, int variant, hipStream_t s) {
-    const bool ok = K % SK == 0 && aligned16(A) && aligned16(Bm) && (ldb * 2) % 16 == 0 &&
-                    (reinterpret_cast<uintptr_t>(meta) & 7u) == 0;
-    if (!ok) return BIMASK_ERR_UNSUPPORTED;
+    if (!aligned16(A) || !aligned16(meta)) return BIMASK_ERR_ALIGN;
     switch (variant) {
         case 0: return run_sp24<256, 64, 4, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 1: return run_sp24<256, 64, 4, 1, 3>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 1: return run_sp24<256, 64, 2, 2, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
         case 2: return run_sp24<128, 128, 2, 2, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
         case 3: return run_sp24<256, 64, 4, 1, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
         case 4: return run_sp24<128, 64, 4, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
         case 5: return run_sp24<256, 128, 2, 2, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 6: return run_sp24<128, 64, 2, 2, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 7: return run_sp24<256, 64, 2, 2, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 8: return run_sp24<256, 64, 8, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 9: return run_sp24<256, 64, 8, 1, 3>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 10: return run_sp24<256, 32, 8, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 11: return run_sp24<128, 64, 4, 1, 3>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
         default: return BIMASK_ERR_UNSUPPORTED;
     }
 }

@@ -1,0 +1,249 @@
+// 2:4-sparse bf16 GEMM for short contractions (K <= 512), resident-token variant:
+//     C[t][a] = sum_k Bsrc[t][perm[k]] * A[a][k]
+// This is the backward product of Eq. (10) of arXiv 2302.06058 for layers with few output
+// features: k runs over the permuted out-feature index r, Bsrc = g(Y), perm = P.
+//
+// A workgroup owns a tile of tokens.  It loads that tile of g(Y) ONCE, full rows (contiguous
+// 16-byte lanes), and scatters the elements through the inverse permutation into an
+// XOR-swizzled LDS tile, so the column permutation of Eq. (10) costs no extra pass over
+// memory.  It then walks over ALL weight-row tiles: the fragment-major compressed weights
+// stream from L2 straight into the sparse matrix instruction's A registers (prefetched one
+// weight tile ahead), the token fragments come from the resident LDS tile, and every
+// finished 256-wide output strip leaves through LDS as 16-byte row-contiguous stores.
+// Token tiles have a run-time height (<= BN) so that the grid can be cut to the CU count.
+#include "common.hpp"
+
+namespace bimask {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(__bf16)))) __bf16 bf16x16;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+union BFragR { bf16x16 v; u32x4 q[2]; };
+union AFragR { bf16x8 v; u32x4 q; };
+
+__device__ __forceinline__ uint32_t to_bf16r(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+template <int BM, int BN, int NSTG>
+struct ResSmem {
+    static constexpr int kB = NSTG * BN * 256;          // resident token tile, 256 B per row and stage
+    static constexpr int kCRow = BM * 2 + 16;
+    static constexpr int kC = BN * kCRow;
+    static constexpr int kInv = NSTG * 128 * 2;         // inverse permutation (int16)
+    static constexpr int kTotal = kB + kC + kInv;
+};
+
+// byte offset of element (t, r) of the resident tile
+template <int BN>
+__device__ __forceinline__ int resb_off(int t, int r) {
+    return (r >> 7) * (BN * 256) + t * 256 + (((((r & 127) >> 3) ^ (t & 15))) << 4) + (r & 7) * 2;
+}
+
+template <int BM, int BN, int WAVES_M, int NSTG>
+__global__ void __launch_bounds__(64 * WAVES_M)
+k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int64_t K,
+                     const uint16_t* __restrict__ Bsrc, int64_t ldb, const int32_t* __restrict__ perm, int64_t T,
+                     uint16_t* __restrict__ C, int64_t ldc, int rpt, bool vecB, bool vecC) {
+    constexpr int NT = 64 * WAVES_M;
+    using S = ResSmem<BM, BN, NSTG>;
+    constexpr int WM = BM / WAVES_M, TM = WM / 32, TN = BN / 32;
+    extern __shared__ u32x4 smem_u4[];
+    uint8_t* sB = reinterpret_cast<uint8_t*>(smem_u4);
+    uint8_t* sC = sB + S::kB;
+    int16_t* sInv = reinterpret_cast<int16_t*>(sC + S::kC);
+
+    const int tid = threadIdx.x, lane = tid & 63, wm = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * rpt;
+    const int rows = static_cast<int>((T - t0) < rpt ? (T - t0) : rpt);
+    const int tiles_a = static_cast<int>(ceil_div(Adim, BM));
+    const int64_t rt_last = ceil_div(Adim, 32) - 1;
+
+    // ---- weight fragments of one weight tile: NSTG stages x TM row tiles
+    u32x4 ra[2][NSTG][TM][4];
+    u32x2 rmeta[2][NSTG][TM];
+#define BIMASK_LOAD_WTILE(set, at)                                                               \
+    {                                                                                            \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                         \
+            int64_t rt = (static_cast<int64_t>(at) * BM + wm * WM + i * 32) >> 5;                \
+            rt = rt < rt_last ? rt : rt_last;                                                    \
+            const uint16_t* pa = A + (rt * NSTG * 256 + lane) * 8;                               \
+            const uint32_t* pm = Ameta + (rt * NSTG * 64 + lane) * 2;                            \
+            _Pragma("unroll") for (int st = 0; st < NSTG; ++st) {                                \
+                _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                 \
+                    ra[set][st][i][s4] = *reinterpret_cast<const u32x4*>(pa + (st * 4 + s4) * 512); \
+                rmeta[set][st][i] = *reinterpret_cast<const u32x2*>(pm + st * 128);              \
+            }                                                                                    \
+        }                                                                                        \
+    }
+    BIMASK_LOAD_WTILE(0, 0)
+
+    // ---- resident token tile: zero, (inverse permutation), fill
+    for (int it = tid; it < S::kB / 16; it += NT) reinterpret_cast<u32x4*>(sB)[it] = (u32x4){0u, 0u, 0u, 0u};
+    if (perm) {
+        for (int r = tid; r < static_cast<int>(K); r += NT) sInv[perm[r]] = static_cast<int16_t>(r);
+    }
+    __syncthreads();
+    {
+        const int G = static_cast<int>((K + 7) >> 3);    // 8-element granules per token row
+        for (int q = tid; q < rows * G; q += NT) {
+            const int t = q / G, g = q - t * G;
+            const uint16_t* src = Bsrc + (t0 + t) * ldb + 8 * g;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (8 * g + 8 <= K) {
+                if (vecB) v = *reinterpret_cast<const u32x4*>(src);
+                else { const uint32_t* p = reinterpret_cast<const uint32_t*>(src); v.x = p[0]; v.y = p[1]; v.z = p[2]; v.w = p[3]; }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (8 * g + e < K) v[e >> 1] |= static_cast<uint32_t>(src[e]) << (16 * (e & 1));
+            }
+            if (perm) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int i = 8 * g + e;
+                    if (i < K)
+                        *reinterpret_cast<uint16_t*>(sB + resb_off<BN>(t, sInv[i])) =
+                            static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1)));
+                }
+            } else {
+                *reinterpret_cast<u32x4*>(sB + resb_off<BN>(t, 8 * g)) = v;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- one weight tile: NSTG x 4 sparse matrix instructions per (row tile, token tile)
+#define BIMASK_WTILE(set, at)                                                                    \
+    {                                                                                            \
+        f32x16 acc[TM][TN];                                                                      \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                       \
+                _Pragma("unroll") for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;               \
+        _Pragma("unroll") for (int st = 0; st < NSTG; ++st) {                                    \
+            _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) {                                   \
+                BFragR bf[TN];                                                                   \
+                _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                 \
+                    const int row = j * 32 + l32;                                                \
+                    const uint8_t* base = sB + st * (BN * 256) + row * 256;                      \
+                    bf[j].q[0] = *reinterpret_cast<const u32x4*>(base + (((2 * s4 + h) ^ (row & 15)) << 4));     \
+                    bf[j].q[1] = *reinterpret_cast<const u32x4*>(base + (((8 + 2 * s4 + h) ^ (row & 15)) << 4)); \
+                }                                                                                \
+                _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                 \
+                    AFragR af;                                                                   \
+                    af.q = ra[set][st][i][s4];                                                   \
+                    const int idx = static_cast<int>(s4 < 2 ? rmeta[set][st][i].x : rmeta[set][st][i].y); \
+                    _Pragma("unroll") for (int j = 0; j < TN; ++j) {                             \
+                        if (s4 & 1)                                                              \
+                            acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[j].v, acc[i][j], idx, 0, 1); \
+                        else                                                                     \
+                            acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[j].v, acc[i][j], idx, 0, 0); \
+                    }                                                                            \
+                }                                                                                \
+            }                                                                                    \
+        }                                                                                        \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                     \
+                const int t = j * 32 + l32;                                                      \
+                _Pragma("unroll") for (int qq = 0; qq < 4; ++qq) {                               \
+                    const int a = wm * WM + i * 32 + 8 * qq + 4 * h;                             \
+                    u32x2 v;                                                                     \
+                    v.x = to_bf16r(acc[i][j][4 * qq + 0]) | (to_bf16r(acc[i][j][4 * qq + 1]) << 16); \
+                    v.y = to_bf16r(acc[i][j][4 * qq + 2]) | (to_bf16r(acc[i][j][4 * qq + 3]) << 16); \
+                    *reinterpret_cast<u32x2*>(sC + t * S::kCRow + a * 2) = v;                    \
+                }                                                                                \
+            }                                                                                    \
+        __syncthreads();                                                                         \
+        {                                                                                        \
+            constexpr int GPR = BM / 8;                                                          \
+            const int64_t a0 = static_cast<int64_t>(at) * BM;                                    \
+            for (int q = tid; q < rows * GPR; q += NT) {                                         \
+                const int row = q / GPR, g = q % GPR;                                            \
+                const int64_t a = a0 + 8 * g;                                                    \
+                if (a >= Adim) continue;                                                         \
+                const u32x4 v = *reinterpret_cast<const u32x4*>(sC + row * S::kCRow + g * 16);   \
+                uint16_t* dst = C + (t0 + row) * ldc + a;                                        \
+                if (vecC && a + 8 <= Adim) {                                                     \
+                    *reinterpret_cast<u32x4*>(dst) = v;                                          \
+                } else {                                                                         \
+                    _Pragma("unroll") for (int e = 0; e < 8; ++e)                                \
+                        if (a + e < Adim) dst[e] = static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1))); \
+                }                                                                                \
+            }                                                                                    \
+        }                                                                                        \
+        __syncthreads();                                                                         \
+    }
+
+    int at = 0;
+#pragma unroll 1
+    for (; at + 2 <= tiles_a; at += 2) {
+        BIMASK_LOAD_WTILE(1, at + 1)
+        BIMASK_WTILE(0, at)
+        { const int nx = at + 2 < tiles_a ? at + 2 : tiles_a - 1; BIMASK_LOAD_WTILE(0, nx) }
+        BIMASK_WTILE(1, at + 1)
+    }
+    if (at < tiles_a) BIMASK_WTILE(0, at)
+#undef BIMASK_WTILE
+#undef BIMASK_LOAD_WTILE
+}
+
+template <int BM, int BN, int WAVES_M, int NSTG>
+int run_resident(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc, int64_t ldb,
+                 const int32_t* perm, int64_t T, void* C, int64_t ldc, int rpt, hipStream_t s) {
+    using S = ResSmem<BM, BN, NSTG>;
+    auto kern = k_gemm_sp24_resident<BM, BN, WAVES_M, NSTG>;
+    if (S::kTotal > 48 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                S::kTotal) != hipSuccess) return BIMASK_ERR_HIP;
+    }
+    const bool vecB = aligned16(Bsrc) && (ldb * 2) % 16 == 0;
+    const bool vecC = aligned16(C) && (ldc * 2) % 16 == 0;
+    const unsigned grid = static_cast<unsigned>(ceil_div(T, rpt));
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WAVES_M), S::kTotal, s, static_cast<const uint16_t*>(A), meta,
+                       Adim, K, static_cast<const uint16_t*>(Bsrc), ldb, perm, T, static_cast<uint16_t*>(C), ldc,
+                       rpt, vecB, vecC);
+    return check_launch();
+}
+
+}  // namespace
+
+// Rows per token tile: as close to BN as possible while the grid is a whole number of
+// waves of `cus` workgroups (every CU gets the same share of the output).
+static int pick_rows_per_tile(int64_t T, int bn, int cus) {
+    const int64_t tiles_min = ceil_div(T, bn);
+    const int64_t tiles = ceil_div(tiles_min, cus) * cus;
+    int64_t rpt = ceil_div(T, tiles);
+    if (rpt < 32) rpt = T < 32 ? T : 32;                // do not starve the 32-wide matrix tiles
+    if (rpt > bn) rpt = bn;
+    return static_cast<int>(rpt);
+}
+
+// Short-contraction 2:4 GEMM with the token tile resident in LDS and an optional fused
+// column gather.  Returns BIMASK_ERR_UNSUPPORTED when K is too long for this kernel.
+int launch_gemm_sp24_resident(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc,
+                              int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, int variant,
+                              hipStream_t s) {
+    if (K > 512) return BIMASK_ERR_UNSUPPORTED;
+    if (!aligned16(A) || !aligned16(meta)) return BIMASK_ERR_ALIGN;
+    const int nstg = static_cast<int>(ceil_div(K, 128));
+    const int rpt = pick_rows_per_tile(T, 64, 256);
+#define BIMASK_RES(WAVES) \
+    switch (nstg) { \
+        case 1: return run_resident<256, 64, WAVES, 1>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s); \
+        case 2: return run_resident<256, 64, WAVES, 2>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s); \
+        case 3: return run_resident<256, 64, WAVES, 3>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s); \
+        default: return run_resident<256, 64, WAVES, 4>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s); \
+    }
+    if (variant == 1) { BIMASK_RES(8) }
+    BIMASK_RES(4)
+#undef BIMASK_RES
+}
+
+}  // namespace bimask

@@ -60,26 +60,32 @@ __global__ void __launch_bounds__(kThreads)
 k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t ldw, int N,
           const uint32_t* __restrict__ mask_in, uint32_t* __restrict__ B_bits,
           typename DT::raw* __restrict__ values, uint32_t* __restrict__ index, int mode,
-          int wpr, int cpr, bool vec_in, bool vec_out) {
+          int wpr, int cpr, int64_t rows_pad, bool vec_in, bool vec_out) {
     using raw = typename DT::raw;
     constexpr int NV = CH / 8;                 // 8-element vectors per chunk
     constexpr int PW = Pack<DT>::kWords;
     const int64_t id = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (id >= I * cpr) return;
+    if (id >= rows_pad * cpr) return;
     const int64_t i = id / cpr;
     const int c = static_cast<int>(id - i * cpr);
     const int64_t j0 = static_cast<int64_t>(c) * CH;
-    const raw* row = W + i * ldw;
+    // mode 1 also covers the zero padding of the fragment-major operand (rows >= I, cols >= J)
+    const bool in_row = i < I;
+    const bool in_mask = in_row && c < wpr * (32 / CH);
+    const raw* row = W + (in_row ? i : 0) * ldw;
+    const int64_t Jr = in_row ? J : 0;         // padding rows read nothing
 
     uint32_t w[NV][PW];
 #pragma unroll
-    for (int v = 0; v < NV; ++v) load8<DT>(row, j0 + 8 * v, J, vec_in, w[v]);
+    for (int v = 0; v < NV; ++v) load8<DT>(row, j0 + 8 * v, Jr, vec_in, w[v]);
 
     // mask bits of this chunk
     uint32_t bits = 0;
     if (mask_in) {
-        if constexpr (CH == 8) bits = reinterpret_cast<const uint8_t*>(mask_in)[i * wpr * 4 + c];
-        else bits = reinterpret_cast<const uint16_t*>(mask_in)[i * wpr * 2 + c];
+        if (in_mask) {
+            if constexpr (CH == 8) bits = reinterpret_cast<const uint8_t*>(mask_in)[i * wpr * 4 + c];
+            else bits = reinterpret_cast<const uint16_t*>(mask_in)[i * wpr * 2 + c];
+        }
     } else {
 #pragma unroll
         for (int g = 0; g < CH / M; ++g) {
@@ -89,11 +95,11 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
                 const int e = g * M + m;
                 key[m] = elem<DT>(w[e / 8], e % 8) & DT::kAbs;
             }
-            const uint32_t sel = (j0 + g * M < J) ? select_top_n<M>(key, N) : 0u;
+            const uint32_t sel = (j0 + g * M < Jr) ? select_top_n<M>(key, N) : 0u;
             bits |= sel << (g * M);
         }
     }
-    if (B_bits) {
+    if (B_bits && in_mask) {
         if constexpr (CH == 8) reinterpret_cast<uint8_t*>(B_bits)[i * wpr * 4 + c] = static_cast<uint8_t>(bits);
         else reinterpret_cast<uint16_t*>(B_bits)[i * wpr * 2 + c] = static_cast<uint16_t>(bits);
     }
@@ -102,7 +108,6 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
         if constexpr (M == 4 && CH == 8) {
             raw out[4];
             uint32_t nibs = 0;
-            const bool full = j0 + 8 <= J;
 #pragma unroll
             for (int g = 0; g < 2; ++g) {
                 const uint32_t mb = (bits >> (4 * g)) & 15u;
@@ -112,10 +117,12 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
                                e2 = elem<DT>(w[0], 4 * g + 2), e3 = elem<DT>(w[0], 4 * g + 3);
                 out[2 * g + 0] = static_cast<raw>(((mb >> p0) & 1u) ? pick4(e0, e1, e2, e3, p0) : 0u);
                 out[2 * g + 1] = static_cast<raw>(((mb >> p1) & 1u) ? pick4(e0, e1, e2, e3, p1) : 0u);
-                if (j0 + 4 * g < J) nibs |= static_cast<uint32_t>(p0 | (p1 << 2)) << (4 * g);
+                if (j0 + 4 * g < Jr) nibs |= static_cast<uint32_t>(p0 | (p1 << 2)) << (4 * g);
             }
-            raw* dst = values + i * (J / 2) + j0 / 2;
-            if (full && vec_out) {
+            // four consecutive slots of one lane vector of the fragment-major layout
+            const int64_t ks = static_cast<int64_t>(cpr) / 16;
+            raw* dst = values + tiled_val_off(i, j0 / 2, ks);
+            if (vec_out) {
                 if constexpr (sizeof(raw) == 2) {
                     uint2 v; v.x = out[0] | (static_cast<uint32_t>(out[1]) << 16); v.y = out[2] | (static_cast<uint32_t>(out[3]) << 16);
                     *reinterpret_cast<uint2*>(dst) = v;
@@ -125,10 +132,10 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
                 }
             } else {
 #pragma unroll
-                for (int g = 0; g < 2; ++g)
-                    if (j0 + 4 * g < J) { dst[2 * g] = out[2 * g]; dst[2 * g + 1] = out[2 * g + 1]; }
+                for (int e = 0; e < 4; ++e) dst[e] = out[e];
             }
-            reinterpret_cast<uint8_t*>(index)[i * wpr * 4 + c] = static_cast<uint8_t>(nibs);
+            const int64_t g0 = j0 / 4;
+            reinterpret_cast<uint8_t*>(index)[tiled_idx_word(i, g0, ks) * 4 + ((g0 & 7) >> 1)] = static_cast<uint8_t>(nibs);
         }
     } else if (mode == 2) {
         raw* dst = values + i * J + j0;
@@ -167,7 +174,7 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
 // ---------------------------------------------------------------------------------
 constexpr int kTR = 128, kTC = 128;
 
-template <typename DT> __host__ __device__ constexpr int lds_stride_m1() { return 64 + 16 / (int)sizeof(typename DT::raw); }
+constexpr int kImgElems = 4 * 4 * 64 * 8;             // mode 1: fragment-major image of 128 rows x 64 slots
 template <typename DT> __host__ __device__ constexpr int lds_stride_m2() { return kTR + 16 / (int)sizeof(typename DT::raw); }
 
 template <typename DT, int M>
@@ -182,13 +189,19 @@ k_backward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t
     constexpr int NB = kTR / M;                         // row blocks per tile
     extern __shared__ uint4 lds_u4[];
     raw* lds_val = reinterpret_cast<raw*>(lds_u4);
-    constexpr int S1 = lds_stride_m1<DT>(), S2 = lds_stride_m2<DT>();
-    uint8_t* lds_meta = reinterpret_cast<uint8_t*>(lds_val + kTC * S1);   // mode 1 only: [kTC][32]
+    constexpr int S2 = lds_stride_m2<DT>();
+    uint8_t* lds_meta = reinterpret_cast<uint8_t*>(lds_val + kImgElems);  // mode 1 only: [kTC][32] nibbles
 
     const int64_t r0 = static_cast<int64_t>(blockIdx.y) * kTR;
     const int64_t c0 = static_cast<int64_t>(blockIdx.x) * kTC;
     const int ch = threadIdx.x & 15;
     const int64_t j0 = c0 + ch * 8;
+
+    if (mode == 1) {                                    // padding of the operand image is zero
+        constexpr int kZeroWords = (kImgElems * (int)sizeof(raw) + kTC * 32) / 16;
+        for (int it = threadIdx.x; it < kZeroWords; it += kThreads) lds_u4[it] = make_uint4(0, 0, 0, 0);
+        __syncthreads();
+    }
 
     for (int kb = threadIdx.x >> 4; kb < NB; kb += kThreads / 16) {
         const int64_t rb = r0 + static_cast<int64_t>(kb) * M;
@@ -231,13 +244,16 @@ k_backward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t
 #pragma unroll
             for (int m = 0; m < M; ++m) ob[m] |= ((keep >> m) & 1u) << q;
             const int col = ch * 8 + q;
+            if (c0 + col >= J) continue;                 // ragged last chunk: not a row of the operand
             if (mode == 1) {
                 if constexpr (M == 4) {
                     const int p0 = __builtin_ctz(sel), p1 = 31 - __builtin_clz(sel);
                     const uint32_t e0 = elem<DT>(w[0], q), e1 = elem<DT>(w[1], q), e2 = elem<DT>(w[2], q), e3 = elem<DT>(w[3], q);
                     const uint32_t v0 = ((keep >> p0) & 1u) ? pick4(e0, e1, e2, e3, p0) : 0u;
                     const uint32_t v1 = ((keep >> p1) & 1u) ? pick4(e0, e1, e2, e3, p1) : 0u;
-                    raw* d = lds_val + col * S1 + kb * 2;
+                    // output row = this column, slots 2kb, 2kb+1 of the stage: lane half kb/16,
+                    // instruction (kb%16)/4, elements 2(kb%4), 2(kb%4)+1
+                    raw* d = lds_val + (((col >> 5) * 4 + ((kb & 15) >> 2)) * 64 + (col & 31) + 32 * (kb >> 4)) * 8 + 2 * (kb & 3);
                     if constexpr (sizeof(raw) == 2) *reinterpret_cast<uint32_t*>(d) = v0 | (v1 << 16);
                     else *reinterpret_cast<uint2*>(d) = make_uint2(v0, v1);
                     lds_meta[col * 32 + kb] = static_cast<uint8_t>(p0 | (p1 << 2));
@@ -260,36 +276,23 @@ k_backward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t
     const int64_t rows_valid = (I - r0) < kTR ? (I - r0) : kTR;       // multiple of M
     const int64_t cols_valid = (J - c0) < kTC ? (J - c0) : kTC;
     if (mode == 1) {
-        const int64_t nvals = rows_valid / 2;                          // per column
-        const int64_t ostride = I / 2;
-        if (vec_out && rows_valid == kTR) {
-            constexpr int GPC = 64 * sizeof(raw) / 16;                 // 16-byte granules per column
-            for (int it = threadIdx.x; it < kTC * GPC; it += kThreads) {
-                const int col = it / GPC, g = it % GPC;
-                if (col >= cols_valid) continue;
-                const uint4 v = *reinterpret_cast<const uint4*>(lds_val + col * S1 + g * (16 / sizeof(raw)));
-                *reinterpret_cast<uint4*>(values + (c0 + col) * ostride + r0 / 2 + g * (16 / sizeof(raw))) = v;
-            }
-        } else {
-            for (int64_t it = threadIdx.x; it < kTC * nvals; it += kThreads) {
-                const int col = static_cast<int>(it / nvals), e = static_cast<int>(it % nvals);
-                if (col >= cols_valid) continue;
-                values[(c0 + col) * ostride + r0 / 2 + e] = lds_val[col * S1 + e];
-            }
+        // the tile is stage r0/128 of output row tiles c0/32 .. c0/32+3: 4 KB-contiguous images
+        const int64_t ks = ceil_div(I, 128), stage = r0 / kTR;
+        const int rts = static_cast<int>((cols_valid + 31) / 32);
+        constexpr int VPT = 2048 * (int)sizeof(raw) / 16;              // 16-byte vectors per row tile
+        for (int it = threadIdx.x; it < rts * VPT; it += kThreads) {
+            const int rtl = it / VPT, v = it % VPT;
+            raw* dst = values + ((c0 / 32 + rtl) * ks + stage) * 2048;
+            reinterpret_cast<uint4*>(dst)[v] = reinterpret_cast<const uint4*>(lds_val + rtl * 2048)[v];
         }
-        const int64_t wprI = ceil_div(I, 32);
-        const int nblk_valid = static_cast<int>(rows_valid / 4);
-        const int nwords = (nblk_valid + 7) / 8;
-        for (int it = threadIdx.x; it < kTC * 4; it += kThreads) {
-            const int col = it >> 2, wd = it & 3;
-            if (col >= cols_valid || wd >= nwords) continue;
+        for (int it = threadIdx.x; it < rts * 128; it += kThreads) {
+            const int rtl = it >> 7, lane = (it & 127) >> 1, wd = it & 1;
+            const int col = rtl * 32 + (lane & 31);
             uint32_t word = 0;
 #pragma unroll
-            for (int b = 0; b < 8; ++b) {
-                const int kb = wd * 8 + b;
-                if (kb < nblk_valid) word |= static_cast<uint32_t>(lds_meta[col * 32 + kb]) << (4 * b);
-            }
-            index[(c0 + col) * wprI + r0 / 32 + wd] = word;
+            for (int b = 0; b < 8; ++b)
+                word |= static_cast<uint32_t>(lds_meta[col * 32 + 16 * (lane >> 5) + 8 * wd + b]) << (4 * b);
+            index[((c0 / 32 + rtl) * ks + stage) * 128 + lane * 2 + wd] = word;
         }
     } else {
         if (vec_out && rows_valid == kTR) {
@@ -317,14 +320,17 @@ int run_forward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const u
     using raw = typename DT::raw;
     constexpr int CH = M == 16 ? 16 : 8;
     const int wpr = static_cast<int>(ceil_div(J, 32));
-    const int cpr = wpr * 32 / CH;
+    // mode 1 walks the padded operand (rows to 32, columns to 128) so that its padding is zeroed
+    const int cpr = mode == 1 ? static_cast<int>(round_up(J, 128) / CH) : wpr * 32 / CH;
+    const int64_t rows_pad = mode == 1 ? round_up(I, 32) : I;
+    if (mode == 1 && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
     const bool vec_in = aligned16(W) && (ldw * sizeof(raw)) % 16 == 0;
-    const bool vec_out = values && aligned16(values) && J % 8 == 0;
-    const int64_t total = I * cpr;
+    const bool vec_out = values && aligned16(values) && (mode == 1 || J % 8 == 0);
+    const int64_t total = rows_pad * cpr;
     const unsigned grid = static_cast<unsigned>(ceil_div(total, kThreads));
     hipLaunchKernelGGL((k_forward<DT, M, CH>), dim3(grid), dim3(kThreads), 0, s,
                        static_cast<const raw*>(W), I, J, ldw, N, mask_in, B_bits, static_cast<raw*>(values),
-                       index, mode, wpr, cpr, vec_in, vec_out);
+                       index, mode, wpr, cpr, rows_pad, vec_in, vec_out);
     return check_launch();
 }
 
@@ -338,8 +344,8 @@ int run_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const 
     bool vec_out = false;
     size_t lds = 0;
     if (mode == 1) {
-        vec_out = aligned16(values) && (I / 2 * sizeof(raw)) % 16 == 0;
-        lds = static_cast<size_t>(kTC) * lds_stride_m1<DT>() * sizeof(raw) + kTC * 32;
+        if (!aligned16(values) || !aligned16(index)) return BIMASK_ERR_ALIGN;
+        lds = static_cast<size_t>(kImgElems) * sizeof(raw) + kTC * 32;
     } else if (mode == 2) {
         vec_out = aligned16(values) && (I * sizeof(raw)) % 16 == 0;
         lds = static_cast<size_t>(kTC) * lds_stride_m2<DT>() * sizeof(raw);

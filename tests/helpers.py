@@ -54,3 +54,24 @@ def rel_err(got: np.ndarray, want: np.ndarray) -> float:
     """max|got - want| / max|want| (infinity-norm relative error)."""
     denom = float(np.max(np.abs(want)))
     return float(np.max(np.abs(got - want))) / (denom if denom > 0 else 1.0)
+
+
+def untile24(values: np.ndarray, index: np.ndarray, rows: int, cols: int):
+    """Fragment-major 2:4 operand buffers (layout stated in include/bimask.h) -> row-major
+    slot values [rows, cols/2] and index words [rows, ceil(cols/32)], plus a flag telling
+    whether all padding (rows >= rows, cols >= cols) is zero.  Pure index permutation."""
+    Rp, Cp = -(-rows // 32) * 32, -(-cols // 128) * 128
+    ks = Cp // 128
+    v = values.reshape(Rp // 32, ks, 4, 2, 32, 8)          # [rt][st][s4][h][r%32][e]
+    v = v.transpose(0, 4, 1, 3, 2, 5).reshape(Rp, Cp // 2)  # slot = st*64 + h*32 + s4*8 + e
+    x = index.reshape(Rp // 32, ks, 2, 32, 2)              # [rt][st][h][r%32][w]
+    x = x.transpose(0, 3, 1, 2, 4).reshape(Rp, Cp // 32)    # word = st*4 + h*2 + w
+    pad_zero = bool((v[rows:] == 0).all() and (v[:, cols // 2:] == 0).all()
+                    and (x[rows:] == 0).all())
+    wv = -(-cols // 32)
+    tail_bits = cols % 32
+    xr = x[:rows, :wv].copy()
+    if tail_bits:
+        pad_zero = pad_zero and bool(((xr[:, -1] >> np.uint32(tail_bits)) == 0).all())
+    pad_zero = pad_zero and bool((x[:rows, wv:] == 0).all())
+    return v[:rows, :cols // 2], xr, pad_zero

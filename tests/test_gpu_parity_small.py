@@ -9,7 +9,7 @@ import pytest
 import oracle
 import paper_2302_06058_amd as bm
 from paper_2302_06058_amd import synth
-from helpers import to_dev, i32_dev, words, from_dev_f64, raw_bits, f64_to_raw, rel_err
+from helpers import to_dev, i32_dev, words, from_dev_f64, raw_bits, f64_to_raw, rel_err, untile24
 
 pytestmark = pytest.mark.gpu
 
@@ -58,10 +58,14 @@ def check_layer(I, J, N, M, dtype, K, seed, kind="normal", T=0):
     B2, vals, index = bm.bimask_forward_mask_compress(W, N, M)
     assert (words(B2) == Bw_o).all(), "fused forward mask"
     vals_s, index_s = bm.bimask_compress_nm(W, N, M, B, None, 0)
+    got_v, got_vs = raw_bits(vals, dtype), raw_bits(vals_s, dtype)
     if s24:
         val_o, idx_o = oracle.compress_fwd(W64, B_o, N, M)
         want_v, want_i = f64_to_raw(val_o, dtype), oracle.pack_index(idx_o, M)
-        assert (words(index) == want_i).all() and (words(index_s) == want_i).all(), "forward index"
+        got_v, got_i, pz = untile24(got_v, words(index), I, J)
+        got_vs, got_is, pzs = untile24(got_vs, words(index_s), I, J)
+        assert pz and pzs, "forward operand padding must be zero"
+        assert (got_i == want_i).all() and (got_is == want_i).all(), "forward index"
     else:
         want_v = f64_to_raw(W64 * B_o, dtype)
     # -0.0 weights: a kept -0 stays -0, a dropped slot is +0 -> compare bit patterns of the oracle's
@@ -70,8 +74,8 @@ def check_layer(I, J, N, M, dtype, K, seed, kind="normal", T=0):
         za = (a & (0x7FFF if dtype == synth.BF16 else 0x7FFFFFFF)) == 0
         zb = (b & (0x7FFF if dtype == synth.BF16 else 0x7FFFFFFF)) == 0
         return ((a == b) | (za & zb)).all()
-    assert same_bits(raw_bits(vals, dtype), want_v), "fused forward values"
-    assert same_bits(raw_bits(vals_s, dtype), want_v), "stand-alone forward values"
+    assert same_bits(got_v, want_v), "fused forward values"
+    assert same_bits(got_vs, want_v), "stand-alone forward values"
 
     # ---- permutation search
     sc_o = oracle.perm_scores(B_o, perms, N, M)
@@ -91,15 +95,19 @@ def check_layer(I, J, N, M, dtype, K, seed, kind="normal", T=0):
         Bbar2, vb, ib = bm.bimask_backward_mask_compress(W, N, M, B, P_d)
         assert (words(Bbar2) == Bbw_o).all(), "fused backward mask"
         vb_s, ib_s = bm.bimask_compress_nm(W, N, M, Bbar, P_d, 1)
+        got_vb, got_vbs = raw_bits(vb, dtype), raw_bits(vb_s, dtype)
         if s24:
             valb_o, idxb_o = oracle.compress_bwd(W64, B_o, P_h, N, M)
             want_vb, want_ib = f64_to_raw(valb_o, dtype), oracle.pack_index(idxb_o, M)
-            assert (words(ib) == want_ib).all() and (words(ib_s) == want_ib).all(), "backward index"
+            got_vb, got_ib, pz = untile24(got_vb, words(ib), J, I)
+            got_vbs, got_ibs, pzs = untile24(got_vbs, words(ib_s), J, I)
+            assert pz and pzs, "backward operand padding must be zero"
+            assert (got_ib == want_ib).all() and (got_ibs == want_ib).all(), "backward index"
         else:
             Wp = W64 if P_h is None else W64[P_h, :]
             want_vb = f64_to_raw(np.ascontiguousarray((Wp * Bbar_o).T), dtype)
-        assert same_bits(raw_bits(vb, dtype), want_vb), "fused backward values"
-        assert same_bits(raw_bits(vb_s, dtype), want_vb), "stand-alone backward values"
+        assert same_bits(got_vb, want_vb), "fused backward values"
+        assert same_bits(got_vbs, want_vb), "stand-alone backward values"
 
         # ---- GEMMs
         if T > 0:
@@ -204,3 +212,9 @@ def test_streaming_gemm_shapes(I, J, T):
     # contraction lengths that are multiples of 128 take the streaming 2:4 kernel in both
     # directions; ragged token counts and weight-row counts exercise its edge tiles
     check_layer(I=I, J=J, N=2, M=4, dtype=synth.BF16, K=6, seed=800 + I + J, T=T)
+
+
+@pytest.mark.parametrize("I,J,T", [(1024, 128, 70), (640, 256, 100)])
+def test_long_contraction_backward_uses_gather_pass(I, J, T):
+    # I > 512: g(Y)[:, P] is gathered into the workspace, then the streaming kernel runs
+    check_layer(I=I, J=J, N=2, M=4, dtype=synth.BF16, K=4, seed=900 + I, T=T)
