@@ -80,6 +80,16 @@ __host__ __device__ inline int64_t tiled_idx_word(int64_t r, int64_t g, int64_t 
     return (((r >> 5) * ks + st) * 64 + (r & 31) + 32 * (q >> 4)) * 2 + ((q >> 3) & 1);
 }
 
+// Two fp32 accumulators -> packed bf16 (round to nearest even) with the gfx950 conversion
+// instruction; the low half holds `lo`.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    const bf16x2_t r = __builtin_convertvector(v, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
 // launchers implemented in the .hip files -------------------------------------------
 int launch_forward(const void* W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
                    const uint32_t* mask_in, uint32_t* B_bits, void* values, uint32_t* index,

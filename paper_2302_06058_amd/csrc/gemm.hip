@@ -164,8 +164,8 @@ k_gemm_dense_bf16(const uint16_t* __restrict__ A, int64_t Adim, int64_t K, const
             for (int qq = 0; qq < 4; ++qq) {
                 const int a = wm * WM + i * 32 + 8 * qq + 4 * h;
                 u32x2 v;
-                v.x = f32_to_bf16_rne(acc[i][j][4 * qq + 0]) | (f32_to_bf16_rne(acc[i][j][4 * qq + 1]) << 16);
-                v.y = f32_to_bf16_rne(acc[i][j][4 * qq + 2]) | (f32_to_bf16_rne(acc[i][j][4 * qq + 3]) << 16);
+                v.x = pack_bf16(acc[i][j][4 * qq + 0], acc[i][j][4 * qq + 1]);
+                v.y = pack_bf16(acc[i][j][4 * qq + 2], acc[i][j][4 * qq + 3]);
                 *reinterpret_cast<u32x2*>(sC + t * S::kCRow + a * 2) = v;
             }
         }
@@ -326,7 +326,7 @@ int launch_gather_cols(const void* dY, int64_t T, int64_t ld, const int32_t* per
 }
 
 bool gemm_bwd_needs_gather(int64_t I, int dtype, int N, int M) {
-    static const int resvar = [] { const char* e = getenv("BIMASK_RES_VARIANT"); return e ? atoi(e) : 0; }();
+    static const int resvar = [] { const char* e = getenv("BIMASK_RES_VARIANT"); return e ? atoi(e) : 1; }();
     return !(dtype == BIMASK_BF16 && N == 2 && M == 4 && I <= 512 && resvar >= 0);
 }
 
@@ -345,7 +345,7 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
     if (sparse24) {
         // tuning hooks: tile shape / prefetch depth of the streaming kernel, wave count of the resident one
         static const int forced = [] { const char* e = getenv("BIMASK_GEMM_VARIANT"); return e ? atoi(e) : -1; }();
-        static const int resvar = [] { const char* e = getenv("BIMASK_RES_VARIANT"); return e ? atoi(e) : 0; }();
+        static const int resvar = [] { const char* e = getenv("BIMASK_RES_VARIANT"); return e ? atoi(e) : 1; }();
         if (K <= 512 && resvar >= 0) {
             const int rc = launch_gemm_sp24_resident(A_values, A_index, Adim, K, Bm, ldb, nullptr, T, C, ldc, resvar, s);
             if (rc != BIMASK_ERR_UNSUPPORTED) return rc;

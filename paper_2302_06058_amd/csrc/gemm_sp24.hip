@@ -12,8 +12,8 @@
 //     double-buffered XOR-swizzled LDS tile and read back as 16-byte fragments;
 //   * PF stages of both operands are kept in flight in registers, so a workgroup has
 //     PF * (BM*72 + BN*256) bytes outstanding to hide HBM latency;
-//   * fp32 accumulators are rounded to bf16, transposed through LDS and written as
-//     16-byte row-contiguous stores.
+//   * fp32 accumulators are rounded to bf16 and, after a swap between the two lane halves,
+//     written straight from registers as 16-byte row-contiguous stores.
 // Lane/operand mapping of v_smfmac_f32_32x32x32_bf16 (checked on the device): lane l holds
 // weight row l%32; with h = l/32, compressed element e of the A register pairs with slot
 // 8h + 4((e%4)/2) + idx_e of the B register of token lane half e/4, and idx_e sits in bits
@@ -44,9 +44,7 @@ union AFrag { bf16x8 v; u32x4 q; };
 template <int BM, int BN>
 struct SpSmem {
     static constexpr int kStage = BN * kRowBytes;
-    static constexpr int kCRow = BM * 2 + 16;
-    static constexpr int kC = BN * kCRow;
-    static constexpr int kTotal = (2 * kStage > kC) ? 2 * kStage : kC;
+    static constexpr int kTotal = 2 * kStage;
 };
 
 // 8 consecutive bf16 of a token row starting at element k, zero beyond kend; 4-byte loads
@@ -199,39 +197,36 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
 #undef BIMASK_STEP
 #undef BIMASK_LOAD_STAGE
 
-    // Epilogue: accumulators -> bf16 tile [t][a] in LDS -> 16-byte row-contiguous stores.
-    __syncthreads();
-    uint8_t* sC = smem;
+    // Epilogue: a lane holds 4 consecutive weight rows of one token per accumulator quad;
+    // swapping quads between the two lane halves gives every lane 8 consecutive bf16
+    // (16 bytes) of its token row, stored straight from registers.
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const int t = wn * WN + j * 32 + l32;
+            const int64_t t = t0 + wn * WN + j * 32 + l32;
 #pragma unroll
-            for (int qq = 0; qq < 4; ++qq) {
-                const int a = wm * WM + i * 32 + 8 * qq + 4 * h;
-                u32x2 v;
-                v.x = to_bf16(acc[i][j][4 * qq + 0]) | (to_bf16(acc[i][j][4 * qq + 1]) << 16);
-                v.y = to_bf16(acc[i][j][4 * qq + 2]) | (to_bf16(acc[i][j][4 * qq + 3]) << 16);
-                *reinterpret_cast<u32x2*>(sC + t * S::kCRow + a * 2) = v;
+            for (int p = 0; p < 2; ++p) {
+                const uint32_t xlo = pack_bf16(acc[i][j][8 * p + 0], acc[i][j][8 * p + 1]);
+                const uint32_t xhi = pack_bf16(acc[i][j][8 * p + 2], acc[i][j][8 * p + 3]);
+                const uint32_t ylo = pack_bf16(acc[i][j][8 * p + 4], acc[i][j][8 * p + 5]);
+                const uint32_t yhi = pack_bf16(acc[i][j][8 * p + 6], acc[i][j][8 * p + 7]);
+                const auto slo = __builtin_amdgcn_permlane32_swap(xlo, ylo, false, false);
+                const auto shi = __builtin_amdgcn_permlane32_swap(xhi, yhi, false, false);
+                const u32x4 v = {slo[0], shi[0], slo[1], shi[1]};
+                const int64_t a = a0 + wm * WM + i * 32 + 16 * p + 8 * h;
+                if (t < T && a < Adim) {
+                    uint16_t* dst = C + t * ldc + a;
+                    if (vecC && a + 8 <= Adim) {
+                        *reinterpret_cast<u32x4*>(dst) = v;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (a + e < Adim) dst[e] = static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1)));
+                    }
+                }
             }
         }
-    __syncthreads();
-    constexpr int GPR = BM / 8;                          // 16-byte granules per output row
-    for (int q = tid; q < BN * GPR; q += NT) {
-        const int row = q / GPR, g = q % GPR;
-        const int64_t t = t0 + row, a = a0 + 8 * g;
-        if (t >= T || a >= Adim) continue;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(sC + row * S::kCRow + g * 16);
-        uint16_t* dst = C + t * ldc + a;
-        if (vecC && a + 8 <= Adim) {
-            *reinterpret_cast<u32x4*>(dst) = v;
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (a + e < Adim) dst[e] = static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1)));
-        }
-    }
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD>

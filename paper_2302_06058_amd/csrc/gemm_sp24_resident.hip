@@ -8,8 +8,10 @@
 // XOR-swizzled LDS tile, so the column permutation of Eq. (10) costs no extra pass over
 // memory.  It then walks over ALL weight-row tiles: the fragment-major compressed weights
 // stream from L2 straight into the sparse matrix instruction's A registers (prefetched one
-// weight tile ahead), the token fragments come from the resident LDS tile, and every
-// finished 256-wide output strip leaves through LDS as 16-byte row-contiguous stores.
+// weight tile ahead), the token fragments come from the resident tile (registers when the
+// contraction is at most 256 long, LDS otherwise), and every finished output strip is
+// stored straight from the accumulators after a cross-half lane swap that gives each lane
+// 16 contiguous bytes of its token row.  After the tile fill no barrier is needed.
 // Token tiles have a run-time height (<= BN) so that the grid can be cut to the CU count.
 #include "common.hpp"
 
@@ -34,10 +36,8 @@ __device__ __forceinline__ uint32_t to_bf16r(float f) {
 template <int BM, int BN, int NSTG>
 struct ResSmem {
     static constexpr int kB = NSTG * BN * 256;          // resident token tile, 256 B per row and stage
-    static constexpr int kCRow = BM * 2 + 16;
-    static constexpr int kC = BN * kCRow;
     static constexpr int kInv = NSTG * 128 * 2;         // inverse permutation (int16)
-    static constexpr int kTotal = kB + kC + kInv;
+    static constexpr int kTotal = kB + kInv;
 };
 
 // byte offset of element (t, r) of the resident tile
@@ -56,8 +56,7 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
     constexpr int WM = BM / WAVES_M, TM = WM / 32, TN = BN / 32;
     extern __shared__ u32x4 smem_u4[];
     uint8_t* sB = reinterpret_cast<uint8_t*>(smem_u4);
-    uint8_t* sC = sB + S::kB;
-    int16_t* sInv = reinterpret_cast<int16_t*>(sC + S::kC);
+    int16_t* sInv = reinterpret_cast<int16_t*>(sB + S::kB);
 
     const int tid = threadIdx.x, lane = tid & 63, wm = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
@@ -85,40 +84,72 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
     }
     BIMASK_LOAD_WTILE(0, 0)
 
-    // ---- resident token tile: zero, (inverse permutation), fill
+    // ---- resident token tile.  The g(Y) rows are requested first (registers), then LDS is
+    // zeroed and the inverse permutation built while they are in flight.
+    const int G = static_cast<int>((K + 7) >> 3);        // 8-element granules per token row
+    constexpr int NL = (BN * NSTG * 16 + NT - 1) / NT;
+    u32x4 v[NL];
+#pragma unroll
+    for (int it = 0; it < NL; ++it) {
+        const int q = tid + NT * it;
+        const int t = q / G, g = q - t * G;
+        v[it] = (u32x4){0u, 0u, 0u, 0u};
+        if (q < rows * G) {
+            const uint16_t* src = Bsrc + (t0 + t) * ldb + 8 * g;
+            if (8 * g + 8 <= K) {
+                if (vecB) v[it] = *reinterpret_cast<const u32x4*>(src);
+                else { const uint32_t* p = reinterpret_cast<const uint32_t*>(src); v[it].x = p[0]; v[it].y = p[1]; v[it].z = p[2]; v[it].w = p[3]; }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (8 * g + e < K) v[it][e >> 1] |= static_cast<uint32_t>(src[e]) << (16 * (e & 1));
+            }
+        }
+    }
     for (int it = tid; it < S::kB / 16; it += NT) reinterpret_cast<u32x4*>(sB)[it] = (u32x4){0u, 0u, 0u, 0u};
     if (perm) {
         for (int r = tid; r < static_cast<int>(K); r += NT) sInv[perm[r]] = static_cast<int16_t>(r);
     }
     __syncthreads();
     {
-        const int G = static_cast<int>((K + 7) >> 3);    // 8-element granules per token row
-        for (int q = tid; q < rows * G; q += NT) {
+#pragma unroll
+        for (int it = 0; it < NL; ++it) {
+            const int q = tid + NT * it;
             const int t = q / G, g = q - t * G;
-            const uint16_t* src = Bsrc + (t0 + t) * ldb + 8 * g;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (8 * g + 8 <= K) {
-                if (vecB) v = *reinterpret_cast<const u32x4*>(src);
-                else { const uint32_t* p = reinterpret_cast<const uint32_t*>(src); v.x = p[0]; v.y = p[1]; v.z = p[2]; v.w = p[3]; }
-            } else {
+            if (q < rows * G) {
+                if (perm) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (8 * g + e < K) v[e >> 1] |= static_cast<uint32_t>(src[e]) << (16 * (e & 1));
-            }
-            if (perm) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int i = 8 * g + e;
-                    if (i < K)
-                        *reinterpret_cast<uint16_t*>(sB + resb_off<BN>(t, sInv[i])) =
-                            static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1)));
+                    for (int e = 0; e < 8; ++e) {
+                        const int i = 8 * g + e;
+                        if (i < K)
+                            *reinterpret_cast<uint16_t*>(sB + resb_off<BN>(t, sInv[i])) =
+                                static_cast<uint16_t>(v[it][e >> 1] >> (16 * (e & 1)));
+                    }
+                } else {
+                    *reinterpret_cast<u32x4*>(sB + resb_off<BN>(t, 8 * g)) = v[it];
                 }
-            } else {
-                *reinterpret_cast<u32x4*>(sB + resb_off<BN>(t, 8 * g)) = v;
             }
         }
     }
     __syncthreads();
+
+    // Short contractions: the token fragments are the same for every weight tile, so they are
+    // read from LDS once and stay in registers (NSTG * 4 * TN * 8 VGPRs).
+    constexpr bool REGB = NSTG <= 2;
+    BFragR bfr[REGB ? NSTG : 1][4][TN];
+    if constexpr (REGB) {
+#pragma unroll
+        for (int st = 0; st < NSTG; ++st)
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int row = j * 32 + l32;
+                    const uint8_t* base = sB + st * (BN * 256) + row * 256;
+                    bfr[st][s4][j].q[0] = *reinterpret_cast<const u32x4*>(base + (((2 * s4 + h) ^ (row & 15)) << 4));
+                    bfr[st][s4][j].q[1] = *reinterpret_cast<const u32x4*>(base + (((8 + 2 * s4 + h) ^ (row & 15)) << 4));
+                }
+    }
 
     // ---- one weight tile: NSTG x 4 sparse matrix instructions per (row tile, token tile)
 #define BIMASK_WTILE(set, at)                                                                    \
@@ -131,10 +162,14 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
             _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) {                                   \
                 BFragR bf[TN];                                                                   \
                 _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                 \
-                    const int row = j * 32 + l32;                                                \
-                    const uint8_t* base = sB + st * (BN * 256) + row * 256;                      \
-                    bf[j].q[0] = *reinterpret_cast<const u32x4*>(base + (((2 * s4 + h) ^ (row & 15)) << 4));     \
-                    bf[j].q[1] = *reinterpret_cast<const u32x4*>(base + (((8 + 2 * s4 + h) ^ (row & 15)) << 4)); \
+                    if constexpr (REGB) {                                                        \
+                        bf[j] = bfr[st][s4][j];                                                  \
+                    } else {                                                                     \
+                        const int row = j * 32 + l32;                                            \
+                        const uint8_t* base = sB + st * (BN * 256) + row * 256;                  \
+                        bf[j].q[0] = *reinterpret_cast<const u32x4*>(base + (((2 * s4 + h) ^ (row & 15)) << 4));     \
+                        bf[j].q[1] = *reinterpret_cast<const u32x4*>(base + (((8 + 2 * s4 + h) ^ (row & 15)) << 4)); \
+                    }                                                                            \
                 }                                                                                \
                 _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                 \
                     AFragR af;                                                                   \
@@ -149,36 +184,32 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
                 }                                                                                \
             }                                                                                    \
         }                                                                                        \
+        /* Output: a lane holds 4 consecutive weight rows of one token per accumulator quad;  \
+           swapping quads between the two lane halves gives every lane 8 consecutive bf16     \
+           (16 bytes) of its token row, stored straight from registers: no LDS, no barrier. */ \
         _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
             _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                     \
                 const int t = j * 32 + l32;                                                      \
-                _Pragma("unroll") for (int qq = 0; qq < 4; ++qq) {                               \
-                    const int a = wm * WM + i * 32 + 8 * qq + 4 * h;                             \
-                    u32x2 v;                                                                     \
-                    v.x = to_bf16r(acc[i][j][4 * qq + 0]) | (to_bf16r(acc[i][j][4 * qq + 1]) << 16); \
-                    v.y = to_bf16r(acc[i][j][4 * qq + 2]) | (to_bf16r(acc[i][j][4 * qq + 3]) << 16); \
-                    *reinterpret_cast<u32x2*>(sC + t * S::kCRow + a * 2) = v;                    \
+                _Pragma("unroll") for (int p = 0; p < 2; ++p) {                                  \
+                    const uint32_t xlo = pack_bf16(acc[i][j][8 * p + 0], acc[i][j][8 * p + 1]);  \
+                    const uint32_t xhi = pack_bf16(acc[i][j][8 * p + 2], acc[i][j][8 * p + 3]);  \
+                    const uint32_t ylo = pack_bf16(acc[i][j][8 * p + 4], acc[i][j][8 * p + 5]);  \
+                    const uint32_t yhi = pack_bf16(acc[i][j][8 * p + 6], acc[i][j][8 * p + 7]);  \
+                    const auto slo = __builtin_amdgcn_permlane32_swap(xlo, ylo, false, false);   \
+                    const auto shi = __builtin_amdgcn_permlane32_swap(xhi, yhi, false, false);   \
+                    const u32x4 v = {slo[0], shi[0], slo[1], shi[1]};                            \
+                    const int64_t a = static_cast<int64_t>(at) * BM + wm * WM + i * 32 + 16 * p + 8 * h; \
+                    if (t < rows && a < Adim) {                                                  \
+                        uint16_t* dst = C + (t0 + t) * ldc + a;                                  \
+                        if (vecC && a + 8 <= Adim) {                                             \
+                            *reinterpret_cast<u32x4*>(dst) = v;                                  \
+                        } else {                                                                 \
+                            _Pragma("unroll") for (int e = 0; e < 8; ++e)                        \
+                                if (a + e < Adim) dst[e] = static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1))); \
+                        }                                                                        \
+                    }                                                                            \
                 }                                                                                \
             }                                                                                    \
-        __syncthreads();                                                                         \
-        {                                                                                        \
-            constexpr int GPR = BM / 8;                                                          \
-            const int64_t a0 = static_cast<int64_t>(at) * BM;                                    \
-            for (int q = tid; q < rows * GPR; q += NT) {                                         \
-                const int row = q / GPR, g = q % GPR;                                            \
-                const int64_t a = a0 + 8 * g;                                                    \
-                if (a >= Adim) continue;                                                         \
-                const u32x4 v = *reinterpret_cast<const u32x4*>(sC + row * S::kCRow + g * 16);   \
-                uint16_t* dst = C + (t0 + row) * ldc + a;                                        \
-                if (vecC && a + 8 <= Adim) {                                                     \
-                    *reinterpret_cast<u32x4*>(dst) = v;                                          \
-                } else {                                                                         \
-                    _Pragma("unroll") for (int e = 0; e < 8; ++e)                                \
-                        if (a + e < Adim) dst[e] = static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1))); \
-                }                                                                                \
-            }                                                                                    \
-        }                                                                                        \
-        __syncthreads();                                                                         \
     }
 
     int at = 0;

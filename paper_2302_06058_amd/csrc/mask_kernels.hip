@@ -165,19 +165,21 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
 }
 
 // ---------------------------------------------------------------------------------
-// Backward direction: a workgroup owns a tile of 128 permuted rows x 128 columns; a thread
-// owns one block of M permuted rows x 8 columns.  Rows of W are gathered through P, every
-// row read is a contiguous 256-byte (bf16) segment.  Transposed outputs go through LDS so
+// Backward direction: a workgroup owns a tile of 128 permuted rows x TC columns (TC = 128,
+// or 32 for small matrices so that enough workgroups exist); a thread owns one block of M
+// permuted rows x 8 columns.  Rows of W are gathered through P, every row read is a
+// contiguous 2*TC-byte (bf16) segment.  Transposed outputs go through LDS so
 // that they leave as contiguous runs along the permuted-row axis.
 //   MODE 0: Bbar only   1: + transposed 2:4 values/index   2: + transposed dense masked
 // Bbar_in != nullptr: Bbar is read instead of selected (stand-alone compression).
 // ---------------------------------------------------------------------------------
-constexpr int kTR = 128, kTC = 128;
+constexpr int kTR = 128;   // permuted rows per tile = one 128-deep stage of the transposed operand
 
-constexpr int kImgElems = 4 * 4 * 64 * 8;             // mode 1: fragment-major image of 128 rows x 64 slots
+// mode 1: fragment-major image of TC output rows x 64 slots (2048 elements per 32 output rows)
+template <int TC> __host__ __device__ constexpr int img_elems() { return TC / 32 * 2048; }
 template <typename DT> __host__ __device__ constexpr int lds_stride_m2() { return kTR + 16 / (int)sizeof(typename DT::raw); }
 
-template <typename DT, int M>
+template <typename DT, int M, int TC>
 __global__ void __launch_bounds__(kThreads)
 k_backward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t ldw, int N,
            const uint32_t* __restrict__ B_bits, const uint32_t* __restrict__ Bbar_in,
@@ -190,20 +192,21 @@ k_backward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t
     extern __shared__ uint4 lds_u4[];
     raw* lds_val = reinterpret_cast<raw*>(lds_u4);
     constexpr int S2 = lds_stride_m2<DT>();
-    uint8_t* lds_meta = reinterpret_cast<uint8_t*>(lds_val + kImgElems);  // mode 1 only: [kTC][32] nibbles
+    constexpr int CPT = TC / 8;                         // 8-column chunks per tile row
+    uint8_t* lds_meta = reinterpret_cast<uint8_t*>(lds_val + img_elems<TC>());  // mode 1 only: [TC][32] nibbles
 
     const int64_t r0 = static_cast<int64_t>(blockIdx.y) * kTR;
-    const int64_t c0 = static_cast<int64_t>(blockIdx.x) * kTC;
-    const int ch = threadIdx.x & 15;
+    const int64_t c0 = static_cast<int64_t>(blockIdx.x) * TC;
+    const int ch = threadIdx.x % CPT;
     const int64_t j0 = c0 + ch * 8;
 
     if (mode == 1) {                                    // padding of the operand image is zero
-        constexpr int kZeroWords = (kImgElems * (int)sizeof(raw) + kTC * 32) / 16;
+        constexpr int kZeroWords = (img_elems<TC>() * (int)sizeof(raw) + TC * 32) / 16;
         for (int it = threadIdx.x; it < kZeroWords; it += kThreads) lds_u4[it] = make_uint4(0, 0, 0, 0);
         __syncthreads();
     }
 
-    for (int kb = threadIdx.x >> 4; kb < NB; kb += kThreads / 16) {
+    for (int kb = threadIdx.x / CPT; kb < NB; kb += kThreads / CPT) {
         const int64_t rb = r0 + static_cast<int64_t>(kb) * M;
         if (rb >= I) continue;
         if (j0 >= J) {                                   // pad bytes of the last mask word stay zero
@@ -274,7 +277,7 @@ k_backward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t
     __syncthreads();
 
     const int64_t rows_valid = (I - r0) < kTR ? (I - r0) : kTR;       // multiple of M
-    const int64_t cols_valid = (J - c0) < kTC ? (J - c0) : kTC;
+    const int64_t cols_valid = (J - c0) < TC ? (J - c0) : TC;
     if (mode == 1) {
         // the tile is stage r0/128 of output row tiles c0/32 .. c0/32+3: 4 KB-contiguous images
         const int64_t ks = ceil_div(I, 128), stage = r0 / kTR;
@@ -298,14 +301,14 @@ k_backward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t
         if (vec_out && rows_valid == kTR) {
             constexpr int EPG = 16 / sizeof(raw);
             constexpr int GPC = kTR / EPG;
-            for (int it = threadIdx.x; it < kTC * GPC; it += kThreads) {
+            for (int it = threadIdx.x; it < TC * GPC; it += kThreads) {
                 const int col = it / GPC, g = it % GPC;
                 if (col >= cols_valid) continue;
                 const uint4 v = *reinterpret_cast<const uint4*>(lds_val + col * S2 + g * EPG);
                 *reinterpret_cast<uint4*>(values + (c0 + col) * I + r0 + g * EPG) = v;
             }
         } else {
-            for (int64_t it = threadIdx.x; it < kTC * rows_valid; it += kThreads) {
+            for (int64_t it = threadIdx.x; it < TC * rows_valid; it += kThreads) {
                 const int col = static_cast<int>(it / rows_valid), e = static_cast<int>(it % rows_valid);
                 if (col >= cols_valid) continue;
                 values[(c0 + col) * I + r0 + e] = lds_val[col * S2 + e];
@@ -334,10 +337,10 @@ int run_forward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const u
     return check_launch();
 }
 
-template <typename DT, int M>
-int run_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const uint32_t* B_bits,
-                 const uint32_t* Bbar_in, const int32_t* perm, uint32_t* Bbar_bits, void* values,
-                 uint32_t* index, int mode, hipStream_t s) {
+template <typename DT, int M, int TC>
+int run_backward_t(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const uint32_t* B_bits,
+                   const uint32_t* Bbar_in, const int32_t* perm, uint32_t* Bbar_bits, void* values,
+                   uint32_t* index, int mode, hipStream_t s) {
     using raw = typename DT::raw;
     const int wpr = static_cast<int>(ceil_div(J, 32));
     const bool vec_in = aligned16(W) && (ldw * sizeof(raw)) % 16 == 0;
@@ -345,20 +348,30 @@ int run_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const 
     size_t lds = 0;
     if (mode == 1) {
         if (!aligned16(values) || !aligned16(index)) return BIMASK_ERR_ALIGN;
-        lds = static_cast<size_t>(kImgElems) * sizeof(raw) + kTC * 32;
+        lds = static_cast<size_t>(img_elems<TC>()) * sizeof(raw) + TC * 32;
     } else if (mode == 2) {
         vec_out = aligned16(values) && (I * sizeof(raw)) % 16 == 0;
-        lds = static_cast<size_t>(kTC) * lds_stride_m2<DT>() * sizeof(raw);
+        lds = static_cast<size_t>(TC) * lds_stride_m2<DT>() * sizeof(raw);
     }
-    auto kern = k_backward<DT, M>;
+    auto kern = k_backward<DT, M, TC>;
     if (lds > 48 * 1024) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 static_cast<int>(lds)) != hipSuccess) return BIMASK_ERR_HIP;
     }
-    dim3 grid(static_cast<unsigned>(ceil_div(J, kTC)), static_cast<unsigned>(ceil_div(I, kTR)));
+    dim3 grid(static_cast<unsigned>(ceil_div(J, TC)), static_cast<unsigned>(ceil_div(I, kTR)));
     hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, s, static_cast<const raw*>(W), I, J, ldw, N, B_bits,
                        Bbar_in, perm, Bbar_bits, static_cast<raw*>(values), index, mode, wpr, vec_in, vec_out);
     return check_launch();
+}
+
+template <typename DT, int M>
+int run_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const uint32_t* B_bits,
+                 const uint32_t* Bbar_in, const int32_t* perm, uint32_t* Bbar_bits, void* values,
+                 uint32_t* index, int mode, hipStream_t s) {
+    // small matrices: narrow tiles so that the grid still covers the chip
+    if (ceil_div(J, 128) * ceil_div(I, kTR) < 256)
+        return run_backward_t<DT, M, 32>(W, I, J, ldw, N, B_bits, Bbar_in, perm, Bbar_bits, values, index, mode, s);
+    return run_backward_t<DT, M, 128>(W, I, J, ldw, N, B_bits, Bbar_in, perm, Bbar_bits, values, index, mode, s);
 }
 
 }  // namespace

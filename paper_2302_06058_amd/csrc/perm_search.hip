@@ -93,23 +93,39 @@ k_perm_score(const uint32_t* __restrict__ B_bits, int64_t I, int64_t J, int wpr3
     }
 }
 
-__global__ void __launch_bounds__(kThreads)
+// Sums the per-tile partial scores, takes the first arg-max and copies the winner.
+// One workgroup of 1024 threads: 128 candidates x 8 tile groups at a time, so every
+// thread issues its few independent loads at once instead of walking all tiles serially.
+constexpr int kFinalThreads = 1024;
+__global__ void __launch_bounds__(kFinalThreads)
 k_perm_final(const int32_t* __restrict__ partial, int ntiles, int K, int64_t I,
              const int32_t* __restrict__ perms, int32_t* __restrict__ scores,
              int32_t* __restrict__ best, int32_t* __restrict__ best_perm) {
-    __shared__ long long red[kThreads];
+    __shared__ int psum[8][128];
+    __shared__ long long red[128];
+    const int cl = threadIdx.x & 127, part = threadIdx.x >> 7;
     long long mine = -1;
-    for (int c = threadIdx.x; c < K; c += kThreads) {
+    for (int c0 = 0; c0 < K; c0 += 128) {
+        const int c = c0 + cl;
         int s = 0;
-        for (int t = 0; t < ntiles; ++t) s += partial[static_cast<int64_t>(t) * K + c];
-        scores[c] = s;
-        // larger score first, then the smaller candidate index
-        const long long key = (static_cast<long long>(s) << 32) | static_cast<uint32_t>(0x7FFFFFFF - c);
-        mine = key > mine ? key : mine;
+        if (c < K)
+            for (int t = part; t < ntiles; t += 8) s += partial[static_cast<int64_t>(t) * K + c];
+        psum[part][cl] = s;
+        __syncthreads();
+        if (part == 0 && c < K) {
+            int tot = 0;
+#pragma unroll
+            for (int p = 0; p < 8; ++p) tot += psum[p][cl];
+            scores[c] = tot;
+            // larger score first, then the smaller candidate index
+            const long long key = (static_cast<long long>(tot) << 32) | static_cast<uint32_t>(0x7FFFFFFF - c);
+            mine = key > mine ? key : mine;
+        }
+        __syncthreads();
     }
-    red[threadIdx.x] = mine;
+    if (part == 0) red[cl] = mine;
     __syncthreads();
-    for (int off = kThreads / 2; off > 0; off >>= 1) {
+    for (int off = 64; off > 0; off >>= 1) {
         if (static_cast<int>(threadIdx.x) < off) {
             const long long o = red[threadIdx.x + off];
             if (o > red[threadIdx.x]) red[threadIdx.x] = o;
@@ -120,7 +136,7 @@ k_perm_final(const int32_t* __restrict__ partial, int ntiles, int K, int64_t I,
     if (threadIdx.x == 0) *best = bc;
     if (best_perm) {
         const int32_t* P = perms + static_cast<int64_t>(bc) * I;
-        for (int64_t i = threadIdx.x; i < I; i += kThreads) best_perm[i] = P[i];
+        for (int64_t i = threadIdx.x; i < I; i += kFinalThreads) best_perm[i] = P[i];
     }
 }
 
@@ -179,7 +195,7 @@ int launch_perm_search(const uint32_t* B_bits, int64_t I, int64_t J, int N, int 
     }
 #undef BIMASK_SCORE
     if (rc != BIMASK_OK) return rc;
-    hipLaunchKernelGGL(k_perm_final, dim3(1), dim3(kThreads), 0, s, partial, pl.ntiles, K, I, perms, scores, best,
+    hipLaunchKernelGGL(k_perm_final, dim3(1), dim3(kFinalThreads), 0, s, partial, pl.ntiles, K, I, perms, scores, best,
                        best_perm);
     return check_launch();
 }
