@@ -25,12 +25,6 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 constexpr int BK = 64;                // dense k per pipeline stage
 constexpr int kRowB = 144;            // LDS bytes per 64-k row (128 + 16 pad: conflict-free 16-byte reads)
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-
 // 8 consecutive bf16 of a row starting at element k (zero beyond kend).
 __device__ __forceinline__ u32x4 load_granule(const uint16_t* row, int64_t k, int64_t kend, bool vec) {
     if (k + 8 <= kend) {

@@ -32,12 +32,6 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 constexpr int SK = 128;                 // dense k per stage
 constexpr int kRowBytes = SK * 2;       // LDS bytes per token row per stage (16 granules)
 
-__device__ __forceinline__ uint32_t to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-
 union BFrag { bf16x16 v; u32x4 q[2]; };
 union AFrag { bf16x8 v; u32x4 q; };
 

@@ -27,12 +27,6 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 union BFragR { bf16x16 v; u32x4 q[2]; };
 union AFragR { bf16x8 v; u32x4 q; };
 
-__device__ __forceinline__ uint32_t to_bf16r(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-
 template <int BM, int BN, int NSTG>
 struct ResSmem {
     static constexpr int kB = NSTG * BN * 256;          // resident token tile, 256 B per row and stage
