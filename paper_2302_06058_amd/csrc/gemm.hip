@@ -344,7 +344,10 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
             const int rc = launch_gemm_sp24_resident(A_values, A_index, Adim, K, Bm, ldb, nullptr, T, C, ldc, resvar, s);
             if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
         }
-        const int variant = forced >= 0 ? forced : 0;
+        // large problems: 256 x 128 tiles on 8 wavefronts (half the weight traffic per token);
+        // otherwise 256 x 64 tiles so that the grid still covers the chip
+        const bool big = ceil_div(Adim, 256) * ceil_div(T, 128) >= 512;
+        const int variant = forced >= 0 ? forced : (big ? 14 : 0);
         return launch_gemm_sp24(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, variant, s);
     }
     return run_dense(A_values, Adim, K, Bm, T, ldb, C, ldc, s);

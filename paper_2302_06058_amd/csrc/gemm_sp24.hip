@@ -76,13 +76,23 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WAVES_M, wn = wave / WAVES_M;
     const int l32 = lane & 31, h = lane >> 5;
-    const int64_t a0 = static_cast<int64_t>(blockIdx.x % tiles_a) * BM;
-    const int64_t t0 = static_cast<int64_t>(blockIdx.x / tiles_a) * BN;
+    // Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2, so
+    // XCD x takes the contiguous chunk [x*per_xcd, (x+1)*per_xcd) of a grouped tile sequence in
+    // which 8 token tiles x consecutive weight tiles run side by side: the ~32 workgroups an
+    // XCD holds at one time share 4 weight tiles and 8 token tiles through that XCD's L2.
+    constexpr int kGroupT = 8;
+    const int64_t tiles_t = ceil_div(T, BN);
+    const int64_t total = tiles_t * tiles_a;
+    const int64_t per_xcd = ceil_div(total, 8);
+    const int64_t n = static_cast<int64_t>(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (n >= total) return;
+    const int64_t grp = n / (static_cast<int64_t>(kGroupT) * tiles_a);
+    const int64_t first_t = grp * kGroupT;
+    const int64_t gsz = (tiles_t - first_t) < kGroupT ? (tiles_t - first_t) : kGroupT;
+    const int64_t within = n - grp * kGroupT * tiles_a;
+    const int64_t a0 = (within / gsz) * BM;
+    const int64_t t0 = (first_t + within % gsz) * BN;
     const int nk = static_cast<int>(ceil_div(K, SK));   // = stages of the padded weight operand
-    // Workgroups walk the contraction in rotated order: at any instant they touch different
-    // k offsets, which spreads the concurrent token-row reads (same row pitch for everyone)
-    // over all memory channels and the weight reads over all L2 lines.
-    const int koff = static_cast<int>((blockIdx.x / tiles_a) % nk);
     const int64_t rt_last = ceil_div(Adim, 32) - 1;
 
     // per-lane source pointers (row tiles / rows clamped at the edges: loaded, never stored)
@@ -120,7 +130,7 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
 
 #define BIMASK_LOAD_STAGE(slot, kt)                                                              \
     {                                                                                            \
-        const int64_t kk = static_cast<int64_t>(((kt) + koff) % nk) * SK;                        \
+        const int64_t kk = static_cast<int64_t>(kt) * SK;                                          \
         _Pragma("unroll") for (int it = 0; it < NB_; ++it) {                                     \
             if constexpr (BGUARD)                                                                \
                 rb[slot][it] = load_guarded(pb[it], kk + 8 * ((tid + NT * it) & 15), K);        \
@@ -131,6 +141,16 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
             _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                     \
                 ra[slot][i][s4] = *reinterpret_cast<const u32x4*>(pa[i] + (kk * 4 + s4 * SK) * 4); \
             rmeta[slot][i] = *reinterpret_cast<const u32x2*>(pm[i] + kk);                        \
+        }                                                                                        \
+    }
+
+#define BIMASK_READ_FRAGS(dst, s4v)                                                              \
+    {                                                                                            \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                         \
+            const int row = wn * WN + j * 32 + l32;                                              \
+            const uint8_t* base = sB + row * kRowBytes;                                          \
+            dst[j].q[0] = *reinterpret_cast<const u32x4*>(base + (((2 * (s4v) + h) ^ (row & 15)) << 4));     \
+            dst[j].q[1] = *reinterpret_cast<const u32x4*>(base + (((8 + 2 * (s4v) + h) ^ (row & 15)) << 4)); \
         }                                                                                        \
     }
 
@@ -148,24 +168,21 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
             BIMASK_LOAD_STAGE(((u) + PF) % NBUF, ktl)                                            \
         }                                                                                        \
         __syncthreads();                                                                         \
+        /* token fragments of instruction s4+1 are requested from LDS before the matrix       \
+           instructions of s4 are issued, so LDS latency hides behind them */                 \
+        BFrag bf[2][TN];                                                                         \
+        BIMASK_READ_FRAGS(bf[0], 0)                                                              \
         _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) {                                       \
-            BFrag bf[TN];                                                                        \
-            _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                     \
-                const int row = wn * WN + j * 32 + l32;                                          \
-                const uint8_t* base = sB + row * kRowBytes;                                      \
-                const int g1 = 2 * s4 + h, g2 = 8 + 2 * s4 + h;                                  \
-                bf[j].q[0] = *reinterpret_cast<const u32x4*>(base + ((g1 ^ (row & 15)) << 4));   \
-                bf[j].q[1] = *reinterpret_cast<const u32x4*>(base + ((g2 ^ (row & 15)) << 4));   \
-            }                                                                                    \
+            if (s4 < 3) BIMASK_READ_FRAGS(bf[(s4 + 1) & 1], s4 + 1)                              \
             _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                     \
                 AFrag af;                                                                        \
                 af.q = ra[u][i][s4];                                                             \
                 const int idx = static_cast<int>(s4 < 2 ? rmeta[u][i].x : rmeta[u][i].y);        \
                 _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                 \
                     if (s4 & 1)                                                                  \
-                        acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[j].v, acc[i][j], idx, 0, 1); \
+                        acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[s4 & 1][j].v, acc[i][j], idx, 0, 1); \
                     else                                                                         \
-                        acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[j].v, acc[i][j], idx, 0, 0); \
+                        acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[s4 & 1][j].v, acc[i][j], idx, 0, 0); \
                 }                                                                                \
             }                                                                                    \
         }                                                                                        \
@@ -189,6 +206,7 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
         if (kt0 + u < nk) BIMASK_STEP(u, kt0 + u, false)
     }
 #undef BIMASK_STEP
+#undef BIMASK_READ_FRAGS
 #undef BIMASK_LOAD_STAGE
 
     // Epilogue: a lane holds 4 consecutive weight rows of one token per accumulator quad;
@@ -235,7 +253,8 @@ int run_sp24_t(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, con
     const bool vecC = aligned16(C) && (ldc * 2) % 16 == 0;
     const int tiles_a = static_cast<int>(ceil_div(Adim, BM));
     const int64_t tiles_t = ceil_div(T, BN);
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(tiles_a * tiles_t)), dim3(64 * WAVES_M * WAVES_N), S::kTotal, s,
+    const int64_t grid = ceil_div(tiles_a * tiles_t, 8) * 8;      // whole rounds over the 8 XCDs
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(64 * WAVES_M * WAVES_N), S::kTotal, s,
                        static_cast<const uint16_t*>(A), meta, Adim, K, static_cast<const uint16_t*>(Bm), T, ldb,
                        static_cast<uint16_t*>(C), ldc, tiles_a, vecC);
     return check_launch();
@@ -268,6 +287,10 @@ int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t 
         case 9: return run_sp24<256, 64, 8, 1, 3>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
         case 10: return run_sp24<256, 32, 8, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
         case 11: return run_sp24<128, 64, 4, 1, 3>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 12: return run_sp24<256, 128, 4, 1, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 13: return run_sp24<256, 128, 8, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 14: return run_sp24<256, 128, 8, 1, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case 15: return run_sp24<256, 128, 4, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
         default: return BIMASK_ERR_UNSUPPORTED;
     }
 }
