@@ -2,6 +2,8 @@
 // of arXiv 2302.06058).  Pure integer work on bit patterns; bound by the HBM read of W.
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace bimask {
 namespace {
 
@@ -50,9 +52,26 @@ __device__ __forceinline__ uint32_t pick4(uint32_t a0, uint32_t a1, uint32_t a2,
     return r;
 }
 
+// Positions p0 < p1 of the two largest magnitudes among four bf16 values packed as
+// w0 = (e1:e0), w1 = (e3:e2); equal magnitudes go to the lower index (Eq. 4 with N:M = 2:4).
+// Each key is magnitude * 4 + (3 - position): the four keys differ, so the two largest keys
+// are exactly the selection, and the second largest of four follows from a 2+2 network.
+__device__ __forceinline__ void top2_of4_bf16(uint32_t w0, uint32_t w1, uint32_t& p0, uint32_t& p1) {
+    const uint32_t k0 = ((w0 & 0x7FFFu) << 2) | 3u;
+    const uint32_t k1 = (((w0 >> 16) & 0x7FFFu) << 2) | 2u;
+    const uint32_t k2 = ((w1 & 0x7FFFu) << 2) | 1u;
+    const uint32_t k3 = ((w1 >> 16) & 0x7FFFu) << 2;
+    const uint32_t hi1 = max(k0, k1), lo1 = min(k0, k1), hi2 = max(k2, k3), lo2 = min(k2, k3);
+    const uint32_t top = max(hi1, hi2);
+    const uint32_t second = max(min(hi1, hi2), max(lo1, lo2));
+    const uint32_t a = top & 3u, b = second & 3u;           // 3 - position
+    p0 = 3u - max(a, b);
+    p1 = 3u - min(a, b);
+}
+
 // ---------------------------------------------------------------------------------
 // Forward direction: one thread owns CH consecutive columns of one row.
-//   MODE 0: mask only   1: + 2:4 compressed values/index   2: + dense masked values
+//   MODE 0: mask only   2: + dense masked values   (2:4 compression: k_forward24 below)
 // mask_in != nullptr: the mask is read instead of selected (stand-alone compression).
 // ---------------------------------------------------------------------------------
 template <typename DT, int M, int CH>
@@ -69,7 +88,6 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
     const int64_t i = id / cpr;
     const int c = static_cast<int>(id - i * cpr);
     const int64_t j0 = static_cast<int64_t>(c) * CH;
-    // mode 1 also covers the zero padding of the fragment-major operand (rows >= I, cols >= J)
     const bool in_row = i < I;
     const bool in_mask = in_row && c < wpr * (32 / CH);
     const raw* row = W + (in_row ? i : 0) * ldw;
@@ -104,40 +122,7 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
         else reinterpret_cast<uint16_t*>(B_bits)[i * wpr * 2 + c] = static_cast<uint16_t>(bits);
     }
 
-    if (mode == 1) {
-        if constexpr (M == 4 && CH == 8) {
-            raw out[4];
-            uint32_t nibs = 0;
-#pragma unroll
-            for (int g = 0; g < 2; ++g) {
-                const uint32_t mb = (bits >> (4 * g)) & 15u;
-                const uint32_t sel = complete_slots<4>(mb, 2);
-                const int p0 = __builtin_ctz(sel), p1 = 31 - __builtin_clz(sel);
-                const uint32_t e0 = elem<DT>(w[0], 4 * g + 0), e1 = elem<DT>(w[0], 4 * g + 1),
-                               e2 = elem<DT>(w[0], 4 * g + 2), e3 = elem<DT>(w[0], 4 * g + 3);
-                out[2 * g + 0] = static_cast<raw>(((mb >> p0) & 1u) ? pick4(e0, e1, e2, e3, p0) : 0u);
-                out[2 * g + 1] = static_cast<raw>(((mb >> p1) & 1u) ? pick4(e0, e1, e2, e3, p1) : 0u);
-                if (j0 + 4 * g < Jr) nibs |= static_cast<uint32_t>(p0 | (p1 << 2)) << (4 * g);
-            }
-            // four consecutive slots of one lane vector of the fragment-major layout
-            const int64_t ks = static_cast<int64_t>(cpr) / 16;
-            raw* dst = values + tiled_val_off(i, j0 / 2, ks);
-            if (vec_out) {
-                if constexpr (sizeof(raw) == 2) {
-                    uint2 v; v.x = out[0] | (static_cast<uint32_t>(out[1]) << 16); v.y = out[2] | (static_cast<uint32_t>(out[3]) << 16);
-                    *reinterpret_cast<uint2*>(dst) = v;
-                } else {
-                    uint4 v; v.x = out[0]; v.y = out[1]; v.z = out[2]; v.w = out[3];
-                    *reinterpret_cast<uint4*>(dst) = v;
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) dst[e] = out[e];
-            }
-            const int64_t g0 = j0 / 4;
-            reinterpret_cast<uint8_t*>(index)[tiled_idx_word(i, g0, ks) * 4 + ((g0 & 7) >> 1)] = static_cast<uint8_t>(nibs);
-        }
-    } else if (mode == 2) {
+    if (mode == 2) {
         raw* dst = values + i * J + j0;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
@@ -160,6 +145,118 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
                 for (int q = 0; q < 8; ++q)
                     if (j0 + 8 * v + q < J) dst[8 * v + q] = static_cast<raw>(elem<DT>(o, q));
             }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Forward direction, 2:4 with compression (the hot case).  A wavefront owns 8 rows x one
+// 128-column stage: lane (r, q) = (l/8, l%8) reads the 16 weights [16q, 16q+16) of its row
+// (8 lanes cover the row's stage contiguously) and produces exactly one 16-byte lane vector
+// of the fragment-major operand -- the 8 lanes that share q write 128 contiguous bytes --
+// plus 16 mask bits and 16 index bits, which neighbouring lanes merge into whole words.
+// mask_in != nullptr: the mask is read instead of selected (stand-alone compression).
+// ---------------------------------------------------------------------------------
+template <typename DT>
+__global__ void __launch_bounds__(kThreads)
+k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t ldw,
+            const uint32_t* __restrict__ mask_in, uint32_t* __restrict__ B_bits,
+            typename DT::raw* __restrict__ values, uint32_t* __restrict__ index,
+            int wpr, int ks, int64_t row_octets, bool vec_in) {
+    using raw = typename DT::raw;
+    constexpr int PW = Pack<DT>::kWords;
+    constexpr int U = 2;                               // stages per wavefront: 4 loads in flight per lane
+    const int lane = threadIdx.x & 63;
+    const int ksu = (ks + U - 1) / U;
+    const int64_t unit = static_cast<int64_t>(blockIdx.x) * (kThreads / 64) + (threadIdx.x >> 6);
+    if (unit >= row_octets * ksu) return;
+    const int64_t r8 = unit / ksu;
+    const int st0 = static_cast<int>(unit - r8 * ksu) * U;
+    const int q = lane & 7;
+    const int64_t i = r8 * 8 + (lane >> 3);
+    const bool in_row = i < I;
+    const int64_t Jr = in_row ? J : 0;                 // padding rows read nothing
+    const raw* row = W + (in_row ? i : 0) * ldw;
+
+    uint32_t w[U][2][PW];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t j0 = static_cast<int64_t>(st0 + u) * 128 + 16 * q;
+        load8<DT>(row, j0, Jr, vec_in, w[u][0]);
+        load8<DT>(row, j0 + 8, Jr, vec_in, w[u][1]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int st = st0 + u;
+        if (st >= ks) break;                           // wave-uniform
+        const int64_t j0 = static_cast<int64_t>(st) * 128 + 16 * q;
+        const bool in_mask = in_row && (j0 >> 4) < 2 * wpr;      // this lane's half-word exists in B
+        uint32_t bits = 0, nibs = 0;
+        // values: lane vector (row tile i/32, stage st, instruction q%4, lane i%32 + 32*(q/4))
+        raw* dst = values + ((((i >> 5) * ks + st) * 4 + (q & 3)) * 64 + (i & 31) + 32 * (q >> 2)) * 8;
+        bool done = false;
+        if constexpr (sizeof(raw) == 2) {
+            if (!mask_in) {                                // wave-uniform: select and compress in one go
+                uint32_t ow[4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const uint32_t w0 = w[u][g >> 1][(g & 1) * 2], w1 = w[u][g >> 1][(g & 1) * 2 + 1];
+                    uint32_t p0, p1;
+                    top2_of4_bf16(w0, w1, p0, p1);
+                    bits |= ((1u << p0) | (1u << p1)) << (4 * g);
+                    nibs |= (p0 | (p1 << 2)) << (4 * g);
+                    // bytes (2 p0, 2 p0 + 1, 2 p1, 2 p1 + 1) of the 8-byte group
+                    ow[g] = __builtin_amdgcn_perm(w1, w0, 0x01000100u + p0 * 0x0202u + p1 * 0x02020000u);
+                }
+                // groups at or beyond the row end (zero padding): no mask bits, index 0
+                const int64_t left = (Jr - j0) >> 2;
+                const uint32_t vmask = left >= 4 ? 0xFFFFu : (left <= 0 ? 0u : (1u << (4 * static_cast<int>(left))) - 1u);
+                bits &= vmask;
+                nibs &= vmask;
+                *reinterpret_cast<uint4*>(dst) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+                done = true;
+            }
+        }
+        if (!done) {
+            if (mask_in) {
+                if (in_mask) bits = reinterpret_cast<const uint16_t*>(mask_in)[i * wpr * 2 + (j0 >> 4)];
+            } else {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    uint32_t key[4];
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) key[m] = elem<DT>(w[u][g >> 1], (g & 1) * 4 + m) & DT::kAbs;
+                    const uint32_t sel = (j0 + 4 * g < Jr) ? select_top_n<4>(key, 2) : 0u;
+                    bits |= sel << (4 * g);
+                }
+            }
+            uint32_t out[8];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const uint32_t mb = (bits >> (4 * g)) & 15u;
+                const uint32_t sel = complete_slots<4>(mb, 2);
+                const int p0 = __builtin_ctz(sel), p1 = 31 - __builtin_clz(sel);
+                const uint32_t e0 = elem<DT>(w[u][g >> 1], (g & 1) * 4 + 0), e1 = elem<DT>(w[u][g >> 1], (g & 1) * 4 + 1),
+                               e2 = elem<DT>(w[u][g >> 1], (g & 1) * 4 + 2), e3 = elem<DT>(w[u][g >> 1], (g & 1) * 4 + 3);
+                out[2 * g + 0] = ((mb >> p0) & 1u) ? pick4(e0, e1, e2, e3, p0) : 0u;
+                out[2 * g + 1] = ((mb >> p1) & 1u) ? pick4(e0, e1, e2, e3, p1) : 0u;
+                if (j0 + 4 * g < Jr) nibs |= static_cast<uint32_t>(p0 | (p1 << 2)) << (4 * g);
+            }
+            if constexpr (sizeof(raw) == 2) {
+                *reinterpret_cast<uint4*>(dst) = make_uint4(out[0] | (out[1] << 16), out[2] | (out[3] << 16),
+                                                            out[4] | (out[5] << 16), out[6] | (out[7] << 16));
+            } else {
+                reinterpret_cast<uint4*>(dst)[0] = make_uint4(out[0], out[1], out[2], out[3]);
+                reinterpret_cast<uint4*>(dst)[1] = make_uint4(out[4], out[5], out[6], out[7]);
+            }
+        }
+        // index / mask: lanes q and q^1 merge their 16 bits into one word, written by the even lane
+        const uint32_t nib_other = __shfl_xor(nibs, 1, 64), bit_other = __shfl_xor(bits, 1, 64);
+        if (!(q & 1)) {
+            const uint32_t iw = nibs | (nib_other << 16), bw = bits | (bit_other << 16);
+            index[(((i >> 5) * ks + st) * 64 + (i & 31) + 32 * (q >> 2)) * 2 + ((q >> 1) & 1)] = iw;
+            const int64_t word = (j0 >> 5);
+            if (B_bits && in_row && word < wpr) B_bits[i * wpr + word] = bw;
         }
     }
 }
@@ -317,18 +414,178 @@ k_backward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t
     }
 }
 
+// ---------------------------------------------------------------------------------
+// Backward direction, bf16 2:4 with transposed compression (the hot case).  A wavefront owns
+// 32 permuted rows x 64*NO columns and needs no other wavefront: lane (k, c) = (l/8, l%8)
+// owns the block of 4 permuted rows 4k..4k+3 and the column octets c (and c + 8 for NO = 2).
+// Rows of W are gathered through P as contiguous 128*NO-byte segments (8 lanes x 16 bytes).
+// The mask words of B are loaded once per quad of lanes and redistributed with a 4x4 byte
+// transpose inside the quad, so that each lane has the bits of its octet for its 4 rows;
+// the same transpose in the other direction yields whole words of Bbar.  W is ANDed with
+// the expanded mask (this is B (.) W of Eq. 9), each column's 4 values are brought into one
+// register pair and selected like a forward group.  Transposed values go through a
+// bank-swizzled LDS image of the wavefront's part of the fragment-major operand and leave
+// as 512-byte contiguous runs; the 2-bit indices are transposed across the 8 row-block
+// lanes in registers and stored as whole words.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t quad_transpose_bytes(uint32_t x, int lane) {
+    // lane j of each quad ends with byte j of the four lanes (byte m from lane m); involution
+    uint32_t p = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0xB1, 0xF, 0xF, true));
+    x = __builtin_amdgcn_perm(p, x, (lane & 1) ? 0x03070105u : 0x06020400u);
+    p = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x4E, 0xF, 0xF, true));
+    x = __builtin_amdgcn_perm(p, x, (lane & 2) ? 0x03020706u : 0x05040100u);
+    return x;
+}
+
+// 8x8 transpose of 4-bit fields across the 8 lanes that share lane % 8 (k = lane / 8):
+// lane k ends with field k of every lane, field j coming from lane j.
+__device__ __forceinline__ uint32_t nibble_transpose8(uint32_t x, int k) {
+    uint32_t p = __shfl_xor(x, 32, 64);
+    x = (k & 4) ? ((x & 0xFFFF0000u) | (p >> 16)) : ((x & 0x0000FFFFu) | (p << 16));
+    p = __shfl_xor(x, 16, 64);
+    x = (k & 2) ? ((x & 0xFF00FF00u) | ((p >> 8) & 0x00FF00FFu)) : ((x & 0x00FF00FFu) | ((p << 8) & 0xFF00FF00u));
+    p = __shfl_xor(x, 8, 64);
+    x = (k & 1) ? ((x & 0xF0F0F0F0u) | ((p >> 4) & 0x0F0F0F0Fu)) : ((x & 0x0F0F0F0Fu) | ((p << 4) & 0xF0F0F0F0u));
+    return x;
+}
+
+template <int NO>
+__global__ void __launch_bounds__(kThreads)
+k_backward24_bf16(const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t ldw,
+                  const uint32_t* __restrict__ B_bits, const int32_t* __restrict__ perm,
+                  uint32_t* __restrict__ Bbar_bits, uint16_t* __restrict__ values,
+                  uint32_t* __restrict__ index, int wpr, int64_t col_tiles, int64_t units,
+                  bool vec_in, bool vec_perm) {
+    constexpr int TC = 64 * NO;
+    // per wavefront: 2*NO output row tiles x 2 instruction slots x 32 lanes x 16 bytes
+    __shared__ uint4 lds[kThreads / 64][NO * 128];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 7, k = lane >> 3;
+    const int64_t unit = static_cast<int64_t>(blockIdx.x) * (blockDim.x >> 6) + wave;
+    const bool active = unit < units;
+    const int64_t rg = active ? unit / col_tiles : 0;
+    const int64_t c0 = (active ? unit - rg * col_tiles : 0) * TC;
+    const int64_t r0 = rg * 32, rb = r0 + 4 * k;
+    const bool row_ok = active && rb < I;
+    const int64_t Jr = row_ok ? J : 0;                   // rows beyond I (stage padding) read nothing
+
+    int64_t src[4] = {0, 0, 0, 0};
+    if (row_ok) {
+        if (!perm) {
+#pragma unroll
+            for (int m = 0; m < 4; ++m) src[m] = rb + m;
+        } else if (vec_perm) {
+            const int4 pv = *reinterpret_cast<const int4*>(perm + rb);
+            src[0] = pv.x; src[1] = pv.y; src[2] = pv.z; src[3] = pv.w;
+        } else {
+#pragma unroll
+            for (int m = 0; m < 4; ++m) src[m] = perm[rb + m];
+        }
+    }
+    uint32_t w[4][NO][4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int o2 = 0; o2 < NO; ++o2)
+            load8<BF16>(W + src[m] * ldw, c0 + 8 * (c + 8 * o2), Jr, vec_in, w[m][o2]);
+
+    // mask bits: lane (a, m) = (c / 4, c % 4) fetches word a (+ 2 for the second octet) of row m
+    const int64_t src_m = (c & 2) ? ((c & 1) ? src[3] : src[2]) : ((c & 1) ? src[1] : src[0]);
+    uint32_t X[NO];
+#pragma unroll
+    for (int o2 = 0; o2 < NO; ++o2) {
+        const int64_t word = c0 / 32 + 2 * o2 + (c >> 2);
+        const uint32_t bw = (row_ok && word < wpr) ? B_bits[src_m * wpr + word] : 0u;
+        X[o2] = quad_transpose_bytes(bw, lane);          // byte m = bits of row m for this lane's octet
+    }
+
+    uint32_t* lds32 = reinterpret_cast<uint32_t*>(lds[wave]);
+    uint32_t nib[NO], R[NO];
+#pragma unroll
+    for (int o2 = 0; o2 < NO; ++o2) {
+        // B (.) W
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t lo = 0u - ((X[o2] >> (8 * m + 2 * j)) & 1u);
+                const uint32_t hi = 0u - ((X[o2] >> (8 * m + 2 * j + 1)) & 1u);
+                w[m][o2][j] &= (lo & 0x0000FFFFu) | (hi & 0xFFFF0000u);
+            }
+        nib[o2] = 0;
+        R[o2] = 0;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int j = q >> 1;
+            const uint32_t half = (q & 1) ? 0x07060302u : 0x05040100u;
+            const uint32_t e01 = __builtin_amdgcn_perm(w[1][o2][j], w[0][o2][j], half);   // (row 1 : row 0)
+            const uint32_t e23 = __builtin_amdgcn_perm(w[3][o2][j], w[2][o2][j], half);   // (row 3 : row 2)
+            uint32_t p0, p1;
+            top2_of4_bf16(e01, e23, p0, p1);
+            const uint32_t ow = __builtin_amdgcn_perm(e23, e01, 0x01000100u + p0 * 0x0202u + p1 * 0x02020000u);
+            nib[o2] |= (p0 | (p1 << 2)) << (4 * q);
+            R[o2] |= (1u << (8 * p0 + q)) | (1u << (8 * p1 + q));       // byte m: columns that select row m
+            // output row = this column; slots 2kb, 2kb+1 of the stage (kb = row block in the stage)
+            const int ul = (((c >> 2) + 2 * o2) * 2 + (k >> 2)) * 32 + 8 * (c & 3) + q;
+            lds32[((ul ^ ((ul >> 4) & 7)) << 2) + (k & 3)] = ow;
+        }
+    }
+
+    // position of this wavefront's 32 rows inside the 128-deep stage of the transposed operand
+    const int64_t ks = ceil_div(I, 128), stage = r0 >> 7;
+    const int kb0 = static_cast<int>(r0 & 127) >> 2;     // first row block: 0, 8, 16 or 24
+    const int lane_half = kb0 >> 4, s4base = (kb0 & 15) >> 2, wd = (kb0 >> 3) & 1;
+
+#pragma unroll
+    for (int o2 = 0; o2 < NO; ++o2) {
+        // Bbar = selection AND B, back to whole words per row
+        const uint32_t back = quad_transpose_bytes(R[o2] & X[o2], lane);
+        const int64_t word = c0 / 32 + 2 * o2 + (c >> 2);
+        if (Bbar_bits && row_ok && word < wpr) Bbar_bits[(rb + (c & 3)) * wpr + word] = back;
+        // indices: columns at or beyond J and padding rows carry index 0
+        const int64_t left = J - (c0 + 8 * (c + 8 * o2));
+        const uint32_t vm = !row_ok || left <= 0 ? 0u : (left >= 8 ? 0xFFFFFFFFu : (1u << (4 * static_cast<int>(left))) - 1u);
+        const uint32_t iw = nibble_transpose8(nib[o2] & vm, k);          // column 8 (c + 8 o2) + k, row blocks kb0..kb0+7
+        const int col = 8 * (c + 8 * o2) + k;
+        if (active && c0 + (col & ~31) < J)
+            index[((c0 / 32 + (col >> 5)) * ks + stage) * 128 + ((col & 31) + 32 * lane_half) * 2 + wd] = iw;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it0 = 0; it0 < 2 * NO; ++it0) {
+        const int it = lane + 64 * it0;                   // (row tile it0, slot it/32 % 2, lane it % 32)
+        const uint4 v = lds[wave][it ^ ((it >> 4) & 7)];
+        if (active && c0 + 32 * it0 < J) {
+            uint16_t* dst = values + ((((c0 / 32 + it0) * ks + stage) * 4 + s4base + ((it >> 5) & 1)) * 64 + (it & 31) + 32 * lane_half) * 8;
+            *reinterpret_cast<uint4*>(dst) = v;
+        }
+    }
+}
+
 template <typename DT, int M>
 int run_forward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const uint32_t* mask_in,
                 uint32_t* B_bits, void* values, uint32_t* index, int mode, hipStream_t s) {
     using raw = typename DT::raw;
     constexpr int CH = M == 16 ? 16 : 8;
     const int wpr = static_cast<int>(ceil_div(J, 32));
-    // mode 1 walks the padded operand (rows to 32, columns to 128) so that its padding is zeroed
-    const int cpr = mode == 1 ? static_cast<int>(round_up(J, 128) / CH) : wpr * 32 / CH;
-    const int64_t rows_pad = mode == 1 ? round_up(I, 32) : I;
-    if (mode == 1 && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
+    if constexpr (M == 4) {
+        if (mode == 1) {
+            if (!aligned16(values) || !aligned16(index)) return BIMASK_ERR_ALIGN;
+            const bool vec_in = aligned16(W) && (ldw * sizeof(raw)) % 16 == 0;
+            const int ks = static_cast<int>(round_up(J, 128) / 128);
+            const int64_t row_octets = round_up(I, 32) / 8;
+            const int64_t units = row_octets * ((ks + 1) / 2);     // one wavefront each (two stages)
+            hipLaunchKernelGGL((k_forward24<DT>), dim3(static_cast<unsigned>(ceil_div(units, kThreads / 64))),
+                               dim3(kThreads), 0, s, static_cast<const raw*>(W), I, J, ldw, mask_in, B_bits,
+                               static_cast<raw*>(values), index, wpr, ks, row_octets, vec_in);
+            return check_launch();
+        }
+    }
+    if (mode == 1) return BIMASK_ERR_NM;               // compressed operands exist for 2:4 only
+    const int cpr = wpr * 32 / CH;
+    const int64_t rows_pad = I;
     const bool vec_in = aligned16(W) && (ldw * sizeof(raw)) % 16 == 0;
-    const bool vec_out = values && aligned16(values) && (mode == 1 || J % 8 == 0);
+    const bool vec_out = values && aligned16(values) && J % 8 == 0;
     const int64_t total = rows_pad * cpr;
     const unsigned grid = static_cast<unsigned>(ceil_div(total, kThreads));
     hipLaunchKernelGGL((k_forward<DT, M, CH>), dim3(grid), dim3(kThreads), 0, s,
@@ -368,6 +625,29 @@ template <typename DT, int M>
 int run_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const uint32_t* B_bits,
                  const uint32_t* Bbar_in, const int32_t* perm, uint32_t* Bbar_bits, void* values,
                  uint32_t* index, int mode, hipStream_t s) {
+    if constexpr (std::is_same<DT, BF16>::value && M == 4) {
+        if (mode == 1 && !Bbar_in) {
+            if (!aligned16(values) || !aligned16(index)) return BIMASK_ERR_ALIGN;
+            const int wpr = static_cast<int>(ceil_div(J, 32));
+            const bool vec_in = aligned16(W) && (ldw * 2) % 16 == 0;
+            const bool vec_perm = perm && aligned16(perm);
+            const int64_t row_groups = ceil_div(I, 128) * 4;            // 32-row groups of the padded stages
+            const uint16_t* Wp = static_cast<const uint16_t*>(W);
+            uint16_t* vp = static_cast<uint16_t*>(values);
+            // wide tiles when they still give every SIMD of the chip a wavefront
+            if (row_groups * ceil_div(J, 128) >= 2048) {
+                const int64_t ct = ceil_div(J, 128), units = row_groups * ct;
+                hipLaunchKernelGGL((k_backward24_bf16<2>), dim3(static_cast<unsigned>(ceil_div(units, 4))), dim3(kThreads),
+                                   0, s, Wp, I, J, ldw, B_bits, perm, Bbar_bits, vp, index, wpr, ct, units, vec_in, vec_perm);
+            } else {
+                // small matrices: one wavefront per workgroup so that the tiles spread over all CUs
+                const int64_t ct = ceil_div(J, 64), units = row_groups * ct;
+                hipLaunchKernelGGL((k_backward24_bf16<1>), dim3(static_cast<unsigned>(units)), dim3(64),
+                                   0, s, Wp, I, J, ldw, B_bits, perm, Bbar_bits, vp, index, wpr, ct, units, vec_in, vec_perm);
+            }
+            return check_launch();
+        }
+    }
     // small matrices: narrow tiles so that the grid still covers the chip
     if (ceil_div(J, 128) * ceil_div(I, kTR) < 256)
         return run_backward_t<DT, M, 32>(W, I, J, ldw, N, B_bits, Bbar_in, perm, Bbar_bits, values, index, mode, s);
