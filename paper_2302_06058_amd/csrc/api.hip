@@ -79,8 +79,7 @@ int bimask_perm_search(const uint32_t* B_bits, int64_t I, int64_t J, int N, int 
     if (I > 0x7FFFFFFFll || J > 0x7FFFFFFFll) return BIMASK_ERR_SHAPE;
     if ((I / M) * J > 0x7FFFFFFFll) return BIMASK_ERR_SHAPE;       // a score must fit int32
     if (!aligned16(perms)) return BIMASK_ERR_ALIGN;
-    const PermPlan pl = plan_perm_search(I, J, K);
-    if (!pl.ok) return BIMASK_ERR_UNSUPPORTED;
+    const PermPlan pl = plan_perm_search(I, J, K, M);
     if (!workspace || workspace_bytes < pl.ws_bytes) return BIMASK_ERR_WORKSPACE;
     return launch_perm_search(B_bits, I, J, N, M, perms, K, scores, best, best_perm, workspace, as_stream(stream));
 }
@@ -171,8 +170,8 @@ size_t bimask_workspace_bytes(int kind, int64_t I, int64_t J, int64_t T, int K, 
     switch (kind) {
         case BIMASK_WS_PERM_SEARCH: {
             if (K <= 0) return 0;
-            const PermPlan pl = plan_perm_search(I, J, K);
-            return pl.ok ? pl.ws_bytes : 0;
+            if (M != 4 && M != 8 && M != 16) return 0;
+            return plan_perm_search(I, J, K, M).ws_bytes;
         }
         case BIMASK_WS_GEMM_FWD:
             return 0;

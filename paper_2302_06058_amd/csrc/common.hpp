@@ -99,15 +99,14 @@ int launch_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int dtype,
                     uint32_t* Bbar_bits, void* values, uint32_t* index, bool want_values, hipStream_t s);
 
 struct PermPlan {
-    int word_bytes;      // 8 or 4: width of one LDS column word
-    int ctw;             // column words per tile
-    int ntiles;          // column tiles
-    int kc;              // candidate chunks (grid = ntiles * kc)
-    size_t lds_bytes;    // dynamic LDS per workgroup
+    int chunks;          // 16-byte chunks per row and slice: 8 (1024 columns) or 32 (4096 columns)
+    int nslices;         // column slices
+    int nseg;            // row-block ranges per (slice, candidate)
+    int sps;             // wavefront steps (8 row blocks each) per range
+    int ntiles;          // nslices * nseg partial scores per candidate
     size_t ws_bytes;     // partial-score scratch
-    bool ok;
 };
-PermPlan plan_perm_search(int64_t I, int64_t J, int K);
+PermPlan plan_perm_search(int64_t I, int64_t J, int K, int M);
 int launch_perm_search(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perms, int K,
                        int32_t* scores, int32_t* best, int32_t* best_perm, void* ws, hipStream_t s);
 

@@ -1,96 +1,135 @@
 // Row-permutation search (Sec. 3.3 / Alg. 1 of arXiv 2302.06058): score K candidate
 // permutations by their number of eligible N:M column blocks and take the first best.
 //
-// A workgroup keeps a column tile of the forward mask -- all I rows x (ctw words) -- in
-// LDS and scores a subset of the candidates on it: per block of M permuted rows the M
-// bit-rows are gathered from LDS, added bit-sliced (one counter per column, all columns
-// of a word at once), compared with N, and the eligible columns are pop-counted.
-// Partial scores per (tile, candidate) go to scratch; a second one-workgroup kernel sums
-// them, takes the arg-max and copies the winning permutation.  Integer only, no atomics:
-// the result is bit-reproducible.
+// The forward mask is cut into column slices of 1024 columns (128 bytes per row, one cache
+// line; 4096 columns when rows do not start on line boundaries).  A wavefront scores one
+// candidate on one slice over a range of row blocks: lane (b, q) = (l / CHL, l % CHL) handles
+// row block b of the current step and 16 bytes of the slice, so one load instruction fetches
+// whole contiguous row segments through the gather P, and the M rows of a block are added
+// bit-sliced (one counter per column, 128 columns per lane at once), compared with N and the
+// eligible columns pop-counted.  Workgroups are numbered so that each XCD works on one slice
+// at a time: the slice then stays in that XCD's L2 for all K candidates and the mask is read
+// from HBM about once.  Partial scores per (slice, row range, candidate) go to scratch; a
+// second one-workgroup kernel sums them, takes the arg-max and copies the winning
+// permutation.  Integer only, no atomics: the result is bit-reproducible.
 #include "common.hpp"
 
 namespace bimask {
 namespace {
 
-constexpr size_t kLdsCap = 144 * 1024;     // of the 160 KB a workgroup may use
-constexpr int kWantGroups = 512;           // enough workgroups for 256 CUs
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 template <int M> struct Planes { static constexpr int L = M == 4 ? 3 : (M == 8 ? 4 : 5); };
 
-template <typename WordT, int M>
+// VEC: rows of the mask start on 16-byte boundaries (whole 16-byte chunks exist or not).
+// CHL: 16-byte chunks per row and slice (8 or 32).  U: row-block groups per step, all in
+// flight at once.  N2OF4: the 2:4 case, where "more than two of four" is a 7-operation
+// boolean formula instead of a bit-sliced adder.
+template <int M, bool VEC, int CHL, int U, bool N2OF4>
 __global__ void __launch_bounds__(kThreads)
-k_perm_score(const uint32_t* __restrict__ B_bits, int64_t I, int64_t J, int wpr32,
-             const int32_t* __restrict__ perms, int K, int N, int kc, int ctw,
+k_perm_score(const uint32_t* __restrict__ B_bits, int I, int64_t J, int wpr32,
+             const int32_t* __restrict__ perms, int K, int N, int nseg, int sps, int64_t items,
              int32_t* __restrict__ partial) {
-    extern __shared__ uint4 smem_u4[];
-    WordT* tile = reinterpret_cast<WordT*>(smem_u4);
-    constexpr int WB = sizeof(WordT) * 8;
     constexpr int L = Planes<M>::L;
-    const int tile_id = blockIdx.x / kc, chunk = blockIdx.x % kc;
+    constexpr int BPS = 64 / CHL;                        // row blocks per load instruction
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // workgroup ids go round-robin over the 8 XCDs: XCD x takes a contiguous range of items
+    const int64_t per_xcd = gridDim.x / 8;
+    const int64_t item = ((blockIdx.x % 8) * per_xcd + blockIdx.x / 8) * (kThreads / 64) + wave;
+    if (item >= items) return;
+    const int seg = static_cast<int>(item % nseg);
+    const int64_t sc = item / nseg;
+    const int c = static_cast<int>(sc % K), slice = static_cast<int>(sc / K);
+    const int bl = lane / CHL, ch = lane % CHL;
+    const int word0 = (slice * CHL + ch) * 4;
 
-    for (int64_t idx = threadIdx.x; idx < I * ctw; idx += kThreads) {
-        const int64_t r = idx / ctw;
-        const int w = static_cast<int>(idx - r * ctw);
-        const int64_t gw = static_cast<int64_t>(tile_id) * ctw + w;
-        WordT v = 0;
-        if constexpr (sizeof(WordT) == 8) {
-            const int64_t w32 = 2 * gw;
-            const uint64_t lo = w32 < wpr32 ? B_bits[r * wpr32 + w32] : 0u;
-            const uint64_t hi = w32 + 1 < wpr32 ? B_bits[r * wpr32 + w32 + 1] : 0u;
-            v = lo | (hi << 32);
-        } else {
-            v = gw < wpr32 ? B_bits[r * wpr32 + gw] : 0u;
-        }
-        tile[idx] = v;
+    // columns at or beyond J never count; words beyond the row are not read (clamped address)
+    uint32_t valid[4];
+    int woff[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const int64_t nv = J - static_cast<int64_t>(word0 + w) * 32;
+        valid[w] = nv >= 32 ? 0xFFFFFFFFu : (nv <= 0 ? 0u : (1u << static_cast<int>(nv)) - 1u);
+        woff[w] = word0 + w < wpr32 ? word0 + w : wpr32 - 1;
     }
-    __syncthreads();
+    const uint32_t* Bs = B_bits + (VEC ? (word0 < wpr32 ? word0 : 0) : 0);
 
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t nblk = I / M;
-    for (int c = chunk + kc * wave; c < K; c += kc * (kThreads / 64)) {
-        const int32_t* P = perms + static_cast<int64_t>(c) * I;
-        int acc = 0;
-        for (int64_t kb = lane; kb < nblk; kb += 64) {
-            int rows[M];
+    const int nblk = I / M, steps = (nblk + BPS * U - 1) / (BPS * U);
+    const int s_begin = seg * sps;
+    const int s_end = s_begin + sps < steps ? s_begin + sps : steps;
+    const int32_t* P = perms + static_cast<int64_t>(c) * I;
+
+    int4 pe[U][M / 4];                                   // permutation entries of the next step
 #pragma unroll
-            for (int v = 0; v < M / 4; ++v) {
-                const int4 q = *reinterpret_cast<const int4*>(P + kb * M + 4 * v);
-                rows[4 * v] = q.x; rows[4 * v + 1] = q.y; rows[4 * v + 2] = q.z; rows[4 * v + 3] = q.w;
+    for (int u = 0; u < U; ++u) {
+        int b = (s_begin * U + u) * BPS + bl;
+        b = b < nblk ? b : nblk - 1;                     // clamped: loaded, counted as nothing
+#pragma unroll
+        for (int v = 0; v < M / 4; ++v) pe[u][v] = *reinterpret_cast<const int4*>(P + static_cast<int64_t>(b) * M + 4 * v);
+    }
+    int acc = 0;
+    for (int s = s_begin; s < s_end; ++s) {
+        u32x4 x[U][M];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const int r = (m & 3) == 0 ? pe[u][m >> 2].x : ((m & 3) == 1 ? pe[u][m >> 2].y
+                            : ((m & 3) == 2 ? pe[u][m >> 2].z : pe[u][m >> 2].w));
+                const uint32_t* row = Bs + static_cast<int64_t>(r) * wpr32;
+                if constexpr (VEC) {
+                    x[u][m] = *reinterpret_cast<const u32x4*>(row);
+                } else {
+                    x[u][m].x = row[woff[0]]; x[u][m].y = row[woff[1]]; x[u][m].z = row[woff[2]]; x[u][m].w = row[woff[3]];
+                }
             }
-            for (int w = 0; w < ctw; ++w) {
-                WordT s[L];
+        const int sn = s + 1 < s_end ? s + 1 : s;        // the last step reloads its own entries
 #pragma unroll
-                for (int p = 0; p < L; ++p) s[p] = 0;
+        for (int u = 0; u < U; ++u) {
+            int b = (sn * U + u) * BPS + bl;
+            b = b < nblk ? b : nblk - 1;
 #pragma unroll
-                for (int m = 0; m < M; ++m) {                    // bit-sliced add of one bit-row
-                    WordT carry = tile[static_cast<int64_t>(rows[m]) * ctw + w];
+            for (int v = 0; v < M / 4; ++v) pe[u][v] = *reinterpret_cast<const int4*>(P + static_cast<int64_t>(b) * M + 4 * v);
+        }
 #pragma unroll
-                    for (int p = 0; p < L; ++p) {
-                        const WordT t = s[p] & carry;
-                        s[p] ^= carry;
-                        carry = t;
+        for (int u = 0; u < U; ++u) {
+            int cnt = 0;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                uint32_t gt;                             // columns whose block holds more than N ones
+                if constexpr (N2OF4) {
+                    const uint32_t a = x[u][0][w], b = x[u][1][w], cc = x[u][2][w], d = x[u][3][w];
+                    gt = (a & b & (cc | d)) | (cc & d & (a | b));
+                } else {
+                    uint32_t sp[L];
+#pragma unroll
+                    for (int p = 0; p < L; ++p) sp[p] = 0;
+#pragma unroll
+                    for (int m = 0; m < M; ++m) {        // bit-sliced add of one bit-row
+                        uint32_t carry = x[u][m][w];
+#pragma unroll
+                        for (int p = 0; p < L; ++p) {
+                            const uint32_t t = sp[p] & carry;
+                            sp[p] ^= carry;
+                            carry = t;
+                        }
+                    }
+                    uint32_t eq = 0xFFFFFFFFu;
+                    gt = 0;
+#pragma unroll
+                    for (int p = L - 1; p >= 0; --p) {
+                        if ((N >> p) & 1) { eq &= sp[p]; }
+                        else { gt |= eq & sp[p]; eq &= ~sp[p]; }
                     }
                 }
-                WordT gt = 0, eq = ~static_cast<WordT>(0);        // per-column count > N
-#pragma unroll
-                for (int p = L - 1; p >= 0; --p) {
-                    if ((N >> p) & 1) { eq &= s[p]; }
-                    else { gt |= eq & s[p]; eq &= ~s[p]; }
-                }
-                const int64_t col0 = (static_cast<int64_t>(tile_id) * ctw + w) * WB;
-                const int64_t nvalid = J - col0;
-                WordT valid = nvalid >= WB ? ~static_cast<WordT>(0)
-                                           : (nvalid <= 0 ? 0 : ((static_cast<WordT>(1) << nvalid) - 1));
-                const WordT ok = ~gt & valid;
-                if constexpr (sizeof(WordT) == 8) acc += __popcll(ok);
-                else acc += __popc(ok);
+                cnt += __popc(~gt & valid[w]);
             }
+            acc += (s * U + u) * BPS + bl < nblk ? cnt : 0;   // a clamped (repeated) block counts nothing
         }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
-        if (lane == 0) partial[static_cast<int64_t>(tile_id) * K + c] = acc;
     }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+    if (lane == 0) partial[(static_cast<int64_t>(slice) * nseg + seg) * K + c] = acc;
 }
 
 // Sums the per-tile partial scores, takes the first arg-max and copies the winner.
@@ -140,60 +179,58 @@ k_perm_final(const int32_t* __restrict__ partial, int ntiles, int K, int64_t I,
     }
 }
 
-template <typename WordT, int M>
+template <int M>
 int run_score(const uint32_t* B_bits, int64_t I, int64_t J, int N, const int32_t* perms, int K,
               const PermPlan& pl, int32_t* partial, hipStream_t s) {
-    auto kern = k_perm_score<WordT, M>;
-    if (pl.lds_bytes > 48 * 1024) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                static_cast<int>(pl.lds_bytes)) != hipSuccess) return BIMASK_ERR_HIP;
-    }
+    constexpr int U = M == 16 ? 1 : 2;
     const int wpr32 = static_cast<int>(ceil_div(J, 32));
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(pl.ntiles * pl.kc)), dim3(kThreads), pl.lds_bytes, s,
-                       B_bits, I, J, wpr32, perms, K, N, pl.kc, pl.ctw, partial);
+    const int64_t items = static_cast<int64_t>(pl.ntiles) * K;
+    const unsigned grid = static_cast<unsigned>(round_up(ceil_div(items, kThreads / 64), 8));
+    const bool vec = aligned16(B_bits) && wpr32 % 4 == 0;
+#define BIMASK_SCORE(VEC, CHL)                                                                               \
+    {                                                                                                        \
+        if (M == 4 && N == 2)                                                                                \
+            hipLaunchKernelGGL((k_perm_score<M, VEC, CHL, U, M == 4>), dim3(grid), dim3(kThreads), 0, s, B_bits, \
+                               static_cast<int>(I), J, wpr32, perms, K, N, pl.nseg, pl.sps, items, partial); \
+        else                                                                                                 \
+            hipLaunchKernelGGL((k_perm_score<M, VEC, CHL, U, false>), dim3(grid), dim3(kThreads), 0, s, B_bits, \
+                               static_cast<int>(I), J, wpr32, perms, K, N, pl.nseg, pl.sps, items, partial); \
+    }
+    if (pl.chunks == 32) { if (vec) BIMASK_SCORE(true, 32) else BIMASK_SCORE(false, 32) }
+    else                 { if (vec) BIMASK_SCORE(true, 8)  else BIMASK_SCORE(false, 8) }
+#undef BIMASK_SCORE
     return check_launch();
 }
 
 }  // namespace
 
-PermPlan plan_perm_search(int64_t I, int64_t J, int K) {
+PermPlan plan_perm_search(int64_t I, int64_t J, int K, int M) {
     PermPlan pl{};
-    pl.ok = false;
-    if (static_cast<size_t>(I) * 8 <= kLdsCap) pl.word_bytes = 8;
-    else if (static_cast<size_t>(I) * 4 <= kLdsCap) pl.word_bytes = 4;
-    else return pl;                                              // the mask column tile must fit in LDS
-    const int64_t nw = ceil_div(J, pl.word_bytes * 8);           // column words per row
-    pl.kc = K < 8 ? K : 8;                                       // candidate chunks; 8 = one per XCD
-    const int64_t ctw_max = static_cast<int64_t>((64 * 1024) / (static_cast<size_t>(I) * pl.word_bytes));
-    const int64_t tiles_wanted = ceil_div(kWantGroups, pl.kc);
-    int64_t ctw = nw / tiles_wanted;
-    if (ctw > ctw_max) ctw = ctw_max;
-    if (ctw < 1) ctw = 1;
-    pl.ctw = static_cast<int>(ctw);
-    pl.ntiles = static_cast<int>(ceil_div(nw, ctw));
-    pl.lds_bytes = static_cast<size_t>(I) * pl.ctw * pl.word_bytes;
+    const int64_t pitch = ceil_div(J, 32) * 4;                   // bytes per mask row
+    pl.chunks = (pitch % 128 != 0 && J >= 4096) ? 32 : 8;
+    if (const char* e = getenv("BIMASK_PERM_CHUNKS")) pl.chunks = atoi(e) == 32 ? 32 : 8;
+    pl.nslices = static_cast<int>(ceil_div(J, pl.chunks * 128));
+    const int U = M == 16 ? 1 : 2;
+    const int64_t steps = ceil_div(I / M, (64 / pl.chunks) * U); // row blocks per wavefront step
+    // about 32 wavefronts per CU, at least 2 steps each
+    int64_t nseg = ceil_div(8192, static_cast<int64_t>(pl.nslices) * K);
+    const int64_t nseg_max = steps / 2 > 1 ? steps / 2 : 1;
+    nseg = nseg < 1 ? 1 : (nseg > nseg_max ? nseg_max : nseg);
+    pl.sps = static_cast<int>(ceil_div(steps, nseg));
+    pl.nseg = static_cast<int>(ceil_div(steps, pl.sps));
+    pl.ntiles = pl.nslices * pl.nseg;
     pl.ws_bytes = static_cast<size_t>(pl.ntiles) * K * sizeof(int32_t);
-    pl.ok = true;
     return pl;
 }
 
 int launch_perm_search(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perms, int K,
                        int32_t* scores, int32_t* best, int32_t* best_perm, void* ws, hipStream_t s) {
-    const PermPlan pl = plan_perm_search(I, J, K);
-    if (!pl.ok) return BIMASK_ERR_UNSUPPORTED;
+    const PermPlan pl = plan_perm_search(I, J, K, M);
     int32_t* partial = static_cast<int32_t*>(ws);
     int rc = BIMASK_ERR_NM;
-#define BIMASK_SCORE(WT, MM) rc = run_score<WT, MM>(B_bits, I, J, N, perms, K, pl, partial, s)
-    if (pl.word_bytes == 8) {
-        if (M == 4) BIMASK_SCORE(uint64_t, 4);
-        else if (M == 8) BIMASK_SCORE(uint64_t, 8);
-        else if (M == 16) BIMASK_SCORE(uint64_t, 16);
-    } else {
-        if (M == 4) BIMASK_SCORE(uint32_t, 4);
-        else if (M == 8) BIMASK_SCORE(uint32_t, 8);
-        else if (M == 16) BIMASK_SCORE(uint32_t, 16);
-    }
-#undef BIMASK_SCORE
+    if (M == 4) rc = run_score<4>(B_bits, I, J, N, perms, K, pl, partial, s);
+    else if (M == 8) rc = run_score<8>(B_bits, I, J, N, perms, K, pl, partial, s);
+    else if (M == 16) rc = run_score<16>(B_bits, I, J, N, perms, K, pl, partial, s);
     if (rc != BIMASK_OK) return rc;
     hipLaunchKernelGGL(k_perm_final, dim3(1), dim3(kFinalThreads), 0, s, partial, pl.ntiles, K, I, perms, scores, best,
                        best_perm);
