@@ -208,7 +208,6 @@ PermPlan plan_perm_search(int64_t I, int64_t J, int K, int M) {
     PermPlan pl{};
     const int64_t pitch = ceil_div(J, 32) * 4;                   // bytes per mask row
     pl.chunks = (pitch % 128 != 0 && J >= 4096) ? 32 : 8;
-    if (const char* e = getenv("BIMASK_PERM_CHUNKS")) pl.chunks = atoi(e) == 32 ? 32 : 8;
     pl.nslices = static_cast<int>(ceil_div(J, pl.chunks * 128));
     const int U = M == 16 ? 1 : 2;
     const int64_t steps = ceil_div(I / M, (64 / pl.chunks) * U); // row blocks per wavefront step

@@ -146,6 +146,32 @@ def test_degenerate_shapes(dtype):
     check_layer(I=16, J=16, N=1, M=16, dtype=dtype, K=2, seed=404, T=3)
 
 
+@pytest.mark.parametrize("I,J,N,M", [
+    (64, 4224, 2, 4),     # row pitch 528 B: not a multiple of 128 -> wide slices, 16-byte row starts
+    (32, 4360, 2, 4),     # 137 words per row: rows not 16-byte aligned, wide slices, ragged last slice
+    (96, 2080, 2, 4),     # narrow slices, ragged last slice (2080 = 2 * 1024 + 32)
+    (136, 1032, 4, 8),    # M = 8, row blocks not a multiple of the per-step group
+    (208, 1040, 1, 16),   # M = 16
+])
+def test_perm_search_slice_paths(I, J, N, M):
+    rng = np.random.default_rng(700 + J)
+    Bo = np.zeros((I, J), dtype=np.uint8)
+    for g in range(J // M):                                   # any N-per-group mask will do here
+        idx = np.argsort(rng.random((I, M)), axis=1)[:, :N]
+        np.put_along_axis(Bo[:, g * M:(g + 1) * M], idx, 1, axis=1)
+    perms = perms_of(I, 13, 701 + J)
+    wpr = (J + 31) // 32
+    bits = np.zeros((I, wpr * 32), dtype=np.uint8)
+    bits[:, :J] = Bo
+    words = (bits.reshape(I, wpr, 32).astype(np.uint64) << np.arange(32, dtype=np.uint64)).sum(axis=2).astype(np.uint32)
+    B = i32_dev(words.view(np.int32))
+    scores, best, best_perm = bm.bimask_perm_search(B, I, J, N, M, i32_dev(perms))
+    sc_o = oracle.perm_scores(Bo, perms, N, M)
+    assert (scores.cpu().numpy() == sc_o).all()
+    assert int(best.item()) == oracle.argmax_first(sc_o)
+    assert (best_perm.cpu().numpy() == perms[int(best.item())]).all()
+
+
 def test_duplicate_candidates_pick_the_first():
     I, J, N, M = 64, 128, 2, 4
     Wh = make_w(I, J, synth.BF16, 501)
