@@ -12,8 +12,8 @@
 //     double-buffered XOR-swizzled LDS tile and read back as 16-byte fragments;
 //   * PF stages of both operands are kept in flight in registers, so a workgroup has
 //     PF * (BM*72 + BN*256) bytes outstanding to hide HBM latency;
-//   * fp32 accumulators are rounded to bf16 and, after a swap between the two lane halves,
-//     written straight from registers as 16-byte row-contiguous stores.
+//   * fp32 accumulators are rounded to bf16, regrouped by a swap between the two lane halves
+//     and a pass through LDS, and written as whole row segments with streaming stores.
 // Lane/operand mapping of v_smfmac_f32_32x32x32_bf16 (checked on the device): lane l holds
 // weight row l%32; with h = l/32, compressed element e of the A register pairs with slot
 // 8h + 4((e%4)/2) + idx_e of the B register of token lane half e/4, and idx_e sits in bits
@@ -211,12 +211,16 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
 
     // Epilogue: a lane holds 4 consecutive weight rows of one token per accumulator quad;
     // swapping quads between the two lane halves gives every lane 8 consecutive bf16
-    // (16 bytes) of its token row, stored straight from registers.
+    // (16 bytes) of its token row.  The tile goes through LDS (the stage buffers are free now)
+    // so that it leaves as whole 2*BM-byte row segments with streaming stores: full lines go
+    // straight to memory and neither evict the operands from L2 nor wait there as dirty lines.
+    static_assert(BN * BM * 2 <= S::kTotal, "output tile must fit the stage buffers");
+    __syncthreads();                                     // every wavefront is done with the last stage
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const int64_t t = t0 + wn * WN + j * 32 + l32;
+            const int t = wn * WN + j * 32 + l32;
 #pragma unroll
             for (int p = 0; p < 2; ++p) {
                 const uint32_t xlo = pack_bf16(acc[i][j][8 * p + 0], acc[i][j][8 * p + 1]);
@@ -226,19 +230,28 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
                 const auto slo = __builtin_amdgcn_permlane32_swap(xlo, ylo, false, false);
                 const auto shi = __builtin_amdgcn_permlane32_swap(xhi, yhi, false, false);
                 const u32x4 v = {slo[0], shi[0], slo[1], shi[1]};
-                const int64_t a = a0 + wm * WM + i * 32 + 16 * p + 8 * h;
-                if (t < T && a < Adim) {
-                    uint16_t* dst = C + t * ldc + a;
-                    if (vecC && a + 8 <= Adim) {
-                        *reinterpret_cast<u32x4*>(dst) = v;
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (a + e < Adim) dst[e] = static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1)));
-                    }
-                }
+                const int u = (wm * WM + i * 32 + 16 * p + 8 * h) >> 3;      // 16-byte unit of the row
+                *reinterpret_cast<u32x4*>(smem + t * (BM * 2) + ((u ^ (2 * (t & 15))) << 4)) = v;
             }
         }
+    __syncthreads();
+    constexpr int UPR = BM / 8;                          // 16-byte units per tile row
+#pragma unroll
+    for (int it = 0; it < BN * UPR / NT; ++it) {
+        const int q = tid + NT * it, t = q / UPR, u = q % UPR;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(smem + t * (BM * 2) + ((u ^ (2 * (t & 15))) << 4));
+        const int64_t a = a0 + 8 * u;
+        if (t0 + t < T && a < Adim) {
+            uint16_t* dst = C + (t0 + t) * ldc + a;
+            if (vecC && a + 8 <= Adim) {
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (a + e < Adim) dst[e] = static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+    }
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD>

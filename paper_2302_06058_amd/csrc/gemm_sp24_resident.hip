@@ -9,9 +9,9 @@
 // memory.  It then walks over ALL weight-row tiles: the fragment-major compressed weights
 // stream from L2 straight into the sparse matrix instruction's A registers (prefetched one
 // weight tile ahead), the token fragments come from the resident tile (registers when the
-// contraction is at most 256 long, LDS otherwise), and every finished output strip is
-// stored straight from the accumulators after a cross-half lane swap that gives each lane
-// 16 contiguous bytes of its token row.  After the tile fill no barrier is needed.
+// contraction is at most 256 long, LDS otherwise), and every finished output strip
+// leaves through a double-buffered LDS tile as whole 512-byte row segments written with
+// streaming stores (one barrier per weight tile).
 // Token tiles have a run-time height (<= BN) so that the grid can be cut to the CU count.
 #include "common.hpp"
 
@@ -31,7 +31,8 @@ template <int BM, int BN, int NSTG>
 struct ResSmem {
     static constexpr int kB = NSTG * BN * 256;          // resident token tile, 256 B per row and stage
     static constexpr int kInv = NSTG * 128 * 2;         // inverse permutation (int16)
-    static constexpr int kTotal = kB + kInv;
+    static constexpr int kOut = BN * BM * 2;            // one bf16 output tile (two of them: double buffer)
+    static constexpr int kTotal = kB + kInv + 2 * kOut;
 };
 
 // byte offset of element (t, r) of the resident tile
@@ -178,9 +179,13 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
                 }                                                                                \
             }                                                                                    \
         }                                                                                        \
-        /* Output: a lane holds 4 consecutive weight rows of one token per accumulator quad;  \
-           swapping quads between the two lane halves gives every lane 8 consecutive bf16     \
-           (16 bytes) of its token row, stored straight from registers: no LDS, no barrier. */ \
+        /* Output.  A lane holds 4 consecutive weight rows of one token per accumulator quad;   \
+           swapping quads between the two lane halves gives every lane 8 consecutive bf16       \
+           (16 bytes) of its token row.  The tile is staged through LDS (double-buffered, one   \
+           barrier per weight tile) so that it leaves as whole 512-byte row segments with        \
+           streaming stores: full-line writes go straight to memory instead of piling up as      \
+           dirty lines in L2 that the end of the kernel has to wait for. */                      \
+        uint8_t* stg = sB + S::kB + S::kInv + ((at) & 1) * S::kOut;                              \
         _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
             _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                     \
                 const int t = j * 32 + l32;                                                      \
@@ -192,18 +197,26 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
                     const auto slo = __builtin_amdgcn_permlane32_swap(xlo, ylo, false, false);   \
                     const auto shi = __builtin_amdgcn_permlane32_swap(xhi, yhi, false, false);   \
                     const u32x4 v = {slo[0], shi[0], slo[1], shi[1]};                            \
-                    const int64_t a = static_cast<int64_t>(at) * BM + wm * WM + i * 32 + 16 * p + 8 * h; \
-                    if (t < rows && a < Adim) {                                                  \
-                        uint16_t* dst = C + (t0 + t) * ldc + a;                                  \
-                        if (vecC && a + 8 <= Adim) {                                             \
-                            *reinterpret_cast<u32x4*>(dst) = v;                                  \
-                        } else {                                                                 \
-                            _Pragma("unroll") for (int e = 0; e < 8; ++e)                        \
-                                if (a + e < Adim) dst[e] = static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1))); \
-                        }                                                                        \
-                    }                                                                            \
+                    const int u = (wm * WM + i * 32 + 16 * p + 8 * h) >> 3;   /* 16-byte unit of the row */ \
+                    *reinterpret_cast<u32x4*>(stg + t * (BM * 2) + ((u ^ (2 * (t & 15))) << 4)) = v; \
                 }                                                                                \
             }                                                                                    \
+        __syncthreads();                                                                         \
+        constexpr int UPR = BM / 8;                          /* 16-byte units per tile row */    \
+        _Pragma("unroll") for (int it = 0; it < BN * UPR / NT; ++it) {                           \
+            const int q = tid + NT * it, t = q / UPR, u = q % UPR;                               \
+            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + t * (BM * 2) + ((u ^ (2 * (t & 15))) << 4)); \
+            const int64_t a = static_cast<int64_t>(at) * BM + 8 * u;                             \
+            if (t < rows && a < Adim) {                                                          \
+                uint16_t* dst = C + (t0 + t) * ldc + a;                                          \
+                if (vecC && a + 8 <= Adim) {                                                     \
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));               \
+                } else {                                                                         \
+                    _Pragma("unroll") for (int e = 0; e < 8; ++e)                                \
+                        if (a + e < Adim) dst[e] = static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1))); \
+                }                                                                                \
+            }                                                                                    \
+        }                                                                                        \
     }
 
     int at = 0;

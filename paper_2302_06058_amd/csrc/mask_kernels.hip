@@ -7,6 +7,8 @@
 namespace bimask {
 namespace {
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // native 16-byte register vector
+
 // ---------------------------------------------------------------------------------
 // small register helpers
 // ---------------------------------------------------------------------------------
@@ -213,7 +215,8 @@ k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_
                 const uint32_t vmask = left >= 4 ? 0xFFFFu : (left <= 0 ? 0u : (1u << (4 * static_cast<int>(left))) - 1u);
                 bits &= vmask;
                 nibs &= vmask;
-                *reinterpret_cast<uint4*>(dst) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+                // whole 128-byte lines per 8 lanes: streaming store (nothing here is read again by this kernel)
+                __builtin_nontemporal_store((u32x4){ow[0], ow[1], ow[2], ow[3]}, reinterpret_cast<u32x4*>(dst));
                 done = true;
             }
         }
@@ -554,10 +557,10 @@ k_backward24_bf16(const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t 
 #pragma unroll
     for (int it0 = 0; it0 < 2 * NO; ++it0) {
         const int it = lane + 64 * it0;                   // (row tile it0, slot it/32 % 2, lane it % 32)
-        const uint4 v = lds[wave][it ^ ((it >> 4) & 7)];
+        const u32x4 v = reinterpret_cast<const u32x4*>(lds[wave])[it ^ ((it >> 4) & 7)];
         if (active && c0 + 32 * it0 < J) {
             uint16_t* dst = values + ((((c0 / 32 + it0) * ks + stage) * 4 + s4base + ((it >> 5) & 1)) * 64 + (it & 31) + 32 * lane_half) * 8;
-            *reinterpret_cast<uint4*>(dst) = v;
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));     // 512-byte runs, whole lines
         }
     }
 }
