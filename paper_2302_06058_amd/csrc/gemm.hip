@@ -272,6 +272,105 @@ k_gather_cols(const raw* __restrict__ in, int64_t T, int64_t ld, const int32_t* 
     }
 }
 
+// Same result, for rows that fit in LDS: a workgroup reads `rows` whole token rows with
+// contiguous 16-byte lanes, keeps them in LDS, and every thread assembles 16-byte pieces of
+// the permuted rows from 2- or 4-byte LDS reads.  Both global streams are fully coalesced.
+// CPT > 0 (long rows): the grid is persistent, a thread owns the same CPT 16-byte output
+// columns in every row tile and keeps their permutation entries in registers, so the
+// permutation is read once per workgroup instead of once per row tile.
+template <typename raw, int CPT>
+__global__ void __launch_bounds__(kThreads)
+k_gather_cols_lds(const raw* __restrict__ in, int64_t T, int64_t ld, const int32_t* __restrict__ perm, int64_t I,
+                  raw* __restrict__ out, int rows, bool vec_in, bool vec_out) {
+    constexpr int E = 16 / sizeof(raw);
+    constexpr int NP = CPT > 0 ? CPT : 1;
+    extern __shared__ uint4 gather_smem[];
+    raw* buf = reinterpret_cast<raw*>(gather_smem);
+    const int chunks = static_cast<int>(ceil_div(I, E));
+    const int Ipad = chunks * E;
+    const int64_t ntiles = ceil_div(T, rows);
+    int p[NP][E];
+    if constexpr (CPT > 0) {
+#pragma unroll
+        for (int k = 0; k < CPT; ++k) {
+            const int c = threadIdx.x + kThreads * k;
+#pragma unroll
+            for (int e = 0; e < E; ++e) p[k][e] = (c * E + e < I) ? perm[c * E + e] : 0;
+        }
+    }
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t t0 = tile * rows;
+        const int nrows = static_cast<int>((T - t0) < rows ? (T - t0) : rows);
+        for (int idx = threadIdx.x; idx < nrows * chunks; idx += kThreads) {
+            const int row = idx / chunks, c = idx - row * chunks;
+            const raw* src = in + (t0 + row) * ld + static_cast<int64_t>(c) * E;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (vec_in && (c + 1) * E <= I) {
+                v = *reinterpret_cast<const uint4*>(src);
+            } else {
+                uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int e = 0; e < E; ++e)
+                    if (c * E + e < I) {
+                        if constexpr (sizeof(raw) == 2) w[e >> 1] |= static_cast<uint32_t>(src[e]) << (16 * (e & 1));
+                        else w[e] = src[e];
+                    }
+                v = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+            *reinterpret_cast<uint4*>(buf + static_cast<int64_t>(row) * Ipad + c * E) = v;
+        }
+        __syncthreads();
+        auto emit = [&](int c, const int (&pc)[E]) {
+            for (int row = 0; row < nrows; ++row) {
+                const raw* r = buf + static_cast<int64_t>(row) * Ipad;
+                uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    const uint32_t x = r[pc[e]];
+                    if constexpr (sizeof(raw) == 2) w[e >> 1] |= x << (16 * (e & 1));
+                    else w[e] = x;
+                }
+                raw* dst = out + (t0 + row) * I + static_cast<int64_t>(c) * E;
+                if (vec_out && (c + 1) * E <= I) {
+                    *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < E; ++e)
+                        if (c * E + e < I) {
+                            if constexpr (sizeof(raw) == 2) dst[e] = static_cast<raw>(w[e >> 1] >> (16 * (e & 1)));
+                            else dst[e] = w[e];
+                        }
+                }
+            }
+        };
+        if constexpr (CPT > 0) {
+#pragma unroll
+            for (int k = 0; k < CPT; ++k) {
+                const int c = threadIdx.x + kThreads * k;
+                if (c < chunks) emit(c, p[k]);
+            }
+        } else {
+            for (int c = threadIdx.x; c < chunks; c += kThreads) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) p[0][e] = (c * E + e < I) ? perm[c * E + e] : 0;
+                emit(c, p[0]);
+            }
+        }
+        __syncthreads();                                 // the tile buffer is reused by the next row tile
+    }
+}
+
+template <typename raw, int CPT>
+int run_gather_lds(const void* dY, int64_t T, int64_t ld, const int32_t* perm, int64_t I, void* out, int rows,
+                   size_t lds, unsigned grid, bool vec_in, bool vec_out, hipStream_t s) {
+    auto kern = k_gather_cols_lds<raw, CPT>;
+    if (lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess) return BIMASK_ERR_HIP;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, static_cast<const raw*>(dY), T, ld, perm, I,
+                       static_cast<raw*>(out), rows, vec_in, vec_out);
+    return check_launch();
+}
+
 template <bool FAST, int BM, int BN, int WAVES_M, int WAVES_N>
 int run_dense_t(const void* A, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb, void* C,
                 int64_t ldc, hipStream_t s) {
@@ -303,6 +402,35 @@ int run_dense(const void* A, int64_t Adim, int64_t K, const void* Bm, int64_t T,
 
 int launch_gather_cols(const void* dY, int64_t T, int64_t ld, const int32_t* perm, int64_t I, int dtype,
                        void* out, hipStream_t s) {
+    const size_t esz = dtype == BIMASK_BF16 ? 2 : 4;
+    const int64_t E = 16 / static_cast<int64_t>(esz);
+    const size_t row_bytes = static_cast<size_t>(round_up(I, E)) * esz;
+    if (row_bytes <= 64 * 1024) {
+        // rows kept in LDS: as many as fit in 64 KB, but enough workgroups to fill the chip
+        int64_t rows = static_cast<int64_t>((64 * 1024) / row_bytes);
+        if (rows > 32) rows = 32;
+        while (rows > 1 && ceil_div(T, rows) < 1024) rows /= 2;
+        const size_t lds = static_cast<size_t>(rows) * row_bytes;
+        const bool vec_in = aligned16(dY) && (ld * esz) % 16 == 0;
+        const bool vec_out = aligned16(out) && (I * esz) % 16 == 0;
+        const int64_t ntiles = ceil_div(T, rows);
+        const int64_t cpt = ceil_div(ceil_div(I, E), kThreads);      // 16-byte output columns per thread
+        // long rows: persistent grid (3 workgroups per CU), permutation entries in registers
+        const bool persistent = cpt >= 2 && cpt <= 8;
+        const unsigned grid = static_cast<unsigned>(persistent && ntiles > 768 ? 768 : ntiles);
+        const int r = static_cast<int>(rows);
+#define BIMASK_GATHER(RAW)                                                                                       \
+        {                                                                                                        \
+            if (!persistent) return run_gather_lds<RAW, 0>(dY, T, ld, perm, I, out, r, lds, grid, vec_in, vec_out, s); \
+            if (cpt <= 2) return run_gather_lds<RAW, 2>(dY, T, ld, perm, I, out, r, lds, grid, vec_in, vec_out, s);    \
+            if (cpt <= 4) return run_gather_lds<RAW, 4>(dY, T, ld, perm, I, out, r, lds, grid, vec_in, vec_out, s);    \
+            if (cpt <= 6) return run_gather_lds<RAW, 6>(dY, T, ld, perm, I, out, r, lds, grid, vec_in, vec_out, s);    \
+            return run_gather_lds<RAW, 8>(dY, T, ld, perm, I, out, r, lds, grid, vec_in, vec_out, s);                  \
+        }
+        if (dtype == BIMASK_BF16) BIMASK_GATHER(uint16_t)
+        BIMASK_GATHER(uint32_t)
+#undef BIMASK_GATHER
+    }
     if (dtype == BIMASK_BF16) {
         const int64_t total = T * ceil_div(I, 8);
         const bool vec = aligned16(out) && (I * 2) % 16 == 0;
