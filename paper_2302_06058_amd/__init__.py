@@ -129,6 +129,24 @@ def _index_shape(rows: int, cols: int, N: int, M: int):
     return (operand_index_words(rows, cols, N, M),)
 
 
+def prepare(name: str, *args):
+    """Bind one call of include/bimask.h to already marshalled arguments.
+
+    `args` are exactly the C arguments, in order; tensors are replaced by their device
+    addresses once, here.  The returned callable issues the C call and checks its status,
+    nothing else: for launch-bound loops where the per-call marshalling of the wrappers
+    below (shape checks, pointer and stream look-ups) would cost more than the kernels.
+    The caller keeps the tensors alive and passes the stream handle explicitly."""
+    fn = getattr(lib(), name)
+    cargs = tuple(a.data_ptr() if hasattr(a, "data_ptr") else a for a in args)
+
+    def call():
+        st = fn(*cargs)
+        if st:
+            raise BimaskError(name, st)
+    return call
+
+
 # -- the calls of include/bimask.h -----------------------------------------------------
 def bimask_forward_mask(W, N: int, M: int, B_bits=None):
     import torch

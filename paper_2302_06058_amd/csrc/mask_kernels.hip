@@ -9,6 +9,10 @@ namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // native 16-byte register vector
 
+// Compressed operands up to this size are written with ordinary stores so that the GEMM that
+// follows finds them in L2 (4 MB per XCD); larger ones are streamed to memory.
+constexpr size_t kL2Keep = 2u << 20;
+
 // ---------------------------------------------------------------------------------
 // small register helpers
 // ---------------------------------------------------------------------------------
@@ -164,7 +168,7 @@ __global__ void __launch_bounds__(kThreads)
 k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t ldw,
             const uint32_t* __restrict__ mask_in, uint32_t* __restrict__ B_bits,
             typename DT::raw* __restrict__ values, uint32_t* __restrict__ index,
-            int wpr, int ks, int64_t row_octets, bool vec_in) {
+            int wpr, int ks, int64_t row_octets, bool vec_in, bool stream_out) {
     using raw = typename DT::raw;
     constexpr int PW = Pack<DT>::kWords;
     constexpr int U = 2;                               // stages per wavefront: 4 loads in flight per lane
@@ -215,8 +219,11 @@ k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_
                 const uint32_t vmask = left >= 4 ? 0xFFFFu : (left <= 0 ? 0u : (1u << (4 * static_cast<int>(left))) - 1u);
                 bits &= vmask;
                 nibs &= vmask;
-                // whole 128-byte lines per 8 lanes: streaming store (nothing here is read again by this kernel)
-                __builtin_nontemporal_store((u32x4){ow[0], ow[1], ow[2], ow[3]}, reinterpret_cast<u32x4*>(dst));
+                // whole 128-byte lines per 8 lanes; streamed past L2 when the operand is too large to
+                // wait there for the GEMM anyway
+                const u32x4 ov = {ow[0], ow[1], ow[2], ow[3]};
+                if (stream_out) __builtin_nontemporal_store(ov, reinterpret_cast<u32x4*>(dst));
+                else *reinterpret_cast<u32x4*>(dst) = ov;
                 done = true;
             }
         }
@@ -458,7 +465,7 @@ k_backward24_bf16(const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t 
                   const uint32_t* __restrict__ B_bits, const int32_t* __restrict__ perm,
                   uint32_t* __restrict__ Bbar_bits, uint16_t* __restrict__ values,
                   uint32_t* __restrict__ index, int wpr, int64_t col_tiles, int64_t units,
-                  bool vec_in, bool vec_perm) {
+                  bool vec_in, bool vec_perm, bool stream_out) {
     constexpr int TC = 64 * NO;
     // per wavefront: 2*NO output row tiles x 2 instruction slots x 32 lanes x 16 bytes
     __shared__ uint4 lds[kThreads / 64][NO * 128];
@@ -560,7 +567,9 @@ k_backward24_bf16(const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t 
         const u32x4 v = reinterpret_cast<const u32x4*>(lds[wave])[it ^ ((it >> 4) & 7)];
         if (active && c0 + 32 * it0 < J) {
             uint16_t* dst = values + ((((c0 / 32 + it0) * ks + stage) * 4 + s4base + ((it >> 5) & 1)) * 64 + (it & 31) + 32 * lane_half) * 8;
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));     // 512-byte runs, whole lines
+            // 512-byte runs, whole lines; streamed past L2 for operands too large to stay there
+            if (stream_out) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
+            else *reinterpret_cast<u32x4*>(dst) = v;
         }
     }
 }
@@ -580,7 +589,8 @@ int run_forward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const u
             const int64_t units = row_octets * ((ks + 1) / 2);     // one wavefront each (two stages)
             hipLaunchKernelGGL((k_forward24<DT>), dim3(static_cast<unsigned>(ceil_div(units, kThreads / 64))),
                                dim3(kThreads), 0, s, static_cast<const raw*>(W), I, J, ldw, mask_in, B_bits,
-                               static_cast<raw*>(values), index, wpr, ks, row_octets, vec_in);
+                               static_cast<raw*>(values), index, wpr, ks, row_octets, vec_in,
+                               static_cast<size_t>(I) * J * sizeof(raw) / 2 > kL2Keep);
             return check_launch();
         }
     }
@@ -637,16 +647,17 @@ int run_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const 
             const int64_t row_groups = ceil_div(I, 128) * 4;            // 32-row groups of the padded stages
             const uint16_t* Wp = static_cast<const uint16_t*>(W);
             uint16_t* vp = static_cast<uint16_t*>(values);
+            const bool stream_out = static_cast<size_t>(I) * J > kL2Keep;     // operand bytes = I*J*2/2
             // wide tiles when they still give every SIMD of the chip a wavefront
             if (row_groups * ceil_div(J, 128) >= 2048) {
                 const int64_t ct = ceil_div(J, 128), units = row_groups * ct;
                 hipLaunchKernelGGL((k_backward24_bf16<2>), dim3(static_cast<unsigned>(ceil_div(units, 4))), dim3(kThreads),
-                                   0, s, Wp, I, J, ldw, B_bits, perm, Bbar_bits, vp, index, wpr, ct, units, vec_in, vec_perm);
+                                   0, s, Wp, I, J, ldw, B_bits, perm, Bbar_bits, vp, index, wpr, ct, units, vec_in, vec_perm, stream_out);
             } else {
                 // small matrices: one wavefront per workgroup so that the tiles spread over all CUs
                 const int64_t ct = ceil_div(J, 64), units = row_groups * ct;
                 hipLaunchKernelGGL((k_backward24_bf16<1>), dim3(static_cast<unsigned>(units)), dim3(64),
-                                   0, s, Wp, I, J, ldw, B_bits, perm, Bbar_bits, vp, index, wpr, ct, units, vec_in, vec_perm);
+                                   0, s, Wp, I, J, ldw, B_bits, perm, Bbar_bits, vp, index, wpr, ct, units, vec_in, vec_perm, stream_out);
             }
             return check_launch();
         }
