@@ -473,9 +473,12 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
             if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
         }
         // large problems: 256 x 128 tiles on 8 wavefronts (half the weight traffic per token);
-        // otherwise 256 x 64 tiles so that the grid still covers the chip
+        // otherwise 256 x 64 tiles so that the grid still covers the chip; weight dimensions that
+        // would leave a fifth or more of the 256-row tiles empty (384 = 1.5 tiles) take 128-row tiles
         const bool big = ceil_div(Adim, 256) * ceil_div(T, 128) >= 512;
-        const int variant = forced >= 0 ? forced : (big ? 14 : 0);
+        const int64_t w256 = round_up(Adim, 256), w128 = round_up(Adim, 128);
+        const bool narrow = (w256 - w128) * 5 >= w256;
+        const int variant = forced >= 0 ? forced : (narrow ? 4 : (big ? 14 : 0));
         return launch_gemm_sp24(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, variant, s);
     }
     return run_dense(A_values, Adim, K, Bm, T, ldb, C, ldc, s);
