@@ -231,7 +231,7 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
                 const auto shi = __builtin_amdgcn_permlane32_swap(xhi, yhi, false, false);
                 const u32x4 v = {slo[0], shi[0], slo[1], shi[1]};
                 const int u = (wm * WM + i * 32 + 16 * p + 8 * h) >> 3;      // 16-byte unit of the row
-                *reinterpret_cast<u32x4*>(smem + t * (BM * 2) + ((u ^ (2 * (t & 15))) << 4)) = v;
+                *reinterpret_cast<u32x4*>(smem + t * (BM * 2) + ((u ^ ((2 * t) & (BM / 8 - 1))) << 4)) = v;
             }
         }
     __syncthreads();
@@ -239,7 +239,7 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
 #pragma unroll
     for (int it = 0; it < BN * UPR / NT; ++it) {
         const int q = tid + NT * it, t = q / UPR, u = q % UPR;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(smem + t * (BM * 2) + ((u ^ (2 * (t & 15))) << 4));
+        const u32x4 v = *reinterpret_cast<const u32x4*>(smem + t * (BM * 2) + ((u ^ ((2 * t) & (UPR - 1))) << 4));
         const int64_t a = a0 + 8 * u;
         if (t0 + t < T && a < Adim) {
             uint16_t* dst = C + (t0 + t) * ldc + a;

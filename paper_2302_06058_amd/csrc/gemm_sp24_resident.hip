@@ -198,14 +198,14 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
                     const auto shi = __builtin_amdgcn_permlane32_swap(xhi, yhi, false, false);   \
                     const u32x4 v = {slo[0], shi[0], slo[1], shi[1]};                            \
                     const int u = (wm * WM + i * 32 + 16 * p + 8 * h) >> 3;   /* 16-byte unit of the row */ \
-                    *reinterpret_cast<u32x4*>(stg + t * (BM * 2) + ((u ^ (2 * (t & 15))) << 4)) = v; \
+                    *reinterpret_cast<u32x4*>(stg + t * (BM * 2) + ((u ^ ((2 * t) & (BM / 8 - 1))) << 4)) = v; \
                 }                                                                                \
             }                                                                                    \
         __syncthreads();                                                                         \
         constexpr int UPR = BM / 8;                          /* 16-byte units per tile row */    \
         _Pragma("unroll") for (int it = 0; it < BN * UPR / NT; ++it) {                           \
             const int q = tid + NT * it, t = q / UPR, u = q % UPR;                               \
-            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + t * (BM * 2) + ((u ^ (2 * (t & 15))) << 4)); \
+            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + t * (BM * 2) + ((u ^ ((2 * t) & (BM / 8 - 1))) << 4)); \
             const int64_t a = static_cast<int64_t>(at) * BM + 8 * u;                             \
             if (t < rows && a < Adim) {                                                          \
                 uint16_t* dst = C + (t0 + t) * ldc + a;                                          \
