@@ -57,7 +57,12 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
     const int l32 = lane & 31, h = lane >> 5;
     const int64_t t0 = static_cast<int64_t>(blockIdx.x) * rpt;
     const int rows = static_cast<int>((T - t0) < rpt ? (T - t0) : rpt);
-    const int tiles_a = static_cast<int>(ceil_div(Adim, BM));
+    // blockIdx.y selects a contiguous group of weight tiles (layers with few tokens: more workgroups)
+    const int tiles_all = static_cast<int>(ceil_div(Adim, BM));
+    const int tiles_per_group = (tiles_all + static_cast<int>(gridDim.y) - 1) / static_cast<int>(gridDim.y);
+    const int at_begin = static_cast<int>(blockIdx.y) * tiles_per_group;
+    const int tiles_a = at_begin + tiles_per_group < tiles_all ? at_begin + tiles_per_group : tiles_all;   // end of this group
+    if (at_begin >= tiles_a) return;                     // whole workgroup, before any barrier
     const int64_t rt_last = ceil_div(Adim, 32) - 1;
 
     // ---- weight fragments of one weight tile: NSTG stages x TM row tiles
@@ -77,7 +82,7 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
             }                                                                                    \
         }                                                                                        \
     }
-    BIMASK_LOAD_WTILE(0, 0)
+    BIMASK_LOAD_WTILE(0, at_begin)
 
     // ---- resident token tile.  The g(Y) rows are requested first (registers), then LDS is
     // zeroed and the inverse permutation built while they are in flight.
@@ -219,7 +224,7 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
         }                                                                                        \
     }
 
-    int at = 0;
+    int at = at_begin;
 #pragma unroll 1
     for (; at + 2 <= tiles_a; at += 2) {
         BIMASK_LOAD_WTILE(1, at + 1)
@@ -244,7 +249,14 @@ int run_resident(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, c
     const bool vecB = aligned16(Bsrc) && (ldb * 2) % 16 == 0;
     const bool vecC = aligned16(C) && (ldc * 2) % 16 == 0;
     const unsigned grid = static_cast<unsigned>(ceil_div(T, rpt));
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WAVES_M), S::kTotal, s, static_cast<const uint16_t*>(A), meta,
+    // few token tiles: split the weight tiles over blockIdx.y, as far as one round of 256
+    // workgroups goes (the kernel runs one workgroup per CU; a second round costs a full pass)
+    const int64_t tiles_all = ceil_div(Adim, BM);
+    int64_t groups = 256 / grid;
+    if (groups < 1) groups = 1;
+    if (groups > tiles_all) groups = tiles_all;
+    hipLaunchKernelGGL(kern, dim3(grid, static_cast<unsigned>(groups)), dim3(64 * WAVES_M), S::kTotal, s,
+                       static_cast<const uint16_t*>(A), meta,
                        Adim, K, static_cast<const uint16_t*>(Bsrc), ldb, perm, T, static_cast<uint16_t*>(C), ldc,
                        rpt, vecB, vecC);
     return check_launch();
@@ -271,7 +283,15 @@ int launch_gemm_sp24_resident(const void* A, const uint32_t* meta, int64_t Adim,
     if (K > 512) return BIMASK_ERR_UNSUPPORTED;
     if (!aligned16(A) || !aligned16(meta)) return BIMASK_ERR_ALIGN;
     const int nstg = static_cast<int>(ceil_div(K, 128));
-    const int rpt = pick_rows_per_tile(T, 64, 256);
+    if (Adim <= 128 && nstg <= 2) {
+        // one narrow weight tile: the workgroup is a latency chain (fill, multiply, store), so
+        // small token tiles on 4 wavefronts with few registers let three of them share a CU
+        const int rpt = pick_rows_per_tile(T, 32, 256);
+        if (nstg == 1) return run_resident<128, 32, 4, 1>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s);
+        return run_resident<128, 32, 4, 2>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s);
+    }
+    // few tokens: full 64-row tiles (the weight tiles are split over workgroups instead)
+    const int rpt = ceil_div(T, 64) <= 128 ? 64 : pick_rows_per_tile(T, 64, 256);
 #define BIMASK_RES(WAVES) \
     switch (nstg) { \
         case 1: return run_resident<256, 64, WAVES, 1>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s); \
