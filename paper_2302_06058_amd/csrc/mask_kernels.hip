@@ -184,12 +184,38 @@ k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_
     const int64_t Jr = in_row ? J : 0;                 // padding rows read nothing
     const raw* row = W + (in_row ? i : 0) * ldw;
 
+    // Interior wavefronts (8 rows and both stages inside the matrix, aligned rows) issue all
+    // their loads back to back with no control flow between them; the guarded loader is for
+    // the edges only.
+    const bool fast = __builtin_amdgcn_readfirstlane(static_cast<int>(
+        vec_in && r8 * 8 + 8 <= I && static_cast<int64_t>(st0 + U) * 128 <= J)) != 0;
     uint32_t w[U][2][PW];
+    if (fast) {
+        u32x4 t[U][2][PW / 4];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t j0 = static_cast<int64_t>(st0 + u) * 128 + 16 * q;
-        load8<DT>(row, j0, Jr, vec_in, w[u][0]);
-        load8<DT>(row, j0 + 8, Jr, vec_in, w[u][1]);
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int v = 0; v < 2; ++v)
+#pragma unroll
+                for (int x = 0; x < PW / 4; ++x)
+                    t[u][v][x] = *reinterpret_cast<const u32x4*>(
+                        row + static_cast<int64_t>(st0 + u) * 128 + 16 * q + 8 * v + x * (16 / static_cast<int>(sizeof(raw))));
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int v = 0; v < 2; ++v)
+#pragma unroll
+                for (int x = 0; x < PW / 4; ++x) {
+                    w[u][v][4 * x + 0] = t[u][v][x].x; w[u][v][4 * x + 1] = t[u][v][x].y;
+                    w[u][v][4 * x + 2] = t[u][v][x].z; w[u][v][4 * x + 3] = t[u][v][x].w;
+                }
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t j0 = static_cast<int64_t>(st0 + u) * 128 + 16 * q;
+            load8<DT>(row, j0, Jr, vec_in, w[u][0]);
+            load8<DT>(row, j0 + 8, Jr, vec_in, w[u][1]);
+        }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -448,35 +474,36 @@ __device__ __forceinline__ uint32_t quad_transpose_bytes(uint32_t x, int lane) {
 }
 
 // 8x8 transpose of 4-bit fields across the 8 lanes that share lane % 8 (k = lane / 8):
-// lane k ends with field k of every lane, field j coming from lane j.
+// lane k ends with field k of every lane, field j coming from lane j.  Branch-free: the lane's
+// side of each exchange is a select between two shifts and one bit-field insert.
 __device__ __forceinline__ uint32_t nibble_transpose8(uint32_t x, int k) {
     uint32_t p = __shfl_xor(x, 32, 64);
-    x = (k & 4) ? ((x & 0xFFFF0000u) | (p >> 16)) : ((x & 0x0000FFFFu) | (p << 16));
+    uint32_t keep = (k & 4) ? 0xFFFF0000u : 0x0000FFFFu;
+    uint32_t ps = (k & 4) ? (p >> 16) : (p << 16);
+    x = (x & keep) | (ps & ~keep);
     p = __shfl_xor(x, 16, 64);
-    x = (k & 2) ? ((x & 0xFF00FF00u) | ((p >> 8) & 0x00FF00FFu)) : ((x & 0x00FF00FFu) | ((p << 8) & 0xFF00FF00u));
+    keep = (k & 2) ? 0xFF00FF00u : 0x00FF00FFu;
+    ps = (k & 2) ? (p >> 8) : (p << 8);
+    x = (x & keep) | (ps & ~keep);
     p = __shfl_xor(x, 8, 64);
-    x = (k & 1) ? ((x & 0xF0F0F0F0u) | ((p >> 4) & 0x0F0F0F0Fu)) : ((x & 0x0F0F0F0Fu) | ((p << 4) & 0xF0F0F0F0u));
+    keep = (k & 1) ? 0xF0F0F0F0u : 0x0F0F0F0Fu;
+    ps = (k & 1) ? (p >> 4) : (p << 4);
+    x = (x & keep) | (ps & ~keep);
     return x;
 }
 
-template <int NO>
-__global__ void __launch_bounds__(kThreads)
-k_backward24_bf16(const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t ldw,
-                  const uint32_t* __restrict__ B_bits, const int32_t* __restrict__ perm,
-                  uint32_t* __restrict__ Bbar_bits, uint16_t* __restrict__ values,
-                  uint32_t* __restrict__ index, int wpr, int64_t col_tiles, int64_t units,
-                  bool vec_in, bool vec_perm, bool stream_out) {
-    constexpr int TC = 64 * NO;
-    // per wavefront: 2*NO output row tiles x 2 instruction slots x 32 lanes x 16 bytes
-    __shared__ uint4 lds[kThreads / 64][NO * 128];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+// One wavefront's tile.  FAST: all 32 rows and all 64*NO columns lie inside the matrix and
+// rows are 16-byte aligned, so every load and store is unconditional and the row loads are
+// issued back to back; otherwise everything is bounds-checked.
+template <int NO, bool FAST>
+__device__ __forceinline__ void backward24_tile(
+        const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t ldw, const uint32_t* __restrict__ B_bits,
+        const int32_t* __restrict__ perm, uint32_t* __restrict__ Bbar_bits, uint16_t* __restrict__ values,
+        uint32_t* __restrict__ index, int wpr, bool vec_in, bool vec_perm, bool stream_out, bool active,
+        int64_t r0, int c0, uint4* lds_wave, int lane) {
     const int c = lane & 7, k = lane >> 3;
-    const int64_t unit = static_cast<int64_t>(blockIdx.x) * (blockDim.x >> 6) + wave;
-    const bool active = unit < units;
-    const int64_t rg = active ? unit / col_tiles : 0;
-    const int64_t c0 = (active ? unit - rg * col_tiles : 0) * TC;
-    const int64_t r0 = rg * 32, rb = r0 + 4 * k;
-    const bool row_ok = active && rb < I;
+    const int64_t rb = r0 + 4 * k;
+    const bool row_ok = FAST || (active && rb < I);
     const int64_t Jr = row_ok ? J : 0;                   // rows beyond I (stage padding) read nothing
 
     int64_t src[4] = {0, 0, 0, 0};
@@ -493,23 +520,40 @@ k_backward24_bf16(const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t 
         }
     }
     uint32_t w[4][NO][4];
+    if constexpr (FAST) {
+        u32x4 t[4][NO];
 #pragma unroll
-    for (int m = 0; m < 4; ++m)
+        for (int m = 0; m < 4; ++m)
 #pragma unroll
-        for (int o2 = 0; o2 < NO; ++o2)
-            load8<BF16>(W + src[m] * ldw, c0 + 8 * (c + 8 * o2), Jr, vec_in, w[m][o2]);
+            for (int o2 = 0; o2 < NO; ++o2)
+                t[m][o2] = *reinterpret_cast<const u32x4*>(W + src[m] * ldw + c0 + 8 * (c + 8 * o2));
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+            for (int o2 = 0; o2 < NO; ++o2) {
+                w[m][o2][0] = t[m][o2].x; w[m][o2][1] = t[m][o2].y; w[m][o2][2] = t[m][o2].z; w[m][o2][3] = t[m][o2].w;
+            }
+    } else {
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+            for (int o2 = 0; o2 < NO; ++o2)
+                load8<BF16>(W + src[m] * ldw, c0 + 8 * (c + 8 * o2), Jr, vec_in, w[m][o2]);
+    }
 
     // mask bits: lane (a, m) = (c / 4, c % 4) fetches word a (+ 2 for the second octet) of row m
     const int64_t src_m = (c & 2) ? ((c & 1) ? src[3] : src[2]) : ((c & 1) ? src[1] : src[0]);
     uint32_t X[NO];
 #pragma unroll
     for (int o2 = 0; o2 < NO; ++o2) {
-        const int64_t word = c0 / 32 + 2 * o2 + (c >> 2);
-        const uint32_t bw = (row_ok && word < wpr) ? B_bits[src_m * wpr + word] : 0u;
+        const int word = c0 / 32 + 2 * o2 + (c >> 2);
+        const uint32_t bw = (FAST || (row_ok && word < wpr)) ? B_bits[src_m * wpr + word] : 0u;
         X[o2] = quad_transpose_bytes(bw, lane);          // byte m = bits of row m for this lane's octet
     }
 
-    uint32_t* lds32 = reinterpret_cast<uint32_t*>(lds[wave]);
+    uint32_t* lds32 = reinterpret_cast<uint32_t*>(lds_wave);
+    // LDS word of (output row = column 8 (c + 8 o2) + q, row block k): unit ul, word k % 4
+    const int ul0 = ((c >> 2) * 2 + (k >> 2)) * 32 + 8 * (c & 3);
     uint32_t nib[NO], R[NO];
 #pragma unroll
     for (int o2 = 0; o2 < NO; ++o2) {
@@ -536,7 +580,7 @@ k_backward24_bf16(const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t 
             nib[o2] |= (p0 | (p1 << 2)) << (4 * q);
             R[o2] |= (1u << (8 * p0 + q)) | (1u << (8 * p1 + q));       // byte m: columns that select row m
             // output row = this column; slots 2kb, 2kb+1 of the stage (kb = row block in the stage)
-            const int ul = (((c >> 2) + 2 * o2) * 2 + (k >> 2)) * 32 + 8 * (c & 3) + q;
+            const int ul = ul0 + o2 * 128 + q;
             lds32[((ul ^ ((ul >> 4) & 7)) << 2) + (k & 3)] = ow;
         }
     }
@@ -550,28 +594,59 @@ k_backward24_bf16(const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t 
     for (int o2 = 0; o2 < NO; ++o2) {
         // Bbar = selection AND B, back to whole words per row
         const uint32_t back = quad_transpose_bytes(R[o2] & X[o2], lane);
-        const int64_t word = c0 / 32 + 2 * o2 + (c >> 2);
-        if (Bbar_bits && row_ok && word < wpr) Bbar_bits[(rb + (c & 3)) * wpr + word] = back;
+        const int word = c0 / 32 + 2 * o2 + (c >> 2);
+        if (Bbar_bits && (FAST || (row_ok && word < wpr))) Bbar_bits[(rb + (c & 3)) * wpr + word] = back;
         // indices: columns at or beyond J and padding rows carry index 0
-        const int64_t left = J - (c0 + 8 * (c + 8 * o2));
-        const uint32_t vm = !row_ok || left <= 0 ? 0u : (left >= 8 ? 0xFFFFFFFFu : (1u << (4 * static_cast<int>(left))) - 1u);
+        uint32_t vm = 0xFFFFFFFFu;
+        if constexpr (!FAST) {
+            const int64_t left = J - (c0 + 8 * (c + 8 * o2));
+            vm = !row_ok || left <= 0 ? 0u : (left >= 8 ? 0xFFFFFFFFu : (1u << (4 * static_cast<int>(left))) - 1u);
+        }
         const uint32_t iw = nibble_transpose8(nib[o2] & vm, k);          // column 8 (c + 8 o2) + k, row blocks kb0..kb0+7
         const int col = 8 * (c + 8 * o2) + k;
-        if (active && c0 + (col & ~31) < J)
+        if (FAST || (active && c0 + (col & ~31) < J))
             index[((c0 / 32 + (col >> 5)) * ks + stage) * 128 + ((col & 31) + 32 * lane_half) * 2 + wd] = iw;
     }
-    __syncthreads();
+    // the image is written and read by this wavefront only; LDS operations of a wavefront
+    // execute in order, the fence keeps the compiler from moving the reads up
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 #pragma unroll
     for (int it0 = 0; it0 < 2 * NO; ++it0) {
         const int it = lane + 64 * it0;                   // (row tile it0, slot it/32 % 2, lane it % 32)
-        const u32x4 v = reinterpret_cast<const u32x4*>(lds[wave])[it ^ ((it >> 4) & 7)];
-        if (active && c0 + 32 * it0 < J) {
+        const u32x4 v = reinterpret_cast<const u32x4*>(lds_wave)[it ^ ((it >> 4) & 7)];
+        if (FAST || (active && c0 + 32 * it0 < J)) {
             uint16_t* dst = values + ((((c0 / 32 + it0) * ks + stage) * 4 + s4base + ((it >> 5) & 1)) * 64 + (it & 31) + 32 * lane_half) * 8;
             // 512-byte runs, whole lines; streamed past L2 for operands too large to stay there
             if (stream_out) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
             else *reinterpret_cast<u32x4*>(dst) = v;
         }
     }
+}
+
+template <int NO>
+__global__ void __launch_bounds__(kThreads)
+k_backward24_bf16(const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t ldw,
+                  const uint32_t* __restrict__ B_bits, const int32_t* __restrict__ perm,
+                  uint32_t* __restrict__ Bbar_bits, uint16_t* __restrict__ values,
+                  uint32_t* __restrict__ index, int wpr, int64_t col_tiles, int64_t units,
+                  bool vec_in, bool vec_perm, bool stream_out) {
+    constexpr int TC = 64 * NO;
+    // per wavefront: 2*NO output row tiles x 2 instruction slots x 32 lanes x 16 bytes
+    __shared__ uint4 lds[kThreads / 64][NO * 128];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t unit = static_cast<int64_t>(blockIdx.x) * (blockDim.x >> 6) + wave;
+    const bool active = unit < units;
+    const int64_t rg = active ? unit / col_tiles : 0;
+    const int c0 = static_cast<int>((active ? unit - rg * col_tiles : 0) * TC);
+    const int64_t r0 = rg * 32;
+    const bool fast = __builtin_amdgcn_readfirstlane(
+        static_cast<int>(active && vec_in && r0 + 32 <= I && c0 + TC <= J)) != 0;
+    if (fast)
+        backward24_tile<NO, true>(W, I, J, ldw, B_bits, perm, Bbar_bits, values, index, wpr, vec_in, vec_perm,
+                                  stream_out, active, r0, c0, lds[wave], lane);
+    else
+        backward24_tile<NO, false>(W, I, J, ldw, B_bits, perm, Bbar_bits, values, index, wpr, vec_in, vec_perm,
+                                   stream_out, active, r0, c0, lds[wave], lane);
 }
 
 template <typename DT, int M>
