@@ -147,8 +147,16 @@ k_perm_final(const int32_t* __restrict__ partial, int ntiles, int K, int64_t I,
     for (int c0 = 0; c0 < K; c0 += 128) {
         const int c = c0 + cl;
         int s = 0;
-        if (c < K)
-            for (int t = part; t < ntiles; t += 8) s += partial[static_cast<int64_t>(t) * K + c];
+        if (c < K) {
+            // four independent loads per round: the partial sums are L2 latency, not bandwidth
+            int t = part;
+            for (; t + 24 < ntiles; t += 32) {
+                const int a0 = partial[static_cast<int64_t>(t) * K + c], a1 = partial[static_cast<int64_t>(t + 8) * K + c];
+                const int a2 = partial[static_cast<int64_t>(t + 16) * K + c], a3 = partial[static_cast<int64_t>(t + 24) * K + c];
+                s += (a0 + a1) + (a2 + a3);
+            }
+            for (; t < ntiles; t += 8) s += partial[static_cast<int64_t>(t) * K + c];
+        }
         psum[part][cl] = s;
         __syncthreads();
         if (part == 0 && c < K) {
