@@ -479,7 +479,7 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
         const int64_t w256 = round_up(Adim, 256), w128 = round_up(Adim, 128);
         const bool narrow = (w256 - w128) * 5 >= w256;
         // few tokens and few weight tiles: 256-row tiles would leave CUs idle
-        const bool underfilled = ceil_div(Adim, 256) * ceil_div(T, 64) < 200;
+        const bool underfilled = ceil_div(Adim, 256) * ceil_div(T, 64) <= 128;
         const int variant = forced >= 0 ? forced : (narrow || underfilled ? 4 : (big ? 14 : 0));
         return launch_gemm_sp24(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, variant, s);
     }
