@@ -246,3 +246,50 @@ def test_long_contraction_backward_uses_gather_pass(I, J, T):
     # I > 512: g(Y)[:, P] is gathered into the workspace, then the streaming kernel runs;
     # I > 2048: the gather keeps its permutation entries in registers (2100: ragged last 16 bytes)
     check_layer(I=I, J=J, N=2, M=4, dtype=synth.BF16, K=4, seed=900 + I, T=T)
+
+
+@pytest.mark.parametrize("I,J,T", [(256, 384, 100), (1024, 256, 96)])
+def test_leading_dimensions_side_stream_many_candidates(I, J, T):
+    """Operands embedded in wider buffers (ld > columns), calls issued on a non-default stream,
+    K > 128 candidates; the padding columns of the outputs must stay untouched."""
+    import torch
+    N, M, dtype, K = 2, 4, synth.BF16, 150
+    Wh = make_w(I, J, dtype, 1201)
+    W64 = synth.to_f64(Wh, dtype)
+    perms = perms_of(I, K, 1202)
+    r = np.random.default_rng(1203)
+    Xh = synth.store(r.standard_normal((T, J), dtype=np.float32), dtype)
+    dYh = synth.store(r.standard_normal((T, I), dtype=np.float32), dtype)
+
+    def embed(a, extra):                       # device tensor whose rows sit in a wider buffer
+        t = to_dev(a, dtype)
+        big = torch.full((t.shape[0], t.shape[1] + extra), 7.0, dtype=t.dtype, device=t.device)
+        big[:, :t.shape[1]] = t
+        return big[:, :t.shape[1]]
+
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        W, X, dY = embed(Wh, 24), embed(Xh, 8), embed(dYh, 16)
+        Ybig = torch.full((T, I + 8), 3.0, dtype=torch.bfloat16, device="cuda")
+        dXbig = torch.full((T, J + 40), 3.0, dtype=torch.bfloat16, device="cuda")
+        B, vals, index = bm.bimask_forward_mask_compress(W, N, M)
+        scores, best, P = bm.bimask_perm_search(B, I, J, N, M, i32_dev(perms))
+        Bbar, vb, ib = bm.bimask_backward_mask_compress(W, N, M, B, P)
+        bm.bimask_sparse_gemm_fwd(X, vals, index, I, J, N, M, Y=Ybig[:, :I])
+        bm.bimask_sparse_gemm_bwd(dY, P, vb, ib, I, J, N, M, dX=dXbig[:, :J])
+    side.synchronize()
+
+    B_o = oracle.forward_mask(W64, N, M)
+    sc_o = oracle.perm_scores(B_o, perms, N, M)
+    best_o = oracle.argmax_first(sc_o)
+    assert (words(B) == oracle.pack_bits(B_o)).all()
+    assert (scores.cpu().numpy() == sc_o).all() and int(best.item()) == best_o
+    assert (P.cpu().numpy() == perms[best_o]).all()
+    Bbar_o, _ = oracle.backward_mask(W64, B_o, perms[best_o], N, M)
+    assert (words(Bbar) == oracle.pack_bits(Bbar_o)).all()
+    Y_o = oracle.gemm_fwd(synth.to_f64(Xh, dtype), W64, B_o)
+    dX_o = oracle.gemm_bwd(synth.to_f64(dYh, dtype), W64, Bbar_o, perms[best_o])
+    assert rel_err(Ybig[:, :I].float().cpu().numpy().astype(np.float64), Y_o) <= TOL[dtype]
+    assert rel_err(dXbig[:, :J].float().cpu().numpy().astype(np.float64), dX_o) <= TOL[dtype]
+    assert bool((Ybig[:, I:] == 3.0).all()) and bool((dXbig[:, J:] == 3.0).all()), "output padding was written"
