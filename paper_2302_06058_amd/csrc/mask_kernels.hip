@@ -184,38 +184,54 @@ k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_
     const int64_t Jr = in_row ? J : 0;                 // padding rows read nothing
     const raw* row = W + (in_row ? i : 0) * ldw;
 
-    // Interior wavefronts (8 rows and both stages inside the matrix, aligned rows) issue all
-    // their loads back to back with no control flow between them; the guarded loader is for
-    // the edges only.
+    // Interior wavefronts of the bf16 select-and-compress case (8 rows and both stages inside
+    // the matrix, aligned rows) run a straight-line path: all loads issued back to back, no
+    // bounds checks, neighbour exchange by a DPP quad swap.  Everything else takes the guarded
+    // path below.
     const bool fast = __builtin_amdgcn_readfirstlane(static_cast<int>(
-        vec_in && r8 * 8 + 8 <= I && static_cast<int64_t>(st0 + U) * 128 <= J)) != 0;
-    uint32_t w[U][2][PW];
-    if (fast) {
-        u32x4 t[U][2][PW / 4];
+        sizeof(raw) == 2 && !mask_in && vec_in && r8 * 8 + 8 <= I && static_cast<int64_t>(st0 + U) * 128 <= J)) != 0;
+    if constexpr (sizeof(raw) == 2) {
+        if (fast) {
+            u32x4 t[U][2];
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+            for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int v = 0; v < 2; ++v)
+                for (int v = 0; v < 2; ++v)
+                    t[u][v] = *reinterpret_cast<const u32x4*>(row + static_cast<int64_t>(st0 + u) * 128 + 16 * q + 8 * v);
 #pragma unroll
-                for (int x = 0; x < PW / 4; ++x)
-                    t[u][v][x] = *reinterpret_cast<const u32x4*>(
-                        row + static_cast<int64_t>(st0 + u) * 128 + 16 * q + 8 * v + x * (16 / static_cast<int>(sizeof(raw))));
+            for (int u = 0; u < U; ++u) {
+                const int st = st0 + u;
+                uint32_t bits = 0, nibs = 0;
+                u32x4 ov;
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int v = 0; v < 2; ++v)
-#pragma unroll
-                for (int x = 0; x < PW / 4; ++x) {
-                    w[u][v][4 * x + 0] = t[u][v][x].x; w[u][v][4 * x + 1] = t[u][v][x].y;
-                    w[u][v][4 * x + 2] = t[u][v][x].z; w[u][v][4 * x + 3] = t[u][v][x].w;
+                for (int g = 0; g < 4; ++g) {
+                    const uint32_t w0 = t[u][g >> 1][(g & 1) * 2], w1 = t[u][g >> 1][(g & 1) * 2 + 1];
+                    uint32_t p0, p1;
+                    top2_of4_bf16(w0, w1, p0, p1);
+                    bits |= ((1u << p0) | (1u << p1)) << (4 * g);
+                    nibs |= (p0 | (p1 << 2)) << (4 * g);
+                    ov[g] = __builtin_amdgcn_perm(w1, w0, 0x01000100u + p0 * 0x0202u + p1 * 0x02020000u);
                 }
-    } else {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t j0 = static_cast<int64_t>(st0 + u) * 128 + 16 * q;
-            load8<DT>(row, j0, Jr, vec_in, w[u][0]);
-            load8<DT>(row, j0 + 8, Jr, vec_in, w[u][1]);
+                raw* dst = values + ((((i >> 5) * ks + st) * 4 + (q & 3)) * 64 + (i & 31) + 32 * (q >> 2)) * 8;
+                if (stream_out) __builtin_nontemporal_store(ov, reinterpret_cast<u32x4*>(dst));
+                else *reinterpret_cast<u32x4*>(dst) = ov;
+                // lanes q and q^1 merge their 16 index / mask bits into one word (even lane writes)
+                const uint32_t packed = bits | (nibs << 16);
+                const uint32_t other = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(packed), 0xB1, 0xF, 0xF, true));
+                if (!(q & 1)) {
+                    index[(((i >> 5) * ks + st) * 64 + (i & 31) + 32 * (q >> 2)) * 2 + ((q >> 1) & 1)] = (packed >> 16) | (other & 0xFFFF0000u);
+                    if (B_bits) B_bits[i * wpr + st * 4 + (q >> 1)] = (packed & 0xFFFFu) | (other << 16);
+                }
+            }
+            return;
         }
+    }
+    uint32_t w[U][2][PW];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t j0 = static_cast<int64_t>(st0 + u) * 128 + 16 * q;
+        load8<DT>(row, j0, Jr, vec_in, w[u][0]);
+        load8<DT>(row, j0 + 8, Jr, vec_in, w[u][1]);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
