@@ -245,6 +245,10 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
             uint16_t* dst = C + (t0 + t) * ldc + a;
             if (vecC && a + 8 <= Adim) {
                 __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
+            } else if (a + 8 <= Adim) {
+                // rows not 16-byte aligned: 4-byte stores (pointers and pitches are 4-byte aligned)
+                uint32_t* d32 = reinterpret_cast<uint32_t*>(dst);
+                d32[0] = v.x; d32[1] = v.y; d32[2] = v.z; d32[3] = v.w;
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)

@@ -4,7 +4,7 @@
 // features: k runs over the permuted out-feature index r, Bsrc = g(Y), perm = P.
 //
 // A workgroup owns a tile of tokens.  It loads that tile of g(Y) ONCE, full rows (contiguous
-// 16-byte lanes), and scatters the elements through the inverse permutation into an
+// 16-byte lanes) into LDS and regroups it there through the permutation into an
 // XOR-swizzled LDS tile, so the column permutation of Eq. (10) costs no extra pass over
 // memory.  It then walks over ALL weight-row tiles: the fragment-major compressed weights
 // stream from L2 straight into the sparse matrix instruction's A registers (prefetched one
@@ -30,9 +30,10 @@ union AFragR { bf16x8 v; u32x4 q; };
 template <int BM, int BN, int NSTG>
 struct ResSmem {
     static constexpr int kB = NSTG * BN * 256;          // resident token tile, 256 B per row and stage
-    static constexpr int kInv = NSTG * 128 * 2;         // inverse permutation (int16)
+    static constexpr int kInv = NSTG * 128 * 2;         // permutation (int16)
     static constexpr int kOut = BN * BM * 2;            // one bf16 output tile (two of them: double buffer)
     static constexpr int kTotal = kB + kInv + 2 * kOut;
+    static_assert(kB <= 2 * kOut, "the un-permuted row tile shares the output staging area");
 };
 
 // byte offset of element (t, r) of the resident tile
@@ -41,7 +42,10 @@ __device__ __forceinline__ int resb_off(int t, int r) {
     return (r >> 7) * (BN * 256) + t * 256 + (((((r & 127) >> 3) ^ (t & 15))) << 4) + (r & 7) * 2;
 }
 
-template <int BM, int BN, int WAVES_M, int NSTG>
+// PERSIST: the grid is smaller than the number of token tiles; a workgroup walks over its
+// tiles and requests the rows of the next one before it multiplies the current one, and the
+// inverse permutation (and, with a single weight tile, the weight fragments) are set up once.
+template <int BM, int BN, int WAVES_M, int NSTG, bool PERSIST>
 __global__ void __launch_bounds__(64 * WAVES_M)
 k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int64_t K,
                      const uint16_t* __restrict__ Bsrc, int64_t ldb, const int32_t* __restrict__ perm, int64_t T,
@@ -51,12 +55,15 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
     constexpr int WM = BM / WAVES_M, TM = WM / 32, TN = BN / 32;
     extern __shared__ u32x4 smem_u4[];
     uint8_t* sB = reinterpret_cast<uint8_t*>(smem_u4);
-    int16_t* sInv = reinterpret_cast<int16_t*>(sB + S::kB);
+    int16_t* sP = reinterpret_cast<int16_t*>(sB + S::kB);              // the permutation, 16-bit
+    uint8_t* lin = sB + S::kB + S::kInv;                               // un-permuted rows (shares the output staging area)
 
     const int tid = threadIdx.x, lane = tid & 63, wm = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
-    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * rpt;
-    const int rows = static_cast<int>((T - t0) < rpt ? (T - t0) : rpt);
+    const int64_t ntiles = ceil_div(T, rpt);
+    int64_t tile = blockIdx.x;
+    int64_t t0 = tile * rpt;
+    int rows = static_cast<int>((T - t0) < rpt ? (T - t0) : rpt);
     // blockIdx.y selects a contiguous group of weight tiles (layers with few tokens: more workgroups)
     const int tiles_all = static_cast<int>(ceil_div(Adim, BM));
     const int tiles_per_group = (tiles_all + static_cast<int>(gridDim.y) - 1) / static_cast<int>(gridDim.y);
@@ -89,46 +96,74 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
     const int G = static_cast<int>((K + 7) >> 3);        // 8-element granules per token row
     constexpr int NL = (BN * NSTG * 16 + NT - 1) / NT;
     u32x4 v[NL];
-#pragma unroll
-    for (int it = 0; it < NL; ++it) {
-        const int q = tid + NT * it;
-        const int t = q / G, g = q - t * G;
-        v[it] = (u32x4){0u, 0u, 0u, 0u};
-        if (q < rows * G) {
-            const uint16_t* src = Bsrc + (t0 + t) * ldb + 8 * g;
-            if (8 * g + 8 <= K) {
-                if (vecB) v[it] = *reinterpret_cast<const u32x4*>(src);
-                else { const uint32_t* p = reinterpret_cast<const uint32_t*>(src); v[it].x = p[0]; v[it].y = p[1]; v[it].z = p[2]; v[it].w = p[3]; }
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (8 * g + e < K) v[it][e >> 1] |= static_cast<uint32_t>(src[e]) << (16 * (e & 1));
-            }
-        }
+#define BIMASK_LOAD_ROWS(T0, ROWS)                                                               \
+    _Pragma("unroll") for (int it = 0; it < NL; ++it) {                                          \
+        const int q = tid + NT * it;                                                             \
+        const int t = q / G, g = q - t * G;                                                      \
+        v[it] = (u32x4){0u, 0u, 0u, 0u};                                                         \
+        if (q < (ROWS) * G) {                                                                    \
+            const uint16_t* src = Bsrc + ((T0) + t) * ldb + 8 * g;                               \
+            if (8 * g + 8 <= K) {                                                                \
+                if (vecB) v[it] = *reinterpret_cast<const u32x4*>(src);                          \
+                else { const uint32_t* p = reinterpret_cast<const uint32_t*>(src); v[it].x = p[0]; v[it].y = p[1]; v[it].z = p[2]; v[it].w = p[3]; } \
+            } else {                                                                             \
+                _Pragma("unroll") for (int e = 0; e < 8; ++e)                                    \
+                    if (8 * g + e < K) v[it][e >> 1] |= static_cast<uint32_t>(src[e]) << (16 * (e & 1)); \
+            }                                                                                    \
+        }                                                                                        \
     }
+    BIMASK_LOAD_ROWS(t0, rows)
     for (int it = tid; it < S::kB / 16; it += NT) reinterpret_cast<u32x4*>(sB)[it] = (u32x4){0u, 0u, 0u, 0u};
     if (perm) {
-        for (int r = tid; r < static_cast<int>(K); r += NT) sInv[perm[r]] = static_cast<int16_t>(r);
+        for (int r = tid; r < NSTG * 128; r += NT) sP[r] = r < static_cast<int>(K) ? static_cast<int16_t>(perm[r]) : static_cast<int16_t>(0);
     }
-    __syncthreads();
-    {
+    // k positions beyond K keep the zeros written above; rows beyond `rows` keep whatever an
+    // earlier tile left (their outputs are never stored).
+    for (;;) {
+    __syncthreads();                                     // LDS set up / the previous tile is fully consumed
+    if (perm) {
+        // Eq. (10)'s column gather: the rows go to LDS as they are (16-byte stores), then each
+        // thread assembles whole 16-byte granules of the permuted rows from 2-byte LDS reads
+#pragma unroll
+        for (int it = 0; it < NL; ++it) {
+            const int q = tid + NT * it;
+            const int t = q / G, g = q - t * G;
+            if (q < rows * G) *reinterpret_cast<u32x4*>(lin + t * (NSTG * 256) + g * 16) = v[it];
+        }
+        __syncthreads();
 #pragma unroll
         for (int it = 0; it < NL; ++it) {
             const int q = tid + NT * it;
             const int t = q / G, g = q - t * G;
             if (q < rows * G) {
-                if (perm) {
+                const u32x4 pv = *reinterpret_cast<const u32x4*>(sP + 8 * g);   // P[8g .. 8g+7]
+                const uint16_t* row = reinterpret_cast<const uint16_t*>(lin + t * (NSTG * 256));
+                u32x4 o = {0u, 0u, 0u, 0u};
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int i = 8 * g + e;
-                        if (i < K)
-                            *reinterpret_cast<uint16_t*>(sB + resb_off<BN>(t, sInv[i])) =
-                                static_cast<uint16_t>(v[it][e >> 1] >> (16 * (e & 1)));
-                    }
-                } else {
-                    *reinterpret_cast<u32x4*>(sB + resb_off<BN>(t, 8 * g)) = v[it];
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t src_col = (pv[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                    const uint32_t x = 8 * g + e < K ? row[src_col] : 0u;
+                    o[e >> 1] |= x << (16 * (e & 1));
                 }
+                *reinterpret_cast<u32x4*>(sB + resb_off<BN>(t, 8 * g)) = o;
             }
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < NL; ++it) {
+            const int q = tid + NT * it;
+            const int t = q / G, g = q - t * G;
+            if (q < rows * G) *reinterpret_cast<u32x4*>(sB + resb_off<BN>(t, 8 * g)) = v[it];
+        }
+    }
+    const int64_t tile_next = tile + gridDim.x;
+    int64_t t0_next = 0;
+    int rows_next = 0;
+    if constexpr (PERSIST) {
+        if (tile_next < ntiles) {                        // rows of the next tile: in flight during this one
+            t0_next = tile_next * rpt;
+            rows_next = static_cast<int>((T - t0_next) < rpt ? (T - t0_next) : rpt);
+            BIMASK_LOAD_ROWS(t0_next, rows_next)
         }
     }
     __syncthreads();
@@ -216,6 +251,9 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
                 uint16_t* dst = C + (t0 + t) * ldc + a;                                          \
                 if (vecC && a + 8 <= Adim) {                                                     \
                     __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));               \
+                } else if (a + 8 <= Adim) {      /* rows not 16-byte aligned: 4-byte stores */   \
+                    uint32_t* d32 = reinterpret_cast<uint32_t*>(dst);                            \
+                    d32[0] = v.x; d32[1] = v.y; d32[2] = v.z; d32[3] = v.w;                      \
                 } else {                                                                         \
                     _Pragma("unroll") for (int e = 0; e < 8; ++e)                                \
                         if (a + e < Adim) dst[e] = static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1))); \
@@ -233,22 +271,31 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
         BIMASK_WTILE(1, at + 1)
     }
     if (at < tiles_a) BIMASK_WTILE(0, at)
+    if constexpr (!PERSIST) break;
+    if (tile_next >= ntiles) break;
+    tile = tile_next; t0 = t0_next; rows = rows_next;
+    if (tiles_a - at_begin > 1) BIMASK_LOAD_WTILE(0, at_begin)   // several weight tiles: set 0 starts over
+    }
 #undef BIMASK_WTILE
 #undef BIMASK_LOAD_WTILE
+#undef BIMASK_LOAD_ROWS
 }
 
-template <int BM, int BN, int WAVES_M, int NSTG>
+constexpr unsigned kPersistGrid = 768;     // persistent variant: three workgroups per CU
+
+template <int BM, int BN, int WAVES_M, int NSTG, bool PERSIST = false>
 int run_resident(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc, int64_t ldb,
                  const int32_t* perm, int64_t T, void* C, int64_t ldc, int rpt, hipStream_t s) {
     using S = ResSmem<BM, BN, NSTG>;
-    auto kern = k_gemm_sp24_resident<BM, BN, WAVES_M, NSTG>;
+    auto kern = k_gemm_sp24_resident<BM, BN, WAVES_M, NSTG, PERSIST>;
     if (S::kTotal > 48 * 1024) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 S::kTotal) != hipSuccess) return BIMASK_ERR_HIP;
     }
     const bool vecB = aligned16(Bsrc) && (ldb * 2) % 16 == 0;
     const bool vecC = aligned16(C) && (ldc * 2) % 16 == 0;
-    const unsigned grid = static_cast<unsigned>(ceil_div(T, rpt));
+    unsigned grid = static_cast<unsigned>(ceil_div(T, rpt));
+    if (PERSIST && grid > kPersistGrid) grid = kPersistGrid;
     // few token tiles: split the weight tiles over blockIdx.y, as far as one round of 256
     // workgroups goes (the kernel runs one workgroup per CU; a second round costs a full pass)
     const int64_t tiles_all = ceil_div(Adim, BM);
@@ -287,8 +334,8 @@ int launch_gemm_sp24_resident(const void* A, const uint32_t* meta, int64_t Adim,
         // one narrow weight tile: the workgroup is a latency chain (fill, multiply, store), so
         // small token tiles on 4 wavefronts with few registers let three of them share a CU
         const int rpt = pick_rows_per_tile(T, 32, 256);
-        if (nstg == 1) return run_resident<128, 32, 4, 1>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s);
-        return run_resident<128, 32, 4, 2>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s);
+        if (nstg == 1) return run_resident<128, 32, 4, 1, true>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s);
+        return run_resident<128, 32, 4, 2, true>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s);
     }
     // few tokens: full 64-row tiles (the weight tiles are split over workgroups instead)
     const int rpt = ceil_div(T, 64) <= 128 ? 64 : pick_rows_per_tile(T, 64, 256);
