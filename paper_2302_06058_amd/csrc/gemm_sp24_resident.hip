@@ -32,8 +32,9 @@ struct ResSmem {
     static constexpr int kB = NSTG * BN * 256;          // resident token tile, 256 B per row and stage
     static constexpr int kInv = NSTG * 128 * 2;         // permutation (int16)
     static constexpr int kOut = BN * BM * 2;            // one bf16 output tile (two of them: double buffer)
-    static constexpr int kTotal = kB + kInv + 2 * kOut;
-    static_assert(kB <= 2 * kOut, "the un-permuted row tile shares the output staging area");
+    // output staging (two tiles); the un-permuted row tile of the fill phase shares this area
+    static constexpr int kArea = 2 * kOut > kB ? 2 * kOut : kB;
+    static constexpr int kTotal = kB + kInv + kArea;
 };
 
 // byte offset of element (t, r) of the resident tile
