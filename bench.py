@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--copies", type=int, default=0, help="rotating buffer copies (0 = enough for 1 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown-reps", type=int, default=30)
+    ap.add_argument("--all-layers", action="store_true",
+                    help="network aggregate: time every layer of the configuration and print per-stage totals")
     return ap.parse_args()
 
 
@@ -162,6 +164,43 @@ def cpu_baseline(layer, data):
                       "the C loops run on 1 thread, the float64 matmuls on `cores` BLAS threads"}
 
 
+def all_layers(args):
+    """Network aggregate (not the headline line): one pass over every layer of a configuration,
+    each stage timed over `steps` back-to-back calls with HIP events; prints one JSON line with
+    per-stage totals in microseconds and the per-layer rows."""
+    import torch
+    from paper_2302_06058_amd import synth
+    rows, tot = [], {}
+    for layer in synth.get_config(args.config):
+        data = synth.gen_layer(layer)
+        e = 2 if layer.dtype == "bf16" else 4
+        per_copy = e * layer.T * (layer.I + layer.J) * 2
+        copies = max(2, min(9, -(-(1 << 29) // per_copy)))
+        run = LayerRun(layer, data, copies)
+        run.step(0)
+        torch.cuda.synchronize()
+        row = {"layer": layer.name, "I": layer.I, "J": layer.J, "T": layer.T, "nm": f"{layer.N}:{layer.M}"}
+        for name, fn in run.stages:
+            for i in range(max(1, args.warmup // 4)):
+                fn(i % copies)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a.record()
+            for i in range(args.steps):
+                fn(i % copies)
+            b.record()
+            torch.cuda.synchronize()
+            row[name] = round(a.elapsed_time(b) * 1e3 / args.steps, 2)
+            tot[name] = tot.get(name, 0.0) + row[name]
+        rows.append(row)
+        del run, data
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "Bi-Mask hot path, sum over all layers of the configuration", "unit": "us",
+                      "config": args.config, "steps": args.steps, "n_layers": len(rows),
+                      "value": round(sum(tot.values()), 1), "stage_totals_us": {k: round(v, 1) for k, v in tot.items()},
+                      "layers": rows}), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -175,6 +214,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
+    if args.all_layers:
+        return all_layers(args)
     layer = synth.get_config(args.config)[args.layer]
     data = synth.gen_layer(layer)
     e = 2 if layer.dtype == "bf16" else 4
