@@ -139,8 +139,7 @@ int bimask_sparse_gemm_bwd(const void* dY, int64_t T, int64_t lddy, const int32_
     int64_t ldact = lddy;
     if (perm && !gemm_bwd_needs_gather(I, dtype, N, M)) {
         // short contraction: the column gather is fused into the GEMM's token-tile load
-        static const int resvar = [] { const char* e = getenv("BIMASK_RES_VARIANT"); return e ? atoi(e) : 1; }();
-        return launch_gemm_sp24_resident(Wb_values, Wb_index, J, I, dY, lddy, perm, T, dX, lddx, resvar, as_stream(stream));
+        return launch_gemm_sp24_resident(Wb_values, Wb_index, J, I, dY, lddy, perm, T, dX, lddx, as_stream(stream));
     }
     if (perm) {
         const size_t need = bimask_workspace_bytes(BIMASK_WS_GEMM_BWD, I, J, T, 0, dtype, N, M);

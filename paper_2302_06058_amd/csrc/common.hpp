@@ -116,11 +116,13 @@ int launch_gather_cols(const void* dY, int64_t T, int64_t ld, const int32_t* per
 int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int64_t K, bool sparse24,
                 const void* Bm, int64_t T, int64_t ldb, void* C, int64_t ldc, int dtype, hipStream_t s);
 
+// workgroup tile (weight rows x tokens) of the streaming 2:4 kernel
+enum class Sp24Tile { k256x64, k128x64, k256x128 };
 int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
-                     int64_t ldb, void* C, int64_t ldc, int variant, hipStream_t s);
+                     int64_t ldb, void* C, int64_t ldc, Sp24Tile tile, hipStream_t s);
 
 int launch_gemm_sp24_resident(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc,
-                              int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, int variant,
+                              int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc,
                               hipStream_t s);
 // true when the backward GEMM needs the gathered copy of g(Y) in the workspace
 bool gemm_bwd_needs_gather(int64_t I, int dtype, int N, int M);

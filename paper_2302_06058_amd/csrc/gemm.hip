@@ -11,7 +11,6 @@
 // bf16, other: v_mfma_f32_32x32x16_bf16 on the dense masked weights (this file)
 // fp32       : plain fp32 FMA kernel, small problems only (this file)
 #include "common.hpp"
-#include <cstdlib>
 
 namespace bimask {
 namespace {
@@ -448,8 +447,7 @@ int launch_gather_cols(const void* dY, int64_t T, int64_t ld, const int32_t* per
 }
 
 bool gemm_bwd_needs_gather(int64_t I, int dtype, int N, int M) {
-    static const int resvar = [] { const char* e = getenv("BIMASK_RES_VARIANT"); return e ? atoi(e) : 1; }();
-    return !(dtype == BIMASK_BF16 && N == 2 && M == 4 && I <= 512 && resvar >= 0);
+    return !(dtype == BIMASK_BF16 && N == 2 && M == 4 && I <= 512);
 }
 
 int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int64_t K, bool sparse24,
@@ -465,11 +463,8 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
         return check_launch();
     }
     if (sparse24) {
-        // tuning hooks: tile shape / prefetch depth of the streaming kernel, wave count of the resident one
-        static const int forced = [] { const char* e = getenv("BIMASK_GEMM_VARIANT"); return e ? atoi(e) : -1; }();
-        static const int resvar = [] { const char* e = getenv("BIMASK_RES_VARIANT"); return e ? atoi(e) : 1; }();
-        if (K <= 512 && resvar >= 0) {
-            const int rc = launch_gemm_sp24_resident(A_values, A_index, Adim, K, Bm, ldb, nullptr, T, C, ldc, resvar, s);
+        if (K <= 512) {
+            const int rc = launch_gemm_sp24_resident(A_values, A_index, Adim, K, Bm, ldb, nullptr, T, C, ldc, s);
             if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
         }
         // large problems: 256 x 128 tiles on 8 wavefronts (half the weight traffic per token);
@@ -480,8 +475,8 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
         const bool narrow = (w256 - w128) * 5 >= w256;
         // few tokens and few weight tiles: 256-row tiles would leave CUs idle
         const bool underfilled = ceil_div(Adim, 256) * ceil_div(T, 64) <= 128;
-        const int variant = forced >= 0 ? forced : (narrow || underfilled ? 4 : (big ? 14 : 0));
-        return launch_gemm_sp24(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, variant, s);
+        const Sp24Tile tile = narrow || underfilled ? Sp24Tile::k128x64 : (big ? Sp24Tile::k256x128 : Sp24Tile::k256x64);
+        return launch_gemm_sp24(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, tile, s);
     }
     return run_dense(A_values, Adim, K, Bm, T, ldb, C, ldc, s);
 }

@@ -287,29 +287,19 @@ int run_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const
 
 }  // namespace
 
-// 2:4 GEMM on the fragment-major weight operand.  `variant` picks tile shape / prefetch depth.
+// 2:4 GEMM on the fragment-major weight operand.
+//   256 x 64, 4 wavefronts, 2 stages prefetched: mid-size problems (the grid covers the chip)
+//   128 x 64, 4 wavefronts: weight dimensions that would leave 256-row tiles largely empty, or few tokens
+//   256 x 128, 8 wavefronts, 1 stage prefetched: large problems (half the weight traffic per token)
 int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
-                     int64_t ldb, void* C, int64_t ldc, int variant, hipStream_t s) {
+                     int64_t ldb, void* C, int64_t ldc, Sp24Tile tile, hipStream_t s) {
     if (!aligned16(A) || !aligned16(meta)) return BIMASK_ERR_ALIGN;
-    switch (variant) {
-        case 0: return run_sp24<256, 64, 4, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 1: return run_sp24<256, 64, 2, 2, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 2: return run_sp24<128, 128, 2, 2, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 3: return run_sp24<256, 64, 4, 1, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 4: return run_sp24<128, 64, 4, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 5: return run_sp24<256, 128, 2, 2, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 6: return run_sp24<128, 64, 2, 2, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 7: return run_sp24<256, 64, 2, 2, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 8: return run_sp24<256, 64, 8, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 9: return run_sp24<256, 64, 8, 1, 3>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 10: return run_sp24<256, 32, 8, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 11: return run_sp24<128, 64, 4, 1, 3>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 12: return run_sp24<256, 128, 4, 1, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 13: return run_sp24<256, 128, 8, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 14: return run_sp24<256, 128, 8, 1, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        case 15: return run_sp24<256, 128, 4, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-        default: return BIMASK_ERR_UNSUPPORTED;
+    switch (tile) {
+        case Sp24Tile::k256x64: return run_sp24<256, 64, 4, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case Sp24Tile::k128x64: return run_sp24<128, 64, 4, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case Sp24Tile::k256x128: return run_sp24<256, 128, 8, 1, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
     }
+    return BIMASK_ERR_UNSUPPORTED;
 }
 
 }  // namespace bimask

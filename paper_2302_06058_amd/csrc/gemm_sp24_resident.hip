@@ -326,7 +326,7 @@ static int pick_rows_per_tile(int64_t T, int bn, int cus) {
 // Short-contraction 2:4 GEMM with the token tile resident in LDS and an optional fused
 // column gather.  Returns BIMASK_ERR_UNSUPPORTED when K is too long for this kernel.
 int launch_gemm_sp24_resident(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc,
-                              int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, int variant,
+                              int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc,
                               hipStream_t s) {
     if (K > 512) return BIMASK_ERR_UNSUPPORTED;
     if (!aligned16(A) || !aligned16(meta)) return BIMASK_ERR_ALIGN;
@@ -347,8 +347,7 @@ int launch_gemm_sp24_resident(const void* A, const uint32_t* meta, int64_t Adim,
         case 3: return run_resident<256, 64, WAVES, 3>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s); \
         default: return run_resident<256, 64, WAVES, 4>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s); \
     }
-    if (variant == 1) { BIMASK_RES(8) }
-    BIMASK_RES(4)
+    BIMASK_RES(8)
 #undef BIMASK_RES
 }
 
