@@ -45,7 +45,8 @@ __device__ __forceinline__ int resb_off(int t, int r) {
 
 // PERSIST: the grid is smaller than the number of token tiles; a workgroup walks over its
 // tiles and requests the rows of the next one before it multiplies the current one, and the
-// inverse permutation (and, with a single weight tile, the weight fragments) are set up once.
+// 16-bit copy of the permutation (and, with a single weight tile, the weight fragments) are set
+// up once.
 template <int BM, int BN, int WAVES_M, int NSTG, bool PERSIST>
 __global__ void __launch_bounds__(64 * WAVES_M)
 k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int64_t K,
@@ -93,7 +94,7 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
     BIMASK_LOAD_WTILE(0, at_begin)
 
     // ---- resident token tile.  The g(Y) rows are requested first (registers), then LDS is
-    // zeroed and the inverse permutation built while they are in flight.
+    // zeroed and the permutation copied to LDS while they are in flight.
     const int G = static_cast<int>((K + 7) >> 3);        // 8-element granules per token row
     constexpr int NL = (BN * NSTG * 16 + NT - 1) / NT;
     u32x4 v[NL];
