@@ -58,7 +58,11 @@ __device__ __forceinline__ u32x4 load_guarded(const uint16_t* row, int64_t k, in
 
 // BGUARD: token rows are not 16-byte aligned or K is not a multiple of 128; every token
 // load is then bounds-checked against K (the weight operand is zero-padded by its format).
-template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD>
+// BHALF: only the first half of the wavefronts fetch the token tile (twice as much each).  The
+// token rows come from HBM, the weights from L2; a wavefront's loads complete in order, so weight
+// loads queued behind token loads inherit their latency -- with BHALF half of the wavefronts
+// carry nothing but L2 hits.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD, bool BHALF>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int64_t K,
             const uint16_t* __restrict__ Bm, int64_t T, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
@@ -68,13 +72,15 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int NBUF = PF + 1;
-    constexpr int NB_ = BN * 16 / NT;                   // 16-byte granules of Bm per thread per stage
-    static_assert(NB_ >= 1 && (BN * 16) % NT == 0, "token tile too small");
+    constexpr int NTB = BHALF ? NT / 2 : NT;            // threads that fetch the token tile
+    constexpr int NB_ = BN * 16 / NTB;                  // 16-byte granules of Bm per fetching thread per stage
+    static_assert(NB_ >= 1 && (BN * 16) % NTB == 0, "token tile too small");
     extern __shared__ u32x4 smem_u4[];
     uint8_t* smem = reinterpret_cast<uint8_t*>(smem_u4);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+    const bool bfetch = !BHALF || __builtin_amdgcn_readfirstlane(wave) < WAVES_M * WAVES_N / 2;   // wave-uniform
     const int l32 = lane & 31, h = lane >> 5;
     // Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2, so
     // XCD x takes the contiguous chunk [x*per_xcd, (x+1)*per_xcd) of a grouped tile sequence in
@@ -109,7 +115,7 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
     int sb_off[NB_];
 #pragma unroll
     for (int it = 0; it < NB_; ++it) {
-        const int q = tid + NT * it, row = q >> 4, g = q & 15;
+        const int q = (BHALF ? tid & (NTB - 1) : tid) + NTB * it, row = q >> 4, g = q & 15;
         int64_t t = t0 + row;
         t = t < T ? t : T - 1;
         pb[it] = Bm + t * ldb + (BGUARD ? 0 : 8 * g);
@@ -131,9 +137,9 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
 #define BIMASK_LOAD_STAGE(slot, kt)                                                              \
     {                                                                                            \
         const int64_t kk = static_cast<int64_t>(kt) * SK;                                          \
-        _Pragma("unroll") for (int it = 0; it < NB_; ++it) {                                     \
+        if (bfetch) _Pragma("unroll") for (int it = 0; it < NB_; ++it) {                        \
             if constexpr (BGUARD)                                                                \
-                rb[slot][it] = load_guarded(pb[it], kk + 8 * ((tid + NT * it) & 15), K);        \
+                rb[slot][it] = load_guarded(pb[it], kk + 8 * ((tid + NTB * it) & 15), K);       \
             else                                                                                 \
                 rb[slot][it] = *reinterpret_cast<const u32x4*>(pb[it] + kk);                     \
         }                                                                                        \
@@ -161,7 +167,7 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
 #define BIMASK_STEP(u, kt, DO_LOAD)                                                              \
     {                                                                                            \
         uint8_t* sB = smem + ((kt) & 1) * S::kStage;                                             \
-        _Pragma("unroll") for (int it = 0; it < NB_; ++it)                                       \
+        if (bfetch) _Pragma("unroll") for (int it = 0; it < NB_; ++it)                          \
             *reinterpret_cast<u32x4*>(sB + sb_off[it]) = rb[u][it];                              \
         if (DO_LOAD) {                                                                           \
             const int ktl = (kt) + PF < nk ? (kt) + PF : nk - 1;                                 \
@@ -258,11 +264,11 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD, bool BHALF>
 int run_sp24_t(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb,
              void* C, int64_t ldc, hipStream_t s) {
     using S = SpSmem<BM, BN>;
-    auto kern = k_gemm_sp24<BM, BN, WAVES_M, WAVES_N, PF, BGUARD>;
+    auto kern = k_gemm_sp24<BM, BN, WAVES_M, WAVES_N, PF, BGUARD, BHALF>;
     if (S::kTotal > 48 * 1024) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 S::kTotal) != hipSuccess) return BIMASK_ERR_HIP;
@@ -277,12 +283,12 @@ int run_sp24_t(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, con
     return check_launch();
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int PF>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BHALF = false>
 int run_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb,
              void* C, int64_t ldc, hipStream_t s) {
     const bool fastb = K % SK == 0 && aligned16(Bm) && (ldb * 2) % 16 == 0;
-    if (fastb) return run_sp24_t<BM, BN, WAVES_M, WAVES_N, PF, false>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
-    return run_sp24_t<BM, BN, WAVES_M, WAVES_N, 1, true>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+    if (fastb) return run_sp24_t<BM, BN, WAVES_M, WAVES_N, PF, false, BHALF>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+    return run_sp24_t<BM, BN, WAVES_M, WAVES_N, 1, true, false>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
 }
 
 }  // namespace
@@ -295,7 +301,7 @@ int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t 
                      int64_t ldb, void* C, int64_t ldc, Sp24Tile tile, hipStream_t s) {
     if (!aligned16(A) || !aligned16(meta)) return BIMASK_ERR_ALIGN;
     switch (tile) {
-        case Sp24Tile::k256x64: return run_sp24<256, 64, 4, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case Sp24Tile::k256x64: return run_sp24<256, 64, 4, 1, 2, true>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
         case Sp24Tile::k128x64: return run_sp24<128, 64, 4, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
         case Sp24Tile::k256x128: return run_sp24<256, 128, 8, 1, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
     }
