@@ -331,6 +331,10 @@ int launch_gemm_sp24_resident(const void* A, const uint32_t* meta, int64_t Adim,
                               hipStream_t s) {
     if (K > 512) return BIMASK_ERR_UNSUPPORTED;
     if (!aligned16(A) || !aligned16(meta)) return BIMASK_ERR_ALIGN;
+    {   // narrow weights: one wavefront per token tile, weights in registers
+        const int rc = launch_gemm_sp24_narrow(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, s);
+        if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
+    }
     const int nstg = static_cast<int>(ceil_div(K, 128));
     if (Adim <= 128 && nstg <= 2) {
         // one narrow weight tile: the workgroup is a latency chain (fill, multiply, store), so

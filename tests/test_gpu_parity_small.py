@@ -249,6 +249,13 @@ def test_long_contraction_backward_uses_gather_pass(I, J, T):
     check_layer(I=I, J=J, N=2, M=4, dtype=synth.BF16, K=4, seed=900 + I, T=T)
 
 
+@pytest.mark.parametrize("I,J,T", [(64, 148, 131), (68, 148, 131), (132, 260, 77), (64, 148, 4100), (36, 12, 9)])
+def test_contiguous_rows_not_16_byte_aligned(I, J, T):
+    # row pitches of 296 / 136 / 520 / 24 bytes (the 7x7 stem's im2col width is 148): token tiles are
+    # fetched and written as aligned contiguous blocks; odd last tiles end in a partial 16-byte piece
+    check_layer(I=I, J=J, N=2, M=4, dtype=synth.BF16, K=4, seed=1000 + I + T, T=T)
+
+
 @pytest.mark.parametrize("I,J,T", [(256, 384, 100), (1024, 256, 96)])
 def test_leading_dimensions_side_stream_many_candidates(I, J, T):
     """Operands embedded in wider buffers (ld > columns), calls issued on a non-default stream,
