@@ -27,13 +27,18 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 union BFragR { bf16x16 v; u32x4 q[2]; };
 union AFragR { bf16x8 v; u32x4 q; };
 
-template <int BM, int BN, int NSTG>
+template <int BM, int BN, int NSTG, bool PERSIST>
 struct ResSmem {
     static constexpr int kB = NSTG * BN * 256;          // resident token tile, 256 B per row and stage
-    static constexpr int kInv = NSTG * 128 * 2;         // permutation (int16)
+    static constexpr int kPerm = NSTG * 128 * 2;        // permutation (int16)
     static constexpr int kOut = BN * BM * 2;            // one bf16 output tile (two of them: double buffer)
+    // The permutation is only read while the token tile is filled: it sits behind the un-permuted
+    // rows inside the output staging area and is re-written from a register for every tile.
+    // (Two 256 x 64 workgroups with a 128-long contraction then fit one CU's 160 KB exactly.)
+    static constexpr int kInv = 0;
+    static constexpr int kFill = kB + kPerm;
     // output staging (two tiles); the un-permuted row tile of the fill phase shares this area
-    static constexpr int kArea = 2 * kOut > kB ? 2 * kOut : kB;
+    static constexpr int kArea = 2 * kOut > kFill ? 2 * kOut : kFill;
     static constexpr int kTotal = kB + kInv + kArea;
 };
 
@@ -53,12 +58,12 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
                      const uint16_t* __restrict__ Bsrc, int64_t ldb, const int32_t* __restrict__ perm, int64_t T,
                      uint16_t* __restrict__ C, int64_t ldc, int rpt, bool vecB, bool vecC) {
     constexpr int NT = 64 * WAVES_M;
-    using S = ResSmem<BM, BN, NSTG>;
+    using S = ResSmem<BM, BN, NSTG, PERSIST>;
     constexpr int WM = BM / WAVES_M, TM = WM / 32, TN = BN / 32;
     extern __shared__ u32x4 smem_u4[];
     uint8_t* sB = reinterpret_cast<uint8_t*>(smem_u4);
-    int16_t* sP = reinterpret_cast<int16_t*>(sB + S::kB);              // the permutation, 16-bit
     uint8_t* lin = sB + S::kB + S::kInv;                               // un-permuted rows (shares the output staging area)
+    int16_t* sP = reinterpret_cast<int16_t*>(lin + S::kB);             // the permutation, 16-bit
 
     const int tid = threadIdx.x, lane = tid & 63, wm = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
@@ -116,9 +121,8 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
     }
     BIMASK_LOAD_ROWS(t0, rows)
     for (int it = tid; it < S::kB / 16; it += NT) reinterpret_cast<u32x4*>(sB)[it] = (u32x4){0u, 0u, 0u, 0u};
-    if (perm) {
-        for (int r = tid; r < NSTG * 128; r += NT) sP[r] = r < static_cast<int>(K) ? static_cast<int16_t>(perm[r]) : static_cast<int16_t>(0);
-    }
+    static_assert(NT >= NSTG * 128, "one permutation entry per thread");
+    const int16_t pown = perm && tid < static_cast<int>(K) ? static_cast<int16_t>(perm[tid]) : static_cast<int16_t>(0);
     // k positions beyond K keep the zeros written above; rows beyond `rows` keep whatever an
     // earlier tile left (their outputs are never stored).
     for (;;) {
@@ -126,6 +130,7 @@ k_gemm_sp24_resident(const uint16_t* __restrict__ A, const uint32_t* __restrict_
     if (perm) {
         // Eq. (10)'s column gather: the rows go to LDS as they are (16-byte stores), then each
         // thread assembles whole 16-byte granules of the permuted rows from 2-byte LDS reads
+        if (tid < NSTG * 128) sP[tid] = pown;
 #pragma unroll
         for (int it = 0; it < NL; ++it) {
             const int q = tid + NT * it;
@@ -288,7 +293,7 @@ constexpr unsigned kPersistGrid = 768;     // persistent variant: three workgrou
 template <int BM, int BN, int WAVES_M, int NSTG, bool PERSIST = false>
 int run_resident(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc, int64_t ldb,
                  const int32_t* perm, int64_t T, void* C, int64_t ldc, int rpt, hipStream_t s) {
-    using S = ResSmem<BM, BN, NSTG>;
+    using S = ResSmem<BM, BN, NSTG, PERSIST>;
     auto kern = k_gemm_sp24_resident<BM, BN, WAVES_M, NSTG, PERSIST>;
     if (S::kTotal > 48 * 1024) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -297,7 +302,17 @@ int run_resident(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, c
     const bool vecB = aligned16(Bsrc) && (ldb * 2) % 16 == 0;
     const bool vecC = aligned16(C) && (ldc * 2) % 16 == 0;
     unsigned grid = static_cast<unsigned>(ceil_div(T, rpt));
-    if (PERSIST && grid > kPersistGrid) grid = kPersistGrid;
+    if (PERSIST) {
+        unsigned cap = kPersistGrid;
+        if (BM > 128) {                              // large tiles: as many workgroups as stay resident
+            int occ = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void*>(kern), 64 * WAVES_M,
+                                                             static_cast<size_t>(S::kTotal)) != hipSuccess || occ < 1)
+                return BIMASK_ERR_HIP;
+            cap = 256u * static_cast<unsigned>(occ);
+        }
+        if (grid > cap) grid = cap;
+    }
     // few token tiles: split the weight tiles over blockIdx.y, as far as one round of 256
     // workgroups goes (the kernel runs one workgroup per CU; a second round costs a full pass)
     const int64_t tiles_all = ceil_div(Adim, BM);
@@ -351,6 +366,14 @@ int launch_gemm_sp24_resident(const void* A, const uint32_t* meta, int64_t Adim,
         case 2: return run_resident<256, 64, WAVES, 2>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s); \
         case 3: return run_resident<256, 64, WAVES, 3>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s); \
         default: return run_resident<256, 64, WAVES, 4>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, rpt, s); \
+    }
+    if (ceil_div(T, 64) >= 1024) {
+        // many token tiles per CU: persistent workgroups fetch the next tile's rows during the current one
+        switch (nstg) {
+            case 1: return run_resident<256, 64, 8, 1, true>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, 64, s);
+            case 2: return run_resident<256, 64, 8, 2, true>(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, 64, s);
+            default: break;
+        }
     }
     BIMASK_RES(8)
 #undef BIMASK_RES
