@@ -181,7 +181,7 @@ def all_layers(args):
         torch.cuda.synchronize()
         row = {"layer": layer.name, "I": layer.I, "J": layer.J, "T": layer.T, "nm": f"{layer.N}:{layer.M}"}
         for name, fn in run.stages:
-            for i in range(max(1, args.warmup // 4)):
+            for i in range(max(args.warmup, args.steps)):      # as long as the timed run: clocks settle
                 fn(i % copies)
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()

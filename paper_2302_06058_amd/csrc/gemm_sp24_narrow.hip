@@ -33,8 +33,9 @@ __device__ __forceinline__ void wave_lds_fence() { __builtin_amdgcn_fence(__ATOM
 // LDS pitch of a row of `w` bf16: the row itself, plus 8 bytes when that is a multiple of 16
 __host__ __device__ inline int narrow_pitch(int w) { return (w & 7) ? 2 * w : 2 * w + 8; }
 
-// registers: TM * NSTG * 18 for the weights, TM * 16 accumulators, NSTG * 32 for the rows in flight
-constexpr int narrow_waves_per_simd(int tm, int nstg) { return tm * nstg * 18 + tm * 16 + nstg * 32 + 60 <= 256 ? 2 : 1; }
+// registers: TM * NSTG * 18 for the weights, TM * 16 accumulators, NSTG * 32 for the rows in flight;
+// two wavefronts per SIMD (256 registers each) except for the longest contractions
+constexpr int narrow_waves_per_simd(int tm, int nstg) { return nstg >= 4 || (nstg == 3 && tm >= 2) ? 1 : 2; }
 
 template <int TM, int NSTG>
 __global__ void __launch_bounds__(64, narrow_waves_per_simd(TM, NSTG))
