@@ -68,7 +68,7 @@ class LayerRun:
         dev = self.W.device
         self.Y = [torch.empty((L.T, L.I), dtype=tdt, device=dev) for _ in range(copies)]
         self.dX = [torch.empty((L.T, L.J), dtype=tdt, device=dev) for _ in range(copies)]
-        s24 = (L.N, L.M) == (2, 4)
+        s24 = L.N <= 2                         # operands in the sparse matrix instruction's 2-of-4 format
         wj, wi = bm.mask_words(L.J), bm.mask_words(L.I)
         self.B = torch.empty((L.I, wj), dtype=torch.int32, device=dev)
         self.Bbar = torch.empty((L.I, wj), dtype=torch.int32, device=dev)
@@ -132,8 +132,8 @@ def algorithmic(layer):
     """Algorithmic bytes / flops per call of each stage (what the method itself must move)."""
     L = layer
     e = 2 if L.dtype == "bf16" else 4
-    s24 = (L.N, L.M) == (2, 4)
-    wbytes = L.I * L.J * ((e * L.N / L.M + 1 / 8) if s24 else e)       # compressed (or dense masked) operand
+    s24 = L.N <= 2
+    wbytes = L.I * L.J * ((e / 2 + 1 / 8) if s24 else e)       # 2-of-4 compressed (or dense masked) operand
     mask = L.I * L.J / 8
     return {
         "forward_mask_compress": {"bytes": L.I * L.J * e + mask + wbytes, "flops": 0},

@@ -34,9 +34,12 @@
  * tensor core as consumer).  Let the operand have `rows` x `cols` logical entries:
  *   transposed = 0: rows = I, cols = J (groups of M along J);
  *   transposed = 1: rows = J, cols = I (groups of M along the permuted row index r).
- *   for (N, M) = (2, 4), "fragment-major" layout, laid out so that one wavefront of a
- *   32x32x32 sparse matrix instruction fetches its whole A operand with contiguous
- *   16-byte lanes.  Rp = rows rounded up to 32, Cp = cols rounded up to 128, KS = Cp/128.
+ *   for N <= 2 (2:4, 1:4, 2:8, 1:8, 2:16, 1:16): the 2-of-4 format of the 32x32x32 sparse
+ *   matrix instruction, in a "fragment-major" layout in which one wavefront fetches its
+ *   whole A operand with contiguous 16-byte lanes.  M is a multiple of 4, so a mask with at
+ *   most N <= 2 ones per group of M holds at most two ones in every aligned group of 4
+ *   positions; "group" below is such a group of 4, whatever M is.
+ *   Rp = rows rounded up to 32, Cp = cols rounded up to 128, KS = Cp/128.
  *     Logical content per row: slot s = 2g + n (n = 0, 1) of group g holds the n-th slot
  *     value of that group, slots in ascending position order; the group's index nibble is
  *     p0 | (p1 << 2), p0 < p1.  The slot positions are the mask's ones; a group whose
@@ -48,7 +51,7 @@
  *             q%8 (bits [4(q%8)+3 : 4(q%8)]) of word
  *             ((r/32 * KS + st) * 64 + r%32 + 32*(q/16)) * 2 + (q/8)%2.
  *     Both buffers must be 16-byte aligned.
- *   for every other (N, M): values is the dense masked matrix rows x cols, row-major
+ *   for N > 2 (4:8, ...): values is the dense masked matrix rows x cols, row-major
  *     (zeros where the mask is 0), and index is not written (may be NULL).
  *   bimask_operand_elems / bimask_operand_index_words give the buffer sizes.
  *
@@ -109,7 +112,7 @@ BIMASK_API int bimask_forward_mask(const void *W, int64_t I, int64_t J, int64_t 
 /* Forward mask and the compressed forward operand in one pass over W (same results as
  * bimask_forward_mask followed by bimask_compress_nm(transposed = 0)).
  *   values  out  bimask_operand_elems(I, J, N, M) elements
- *   index   out  bimask_operand_index_words(I, J, N, M) words for 2:4, else ignored      */
+ *   index   out  bimask_operand_index_words(I, J, N, M) words for N <= 2, else ignored      */
 BIMASK_API int bimask_forward_mask_compress(const void *W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
                                  uint32_t *B_bits, void *values, uint32_t *index, void *stream);
 
@@ -138,7 +141,7 @@ BIMASK_API int bimask_backward_mask(const void *W, int64_t I, int64_t J, int64_t
 /* Backward mask and the transposed compressed backward operand in one pass (same results
  * as bimask_backward_mask followed by bimask_compress_nm(transposed = 1)).
  *   values  out  bimask_operand_elems(J, I, N, M) elements
- *   index   out  bimask_operand_index_words(J, I, N, M) words for 2:4, else ignored      */
+ *   index   out  bimask_operand_index_words(J, I, N, M) words for N <= 2, else ignored      */
 BIMASK_API int bimask_backward_mask_compress(const void *W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
                                   const uint32_t *B_bits, const int32_t *perm, uint32_t *Bbar_bits,
                                   void *values, uint32_t *index, void *stream);
@@ -153,7 +156,7 @@ BIMASK_API int bimask_compress_nm(const void *W, int64_t I, int64_t J, int64_t l
                        void *values, uint32_t *index, void *stream);
 
 /* Forward GEMM, Eq. (3):  Y[t][i] = sum_j X[t][j] * (B .* W)[i][j], with (B .* W) given in
- * compressed form (transposed = 0).  bf16: fp32 accumulation, bf16 output, 2:4 on the
+ * compressed form (transposed = 0).  bf16: fp32 accumulation, bf16 output, N <= 2 on the
  * sparse matrix cores, other ratios on the dense matrix cores; f32: fp32 throughout.
  *   X  in  T x J (ldx >= J);   Y  out  T x I (ldy >= I);   same dtype as the values.
  *   Pointers at least 4-byte aligned and, for bf16, even leading dimensions (else

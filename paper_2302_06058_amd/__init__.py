@@ -121,8 +121,8 @@ def operand_index_words(rows: int, cols: int, N: int, M: int) -> int:
 
 
 def _values_shape(rows: int, cols: int, N: int, M: int):
-    """2:4: flat fragment-major buffer (see include/bimask.h); else the dense rows x cols matrix."""
-    return (operand_elems(rows, cols, N, M),) if (N, M) == (2, 4) else (rows, cols)
+    """N <= 2: flat fragment-major buffer (see include/bimask.h); else the dense rows x cols matrix."""
+    return (operand_elems(rows, cols, N, M),) if N <= 2 else (rows, cols)
 
 
 def _index_shape(rows: int, cols: int, N: int, M: int):
@@ -169,7 +169,7 @@ def bimask_forward_mask_compress(W, N: int, M: int, B_bits=None, values=None, in
         B_bits = _empty((I, mask_words(J)), torch.int32, W)
     if values is None:
         values = _empty(_values_shape(I, J, N, M), W.dtype, W)
-    if index is None and (N, M) == (2, 4):
+    if index is None and N <= 2:
         index = _empty(_index_shape(I, J, N, M), torch.int32, W)
     _check("bimask_forward_mask_compress",
            lib().bimask_forward_mask_compress(_ptr(W), I, J, ldw, _dtype_code(W), N, M, _ptr(B_bits),
@@ -222,7 +222,7 @@ def bimask_backward_mask_compress(W, N: int, M: int, B_bits, perm=None, Bbar_bit
         Bbar_bits = _empty((I, mask_words(J)), torch.int32, W)
     if values is None:
         values = _empty(_values_shape(J, I, N, M), W.dtype, W)
-    if index is None and (N, M) == (2, 4):
+    if index is None and N <= 2:
         index = _empty(_index_shape(J, I, N, M), torch.int32, W)
     _check("bimask_backward_mask_compress",
            lib().bimask_backward_mask_compress(_ptr(W), I, J, ldw, _dtype_code(W), N, M, _ptr(B_bits), _ptr(perm),
@@ -238,7 +238,7 @@ def bimask_compress_nm(W, N: int, M: int, mask_bits, perm=None, transposed: int 
     rows, cols = (J, I) if transposed else (I, J)
     if values is None:
         values = _empty(_values_shape(rows, cols, N, M), W.dtype, W)
-    if index is None and (N, M) == (2, 4):
+    if index is None and N <= 2:
         index = _empty(_index_shape(rows, cols, N, M), torch.int32, W)
     _check("bimask_compress_nm",
            lib().bimask_compress_nm(_ptr(W), I, J, ldw, _dtype_code(W), N, M, _ptr(mask_bits), _ptr(perm),

@@ -37,8 +37,8 @@ int check_gemm(const void* act, int64_t T, int64_t ldact, int64_t kdim, const vo
     if (int rc = check_dtype(dtype)) return rc;
     if (int rc = check_nm(N, M)) return rc;
     if (T <= 0 || I <= 0 || J <= 0 || I % M || J % M || ldact < kdim || ldout < outdim) return BIMASK_ERR_SHAPE;
-    if (N == 2 && M == 4 && !index) return BIMASK_ERR_NULL;
-    if (N == 2 && M == 4 && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
+    if (uses_sp24(N, M) && !index) return BIMASK_ERR_NULL;
+    if (uses_sp24(N, M) && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
     if (dtype == BIMASK_BF16) {
         // rows are read in 4-byte units at least
         if (ldact % 2 || ldout % 2) return BIMASK_ERR_ALIGN;
@@ -64,9 +64,9 @@ int bimask_forward_mask_compress(const void* W, int64_t I, int64_t J, int64_t ld
                                  uint32_t* B_bits, void* values, uint32_t* index, void* stream) {
     if (int rc = check_matrix(W, I, J, ldw, dtype, N, M)) return rc;
     if (!B_bits || !values) return BIMASK_ERR_NULL;
-    if (N == 2 && M == 4 && !index) return BIMASK_ERR_NULL;
+    if (uses_sp24(N, M) && !index) return BIMASK_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(values) % esize(dtype)) return BIMASK_ERR_ALIGN;
-    if (N == 2 && M == 4 && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
+    if (uses_sp24(N, M) && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
     return launch_forward(W, I, J, ldw, dtype, N, M, nullptr, B_bits, values, index, true, as_stream(stream));
 }
 
@@ -97,9 +97,9 @@ int bimask_backward_mask_compress(const void* W, int64_t I, int64_t J, int64_t l
                                   uint32_t* index, void* stream) {
     if (int rc = check_matrix(W, I, J, ldw, dtype, N, M)) return rc;
     if (!B_bits || !Bbar_bits || !values) return BIMASK_ERR_NULL;
-    if (N == 2 && M == 4 && !index) return BIMASK_ERR_NULL;
+    if (uses_sp24(N, M) && !index) return BIMASK_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(values) % esize(dtype)) return BIMASK_ERR_ALIGN;
-    if (N == 2 && M == 4 && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
+    if (uses_sp24(N, M) && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
     return launch_backward(W, I, J, ldw, dtype, N, M, B_bits, nullptr, perm, Bbar_bits, values, index, true,
                            as_stream(stream));
 }
@@ -109,9 +109,9 @@ int bimask_compress_nm(const void* W, int64_t I, int64_t J, int64_t ldw, int dty
                        uint32_t* index, void* stream) {
     if (int rc = check_matrix(W, I, J, ldw, dtype, N, M)) return rc;
     if (!mask_bits || !values) return BIMASK_ERR_NULL;
-    if (N == 2 && M == 4 && !index) return BIMASK_ERR_NULL;
+    if (uses_sp24(N, M) && !index) return BIMASK_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(values) % esize(dtype)) return BIMASK_ERR_ALIGN;
-    if (N == 2 && M == 4 && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
+    if (uses_sp24(N, M) && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
     if (transposed != 0 && transposed != 1) return BIMASK_ERR_SHAPE;
     if (!transposed) {
         if (perm) return BIMASK_ERR_UNSUPPORTED;                     // rows of the forward operand are not permuted
@@ -126,7 +126,7 @@ int bimask_sparse_gemm_fwd(const void* X, int64_t T, int64_t ldx, const void* Wf
                            size_t workspace_bytes, void* stream) {
     (void)workspace; (void)workspace_bytes;
     if (int rc = check_gemm(X, T, ldx, J, Wf_values, Wf_index, I, J, dtype, N, M, Y, ldy, I)) return rc;
-    const bool sp = (N == 2 && M == 4);
+    const bool sp = uses_sp24(N, M);
     return launch_gemm(Wf_values, Wf_index, I, J, sp, X, T, ldx, Y, ldy, dtype, as_stream(stream));
 }
 
@@ -134,7 +134,7 @@ int bimask_sparse_gemm_bwd(const void* dY, int64_t T, int64_t lddy, const int32_
                            const uint32_t* Wb_index, int64_t I, int64_t J, int dtype, int N, int M, void* dX,
                            int64_t lddx, void* workspace, size_t workspace_bytes, void* stream) {
     if (int rc = check_gemm(dY, T, lddy, I, Wb_values, Wb_index, I, J, dtype, N, M, dX, lddx, J)) return rc;
-    const bool sp = (N == 2 && M == 4);
+    const bool sp = uses_sp24(N, M);
     const void* act = dY;
     int64_t ldact = lddy;
     if (perm && !gemm_bwd_needs_gather(I, dtype, N, M)) {
@@ -154,12 +154,12 @@ int bimask_sparse_gemm_bwd(const void* dY, int64_t T, int64_t lddy, const int32_
 
 int64_t bimask_operand_elems(int64_t rows, int64_t cols, int N, int M) {
     if (rows <= 0 || cols <= 0) return 0;
-    if (N == 2 && M == 4) return round_up(rows, 32) * (round_up(cols, 128) / 2);
+    if (uses_sp24(N, M)) return round_up(rows, 32) * (round_up(cols, 128) / 2);
     return rows * cols;
 }
 
 int64_t bimask_operand_index_words(int64_t rows, int64_t cols, int N, int M) {
-    if (rows <= 0 || cols <= 0 || !(N == 2 && M == 4)) return 0;
+    if (rows <= 0 || cols <= 0 || !uses_sp24(N, M)) return 0;
     return round_up(rows, 32) * (round_up(cols, 128) / 32);
 }
 

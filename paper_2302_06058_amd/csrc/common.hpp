@@ -17,6 +17,10 @@ struct F32  { using raw = uint32_t; static constexpr uint32_t kAbs = 0x7FFFFFFFu
 __host__ __device__ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 __host__ __device__ inline int ilog2(int m) { int b = 0; while ((1 << b) < m) ++b; return b; }
 
+// N:M ratios with N <= 2 keep at most two entries in every aligned group of 4 (M is a multiple
+// of 4), so their operands use the 2-of-4 format of the sparse matrix instruction.
+__host__ __device__ inline bool uses_sp24(int N, int M) { return N <= 2 && M % 4 == 0; }
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 

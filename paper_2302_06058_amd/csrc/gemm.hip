@@ -447,7 +447,7 @@ int launch_gather_cols(const void* dY, int64_t T, int64_t ld, const int32_t* per
 }
 
 bool gemm_bwd_needs_gather(int64_t I, int dtype, int N, int M) {
-    return !(dtype == BIMASK_BF16 && N == 2 && M == 4 && I <= 512);
+    return !(dtype == BIMASK_BF16 && uses_sp24(N, M) && I <= 512);
 }
 
 int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int64_t K, bool sparse24,

@@ -77,7 +77,7 @@ __device__ __forceinline__ void top2_of4_bf16(uint32_t w0, uint32_t w1, uint32_t
 
 // ---------------------------------------------------------------------------------
 // Forward direction: one thread owns CH consecutive columns of one row.
-//   MODE 0: mask only   2: + dense masked values   (2:4 compression: k_forward24 below)
+//   MODE 0: mask only   2: + dense masked values   (2-of-4 compression: k_forward24 below)
 // mask_in != nullptr: the mask is read instead of selected (stand-alone compression).
 // ---------------------------------------------------------------------------------
 template <typename DT, int M, int CH>
@@ -163,9 +163,9 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
 // plus 16 mask bits and 16 index bits, which neighbouring lanes merge into whole words.
 // mask_in != nullptr: the mask is read instead of selected (stand-alone compression).
 // ---------------------------------------------------------------------------------
-template <typename DT>
+template <typename DT, int M>
 __global__ void __launch_bounds__(kThreads)
-k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t ldw,
+k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t ldw, int N,
             const uint32_t* __restrict__ mask_in, uint32_t* __restrict__ B_bits,
             typename DT::raw* __restrict__ values, uint32_t* __restrict__ index,
             int wpr, int ks, int64_t row_octets, bool vec_in, bool stream_out) {
@@ -189,7 +189,7 @@ k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_
     // bounds checks, neighbour exchange by a DPP quad swap.  Everything else takes the guarded
     // path below.
     const bool fast = __builtin_amdgcn_readfirstlane(static_cast<int>(
-        sizeof(raw) == 2 && !mask_in && vec_in && r8 * 8 + 8 <= I && static_cast<int64_t>(st0 + U) * 128 <= J)) != 0;
+        sizeof(raw) == 2 && M == 4 && N == 2 && !mask_in && vec_in && r8 * 8 + 8 <= I && static_cast<int64_t>(st0 + U) * 128 <= J)) != 0;
     if constexpr (sizeof(raw) == 2) {
         if (fast) {
             u32x4 t[U][2];
@@ -243,8 +243,8 @@ k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_
         // values: lane vector (row tile i/32, stage st, instruction q%4, lane i%32 + 32*(q/4))
         raw* dst = values + ((((i >> 5) * ks + st) * 4 + (q & 3)) * 64 + (i & 31) + 32 * (q >> 2)) * 8;
         bool done = false;
-        if constexpr (sizeof(raw) == 2) {
-            if (!mask_in) {                                // wave-uniform: select and compress in one go
+        if constexpr (sizeof(raw) == 2 && M == 4) {
+            if (!mask_in && N == 2) {                      // wave-uniform: select and compress in one go
                 uint32_t ow[4];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
@@ -273,13 +273,14 @@ k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_
             if (mask_in) {
                 if (in_mask) bits = reinterpret_cast<const uint16_t*>(mask_in)[i * wpr * 2 + (j0 >> 4)];
             } else {
+                // Eq. (4): top N of every M consecutive weights (16 / M groups in this lane's 16)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    uint32_t key[4];
+                for (int g = 0; g < 16 / M; ++g) {
+                    uint32_t key[M];
 #pragma unroll
-                    for (int m = 0; m < 4; ++m) key[m] = elem<DT>(w[u][g >> 1], (g & 1) * 4 + m) & DT::kAbs;
-                    const uint32_t sel = (j0 + 4 * g < Jr) ? select_top_n<4>(key, 2) : 0u;
-                    bits |= sel << (4 * g);
+                    for (int m = 0; m < M; ++m) key[m] = elem<DT>(w[u][(g * M + m) >> 3], (g * M + m) & 7) & DT::kAbs;
+                    const uint32_t sel = (j0 + M * g < Jr) ? select_top_n<M>(key, N) : 0u;
+                    bits |= sel << (M * g);
                 }
             }
             uint32_t out[8];
@@ -319,7 +320,7 @@ k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_
 // permuted rows x 8 columns.  Rows of W are gathered through P, every row read is a
 // contiguous 2*TC-byte (bf16) segment.  Transposed outputs go through LDS so
 // that they leave as contiguous runs along the permuted-row axis.
-//   MODE 0: Bbar only   1: + transposed 2:4 values/index   2: + transposed dense masked
+//   MODE 0: Bbar only   1: + transposed 2-of-4 values/index (N <= 2)   2: + transposed dense masked
 // Bbar_in != nullptr: Bbar is read instead of selected (stand-alone compression).
 // ---------------------------------------------------------------------------------
 constexpr int kTR = 128;   // permuted rows per tile = one 128-deep stage of the transposed operand
@@ -398,17 +399,24 @@ k_backward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t
             const int col = ch * 8 + q;
             if (c0 + col >= J) continue;                 // ragged last chunk: not a row of the operand
             if (mode == 1) {
-                if constexpr (M == 4) {
-                    const int p0 = __builtin_ctz(sel), p1 = 31 - __builtin_clz(sel);
-                    const uint32_t e0 = elem<DT>(w[0], q), e1 = elem<DT>(w[1], q), e2 = elem<DT>(w[2], q), e3 = elem<DT>(w[3], q);
-                    const uint32_t v0 = ((keep >> p0) & 1u) ? pick4(e0, e1, e2, e3, p0) : 0u;
-                    const uint32_t v1 = ((keep >> p1) & 1u) ? pick4(e0, e1, e2, e3, p1) : 0u;
-                    // output row = this column, slots 2kb, 2kb+1 of the stage: lane half kb/16,
-                    // instruction (kb%16)/4, elements 2(kb%4), 2(kb%4)+1
-                    raw* d = lds_val + (((col >> 5) * 4 + ((kb & 15) >> 2)) * 64 + (col & 31) + 32 * (kb >> 4)) * 8 + 2 * (kb & 3);
+                // N <= 2: every aligned group of 4 permuted rows keeps at most two entries; its slots
+                // are the kept positions completed with the lowest-index other positions
+#pragma unroll
+                for (int sg = 0; sg < M / 4; ++sg) {
+                    const uint32_t k4 = (keep >> (4 * sg)) & 15u;
+                    const uint32_t sl = complete_slots<4>(k4, 2);
+                    const int p0 = __builtin_ctz(sl), p1 = 31 - __builtin_clz(sl);
+                    const uint32_t e0 = elem<DT>(w[4 * sg + 0], q), e1 = elem<DT>(w[4 * sg + 1], q),
+                                   e2 = elem<DT>(w[4 * sg + 2], q), e3 = elem<DT>(w[4 * sg + 3], q);
+                    const uint32_t v0 = ((k4 >> p0) & 1u) ? pick4(e0, e1, e2, e3, p0) : 0u;
+                    const uint32_t v1 = ((k4 >> p1) & 1u) ? pick4(e0, e1, e2, e3, p1) : 0u;
+                    // output row = this column, group g4 of the stage's 32: lane half g4/16,
+                    // instruction (g4%16)/4, elements 2(g4%4), 2(g4%4)+1
+                    const int g4 = kb * (M / 4) + sg;
+                    raw* d = lds_val + (((col >> 5) * 4 + ((g4 & 15) >> 2)) * 64 + (col & 31) + 32 * (g4 >> 4)) * 8 + 2 * (g4 & 3);
                     if constexpr (sizeof(raw) == 2) *reinterpret_cast<uint32_t*>(d) = v0 | (v1 << 16);
                     else *reinterpret_cast<uint2*>(d) = make_uint2(v0, v1);
-                    lds_meta[col * 32 + kb] = static_cast<uint8_t>(p0 | (p1 << 2));
+                    lds_meta[col * 32 + g4] = static_cast<uint8_t>(p0 | (p1 << 2));
                 }
             } else if (mode == 2) {
 #pragma unroll
@@ -671,21 +679,18 @@ int run_forward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const u
     using raw = typename DT::raw;
     constexpr int CH = M == 16 ? 16 : 8;
     const int wpr = static_cast<int>(ceil_div(J, 32));
-    if constexpr (M == 4) {
-        if (mode == 1) {
-            if (!aligned16(values) || !aligned16(index)) return BIMASK_ERR_ALIGN;
-            const bool vec_in = aligned16(W) && (ldw * sizeof(raw)) % 16 == 0;
-            const int ks = static_cast<int>(round_up(J, 128) / 128);
-            const int64_t row_octets = round_up(I, 32) / 8;
-            const int64_t units = row_octets * ((ks + 1) / 2);     // one wavefront each (two stages)
-            hipLaunchKernelGGL((k_forward24<DT>), dim3(static_cast<unsigned>(ceil_div(units, kThreads / 64))),
-                               dim3(kThreads), 0, s, static_cast<const raw*>(W), I, J, ldw, mask_in, B_bits,
-                               static_cast<raw*>(values), index, wpr, ks, row_octets, vec_in,
-                               static_cast<size_t>(I) * J * sizeof(raw) / 2 > kL2Keep);
-            return check_launch();
-        }
+    if (mode == 1) {                                   // N <= 2: the 2-of-4 operand format
+        if (!aligned16(values) || !aligned16(index)) return BIMASK_ERR_ALIGN;
+        const bool vec_in = aligned16(W) && (ldw * sizeof(raw)) % 16 == 0;
+        const int ks = static_cast<int>(round_up(J, 128) / 128);
+        const int64_t row_octets = round_up(I, 32) / 8;
+        const int64_t units = row_octets * ((ks + 1) / 2);     // one wavefront each (two stages)
+        hipLaunchKernelGGL((k_forward24<DT, M>), dim3(static_cast<unsigned>(ceil_div(units, kThreads / 64))),
+                           dim3(kThreads), 0, s, static_cast<const raw*>(W), I, J, ldw, N, mask_in, B_bits,
+                           static_cast<raw*>(values), index, wpr, ks, row_octets, vec_in,
+                           static_cast<size_t>(I) * J * sizeof(raw) / 2 > kL2Keep);
+        return check_launch();
     }
-    if (mode == 1) return BIMASK_ERR_NM;               // compressed operands exist for 2:4 only
     const int cpr = wpr * 32 / CH;
     const int64_t rows_pad = I;
     const bool vec_in = aligned16(W) && (ldw * sizeof(raw)) % 16 == 0;
@@ -730,7 +735,7 @@ int run_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const 
                  const uint32_t* Bbar_in, const int32_t* perm, uint32_t* Bbar_bits, void* values,
                  uint32_t* index, int mode, hipStream_t s) {
     if constexpr (std::is_same<DT, BF16>::value && M == 4) {
-        if (mode == 1 && !Bbar_in) {
+        if (mode == 1 && !Bbar_in && N == 2) {
             if (!aligned16(values) || !aligned16(index)) return BIMASK_ERR_ALIGN;
             const int wpr = static_cast<int>(ceil_div(J, 32));
             const bool vec_in = aligned16(W) && (ldw * 2) % 16 == 0;
@@ -764,7 +769,7 @@ int run_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const 
 int launch_forward(const void* W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
                    const uint32_t* mask_in, uint32_t* B_bits, void* values, uint32_t* index,
                    bool want_values, hipStream_t s) {
-    const int mode = !want_values ? 0 : ((N == 2 && M == 4) ? 1 : 2);
+    const int mode = !want_values ? 0 : (uses_sp24(N, M) ? 1 : 2);
 #define BIMASK_FWD(DT, MM) return run_forward<DT, MM>(W, I, J, ldw, N, mask_in, B_bits, values, index, mode, s)
     if (dtype == BIMASK_BF16) {
         if (M == 4) BIMASK_FWD(BF16, 4);
@@ -782,7 +787,7 @@ int launch_forward(const void* W, int64_t I, int64_t J, int64_t ldw, int dtype, 
 int launch_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
                     const uint32_t* B_bits, const uint32_t* Bbar_in, const int32_t* perm,
                     uint32_t* Bbar_bits, void* values, uint32_t* index, bool want_values, hipStream_t s) {
-    const int mode = !want_values ? 0 : ((N == 2 && M == 4) ? 1 : 2);
+    const int mode = !want_values ? 0 : (uses_sp24(N, M) ? 1 : 2);
 #define BIMASK_BWD(DT, MM) return run_backward<DT, MM>(W, I, J, ldw, N, B_bits, Bbar_in, perm, Bbar_bits, values, index, mode, s)
     if (dtype == BIMASK_BF16) {
         if (M == 4) BIMASK_BWD(BF16, 4);

@@ -32,7 +32,8 @@ def test_workspace_bytes():
     # long contractions (I > 512) gather g(Y) into the workspace, short bf16 2:4 ones fuse the gather
     assert bm.workspace_bytes(bm.WS_GEMM_BWD, 1024, 256, 12544, 0, bm.BF16, 2, 4) == 12544 * 1024 * 2
     assert bm.workspace_bytes(bm.WS_GEMM_BWD, 256, 2304, 12544, 0, bm.BF16, 2, 4) == 0
-    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 256, 2304, 12544, 0, bm.BF16, 1, 4) == 12544 * 256 * 2
+    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 256, 2304, 12544, 0, bm.BF16, 1, 4) == 0       # N <= 2: sparse cores too
+    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 256, 2304, 12544, 0, bm.BF16, 4, 8) == 12544 * 256 * 2
     assert bm.workspace_bytes(bm.WS_GEMM_BWD, 64, 128, 32, 0, bm.F32, 2, 4) == 32 * 64 * 4
     assert bm.workspace_bytes(bm.WS_GEMM_FWD, 256, 2304, 12544, 0, bm.BF16, 2, 4) == 0
     ws = bm.workspace_bytes(bm.WS_PERM_SEARCH, 256, 2304, 0, 100, bm.BF16, 2, 4)

@@ -49,7 +49,7 @@ def check_full_layer(layer, t_cap=T_CAP, full_scores_limit=4e8):
     dt = L.dtype
     N, M, I, J = L.N, L.M, L.I, L.J
     T = min(L.T, t_cap) if t_cap else L.T
-    s24 = (N, M) == (2, 4)
+    s24 = N <= 2          # operands in the 2-of-4 format of the sparse matrix instruction
     Wh = synth.gen_weights(L)
     perms = synth.gen_perms(L)
     W64 = synth.to_f64(Wh, dt)
@@ -60,9 +60,9 @@ def check_full_layer(layer, t_cap=T_CAP, full_scores_limit=4e8):
     B, vals, index = bm.bimask_forward_mask_compress(W, N, M)
     assert (words(B) == oracle.pack_bits(B_o)).all(), f"{L.name}: forward mask"
     if s24:
-        val_o, idx_o = oracle.compress_fwd(W64, B_o, N, M)
+        val_o, idx_o = oracle.compress_fwd(W64, B_o, 2, 4)        # N <= 2: at most two ones per group of 4
         gv, gi, pz = untile24(raw_bits(vals, dt), words(index), I, J)
-        assert pz and (gi == oracle.pack_index(idx_o, M)).all(), f"{L.name}: forward index"
+        assert pz and (gi == oracle.pack_index(idx_o, 4)).all(), f"{L.name}: forward index"
         assert same_bits(gv, f64_to_raw(val_o, dt), dt), f"{L.name}: forward values"
         del val_o, idx_o, gv, gi
     else:
@@ -90,9 +90,12 @@ def check_full_layer(layer, t_cap=T_CAP, full_scores_limit=4e8):
     Bbar, vb, ib = bm.bimask_backward_mask_compress(W, N, M, B, P_dev)
     assert (words(Bbar) == oracle.pack_bits(Bbar_o)).all(), f"{L.name}: backward mask"
     if s24:
-        valb_o, idxb_o = oracle.compress_bwd(W64, B_o, P, N, M)
+        if (N, M) == (2, 4):
+            valb_o, idxb_o = oracle.compress_bwd(W64, B_o, P, N, M)
+        else:
+            valb_o, idxb_o = oracle.compress_fwd(np.ascontiguousarray(W64[P, :].T), np.ascontiguousarray(Bbar_o.T), 2, 4)
         gv, gi, pz = untile24(raw_bits(vb, dt), words(ib), J, I)
-        assert pz and (gi == oracle.pack_index(idxb_o, M)).all(), f"{L.name}: backward index"
+        assert pz and (gi == oracle.pack_index(idxb_o, 4)).all(), f"{L.name}: backward index"
         assert same_bits(gv, f64_to_raw(valb_o, dt), dt), f"{L.name}: backward values"
         del valb_o, idxb_o, gv, gi
     else:

@@ -48,7 +48,7 @@ def check_layer(I, J, N, M, dtype, K, seed, kind="normal", T=0):
     W64 = synth.to_f64(Wh, dtype)
     perms = perms_of(I, K, seed + 1, identity_first=(seed % 2 == 0))
     W = to_dev(Wh, dtype)
-    s24 = (N, M) == (2, 4)
+    s24 = N <= 2          # operands in the 2-of-4 format of the sparse matrix instruction
 
     # ---- forward mask (+ fused compress, + stand-alone compress)
     B_o = oracle.forward_mask(W64, N, M)
@@ -60,8 +60,10 @@ def check_layer(I, J, N, M, dtype, K, seed, kind="normal", T=0):
     vals_s, index_s = bm.bimask_compress_nm(W, N, M, B, None, 0)
     got_v, got_vs = raw_bits(vals, dtype), raw_bits(vals_s, dtype)
     if s24:
-        val_o, idx_o = oracle.compress_fwd(W64, B_o, N, M)
-        want_v, want_i = f64_to_raw(val_o, dtype), oracle.pack_index(idx_o, M)
+        # (2, 4): the method's own compression.  Other ratios with N <= 2: the mask already holds at
+        # most two ones per aligned group of 4, and the oracle compresses that mask as 2-of-4.
+        val_o, idx_o = oracle.compress_fwd(W64, B_o, 2, 4)
+        want_v, want_i = f64_to_raw(val_o, dtype), oracle.pack_index(idx_o, 4)
         got_v, got_i, pz = untile24(got_v, words(index), I, J)
         got_vs, got_is, pzs = untile24(got_vs, words(index_s), I, J)
         assert pz and pzs, "forward operand padding must be zero"
@@ -97,8 +99,12 @@ def check_layer(I, J, N, M, dtype, K, seed, kind="normal", T=0):
         vb_s, ib_s = bm.bimask_compress_nm(W, N, M, Bbar, P_d, 1)
         got_vb, got_vbs = raw_bits(vb, dtype), raw_bits(vb_s, dtype)
         if s24:
-            valb_o, idxb_o = oracle.compress_bwd(W64, B_o, P_h, N, M)
-            want_vb, want_ib = f64_to_raw(valb_o, dtype), oracle.pack_index(idxb_o, M)
+            if (N, M) == (2, 4):
+                valb_o, idxb_o = oracle.compress_bwd(W64, B_o, P_h, N, M)
+            else:       # the transposed masked matrix, compressed as 2-of-4 along the permuted rows
+                Wp = W64 if P_h is None else W64[P_h, :]
+                valb_o, idxb_o = oracle.compress_fwd(np.ascontiguousarray(Wp.T), np.ascontiguousarray(Bbar_o.T), 2, 4)
+            want_vb, want_ib = f64_to_raw(valb_o, dtype), oracle.pack_index(idxb_o, 4)
             got_vb, got_ib, pz = untile24(got_vb, words(ib), J, I)
             got_vbs, got_ibs, pzs = untile24(got_vbs, words(ib_s), J, I)
             assert pz and pzs, "backward operand padding must be zero"
