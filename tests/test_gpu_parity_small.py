@@ -255,14 +255,17 @@ def test_long_contraction_backward_uses_gather_pass(I, J, T):
     check_layer(I=I, J=J, N=2, M=4, dtype=synth.BF16, K=4, seed=900 + I, T=T)
 
 
-@pytest.mark.parametrize("I,J,T", [(64, 148, 131), (68, 148, 131), (132, 260, 77), (64, 148, 4100), (36, 12, 9)])
-def test_contiguous_rows_not_16_byte_aligned(I, J, T):
-    # row pitches of 296 / 136 / 520 / 24 bytes (the 7x7 stem's im2col width is 148): token tiles are
+@pytest.mark.parametrize("I,J,T", [(64, 148, 131), (68, 148, 131), (132, 260, 77), (64, 148, 4100), (36, 12, 9),
+                                   (64, 64, 1), (224, 64, 31), (192, 96, 65), (64, 256, 8200)])
+def test_narrow_weights_and_unaligned_contiguous_rows(I, J, T):
+    # narrow weight matrices run one wavefront per 32-token tile (weights in registers; more than 160
+    # weight rows are split over two wavefronts); row pitches of 296 / 136 / 520 / 24 bytes (the 7x7 stem's im2col width is 148): token tiles are
     # fetched and written as aligned contiguous blocks; odd last tiles end in a partial 16-byte piece
     check_layer(I=I, J=J, N=2, M=4, dtype=synth.BF16, K=4, seed=1000 + I + T, T=T)
 
 
-@pytest.mark.parametrize("I,J,T", [(256, 384, 100), (1024, 256, 96)])
+@pytest.mark.parametrize("I,J,T", [(256, 384, 100), (1024, 256, 96),
+                                   (64, 128, 77), (160, 64, 33), (256, 64, 70)])   # narrow weights: one wavefront per token tile
 def test_leading_dimensions_side_stream_many_candidates(I, J, T):
     """Operands embedded in wider buffers (ld > columns), calls issued on a non-default stream,
     K > 128 candidates; the padding columns of the outputs must stay untouched."""
