@@ -28,7 +28,7 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 # see profiles/bench_config2_hbm_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
     (2, "sparse_gemm_fwd"): int((30913 * 2.0 + 6272) * 1024),
-    (2, "sparse_gemm_bwd"): int((5863 * 2.0 + 56448) * 1024),
+    (2, "sparse_gemm_bwd"): int((5861 * 2.0 + 56449) * 1024),
 }
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X published dense bf16 matrix peak
