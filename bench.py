@@ -14,6 +14,7 @@ steps do not find them in the 256 MB last-level cache.
 from __future__ import annotations
 
 import argparse
+import numpy as np
 import json
 import os
 import sys
@@ -46,6 +47,12 @@ def parse():
     ap.add_argument("--breakdown-reps", type=int, default=30)
     ap.add_argument("--all-layers", action="store_true",
                     help="network aggregate: time every layer of the configuration and print per-stage totals")
+    ap.add_argument("--grouped", action="store_true",
+                    help="mask and search steps of ALL layers of the configuration through the grouped entry points")
+    ap.add_argument("--search-table", action="store_true",
+                    help="permutation search over all ResNet-50 layers for 2:4, 4:8, 1:4, 2:8, 1:16 (the shape of the paper's Table 6)")
+    ap.add_argument("--delta-t", type=int, default=100,
+                    help="steps between two permutation searches (Sec. 4.1) for the amortised secondary figure")
     return ap.parse_args()
 
 
@@ -201,6 +208,117 @@ def all_layers(args):
                       "layers": rows}), flush=True)
 
 
+def grouped_network(args):
+    """Forward masks, searches and backward masks of every layer of a configuration, issued the way a
+    training step can issue them (Alg. 1 treats layers independently): one grouped call per stage for the
+    whole network, against the same stages as one call per layer.  Microseconds per pass over the network."""
+    import torch
+    import paper_2302_06058_amd as bm
+    from paper_2302_06058_amd import synth
+    from helpers import to_dev, i32_dev
+    layers = synth.get_config(args.config)
+    by_nm = {}
+    for L in layers:
+        by_nm.setdefault((L.N, L.M, L.dtype), []).append(L)
+    st = torch.cuda.current_stream().cuda_stream
+    res = {"forward_mask_compress": [0.0, 0.0], "perm_search": [0.0, 0.0], "backward_mask_compress": [0.0, 0.0]}
+    n_launch_groups = 0
+    for (N, M, dts), Ls in by_nm.items():
+        code = bm.BF16 if dts == "bf16" else bm.F32
+        tdt = torch.bfloat16 if dts == "bf16" else torch.float32
+        entries, single = [], {k: [] for k in res}
+        for L in Ls:
+            W, Pd = to_dev(synth.gen_weights(L), L.dtype), i32_dev(synth.gen_perms(L))
+            dev = W.device
+            i32 = lambda n: torch.empty((n,), dtype=torch.int32, device=dev)
+            nws = max(16, bm.workspace_bytes(bm.WS_PERM_SEARCH, L.I, L.J, 0, L.K, code, N, M))
+            e = dict(W=W, B_bits=torch.empty((L.I, bm.mask_words(L.J)), dtype=torch.int32, device=dev),
+                     Wf_values=torch.empty((bm.operand_elems(L.I, L.J, N, M),), dtype=tdt, device=dev),
+                     Wf_index=i32(max(4, bm.operand_index_words(L.I, L.J, N, M))),
+                     perms=Pd, scores=i32(L.K), best=i32(1), best_perm=i32(L.I),
+                     workspace=torch.empty((nws,), dtype=torch.uint8, device=dev),
+                     Bbar_bits=torch.empty((L.I, bm.mask_words(L.J)), dtype=torch.int32, device=dev),
+                     Wb_values=torch.empty((bm.operand_elems(L.J, L.I, N, M),), dtype=tdt, device=dev),
+                     Wb_index=i32(max(4, bm.operand_index_words(L.J, L.I, N, M))))
+            entries.append(e)
+            single["forward_mask_compress"].append(bm.prepare("bimask_forward_mask_compress", W, L.I, L.J, L.J, code, N, M,
+                                                              e["B_bits"], e["Wf_values"], e["Wf_index"], st))
+            single["perm_search"].append(bm.prepare("bimask_perm_search", e["B_bits"], L.I, L.J, N, M, Pd, L.K, e["scores"],
+                                                    e["best"], e["best_perm"], e["workspace"], nws, st))
+            single["backward_mask_compress"].append(bm.prepare("bimask_backward_mask_compress", W, L.I, L.J, L.J, code, N, M,
+                                                               e["B_bits"], e["best_perm"], e["Bbar_bits"], e["Wb_values"],
+                                                               e["Wb_index"], st))
+        arr = bm.group_layers(entries)
+        K = Ls[0].K
+        grouped = {"forward_mask_compress": lambda: bm.bimask_forward_mask_compress_group(arr, code, N, M),
+                   "perm_search": lambda: bm.bimask_perm_search_group(arr, N, M, K),
+                   "backward_mask_compress": lambda: bm.bimask_backward_mask_compress_group(arr, code, N, M)}
+        n_launch_groups += 1
+        for name in res:
+            for which, fn in ((0, lambda: [c() for c in single[name]]), (1, grouped[name])):
+                for _ in range(max(args.warmup, args.steps)):
+                    fn()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                a.record()
+                for _ in range(args.steps):
+                    fn()
+                b.record()
+                torch.cuda.synchronize()
+                res[name][which] += a.elapsed_time(b) * 1e3 / args.steps
+    print(json.dumps({"metric": "mask and search steps of a whole network, per-layer calls vs grouped calls", "unit": "us",
+                      "config": args.config, "n_layers": len(layers), "steps": args.steps,
+                      "per_layer_calls_us": {k: round(v[0], 1) for k, v in res.items()},
+                      "grouped_calls_us": {k: round(v[1], 1) for k, v in res.items()},
+                      "sum_per_layer_us": round(sum(v[0] for v in res.values()), 1),
+                      "sum_grouped_us": round(sum(v[1] for v in res.values()), 1)}), flush=True)
+
+
+def search_table(args):
+    """Whole-network permutation search (forward mask given, K = 100 candidates scored and the best
+    picked, per layer) for the five N:M patterns of the paper's Table 6, on the ResNet-50 layer
+    shapes.  Rows / columns are padded to multiples of M where a shape needs it (M = 8, 16)."""
+    import torch
+    import paper_2302_06058_amd as bm
+    from paper_2302_06058_amd import synth
+    from helpers import to_dev, i32_dev
+    out = {}
+    for (N, M) in [(2, 4), (4, 8), (1, 4), (2, 8), (1, 16)]:
+        total_us, launches = 0.0, 0
+        for L in synth.config3(N, M):
+            Ip = (L.I + M - 1) // M * M
+            Wh = synth.gen_weights(L)
+            if Ip != L.I:                                  # fc: 1000 rows -> 1008 for M = 16 (zero rows)
+                Wh = np.concatenate([Wh, np.zeros((Ip - L.I, L.J), dtype=Wh.dtype)])
+            rng = np.random.default_rng([L.seed, 77])
+            perms = np.stack([rng.permutation(Ip) for _ in range(L.K)]).astype(np.int32)
+            W, Pd = to_dev(Wh, L.dtype), i32_dev(perms)
+            B = bm.bimask_forward_mask(W, N, M)
+            scores = torch.empty((L.K,), dtype=torch.int32, device=W.device)
+            best = torch.empty((1,), dtype=torch.int32, device=W.device)
+            P = torch.empty((Ip,), dtype=torch.int32, device=W.device)
+            nws = max(16, bm.workspace_bytes(bm.WS_PERM_SEARCH, Ip, L.J, 0, L.K, bm.BF16, N, M))
+            ws = torch.empty((nws,), dtype=torch.uint8, device=W.device)
+            call = bm.prepare("bimask_perm_search", B, Ip, L.J, N, M, Pd, L.K, scores, best, P, ws, nws,
+                              torch.cuda.current_stream().cuda_stream)
+            for _ in range(max(args.warmup, args.steps)):
+                call()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a.record()
+            for _ in range(args.steps):
+                call()
+            b.record()
+            torch.cuda.synchronize()
+            total_us += a.elapsed_time(b) * 1e3 / args.steps
+            launches += 1
+        out[f"{N}:{M}"] = round(total_us / 1e3, 4)
+    print(json.dumps({"metric": "permutation search, all 54 ResNet-50 layers, K = 100 (one search per layer)",
+                      "unit": "ms", "steps": args.steps, "layers": launches, "search_ms": out,
+                      "paper_table6_seconds_a100": {"2:4": 15.5, "4:8": 14.3, "1:4": 13.6, "2:8": 15.7, "1:16": 15.0},
+                      "note": "the paper does not say how many searches its figure covers"}), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -216,6 +334,10 @@ def main():
 
     if args.all_layers:
         return all_layers(args)
+    if args.search_table:
+        return search_table(args)
+    if args.grouped:
+        return grouped_network(args)
     layer = synth.get_config(args.config)[args.layer]
     data = synth.gen_layer(layer)
     e = 2 if layer.dtype == "bf16" else 4
@@ -264,6 +386,18 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     dom_us = sum(a.elapsed_time(b) for a, b in dom_pairs) * 1e3 / len(dom_pairs)
 
+    # -- secondary figure: the step as Alg. 1 runs it between two searches (P kept for delta-T steps):
+    #    forward mask, forward GEMM, backward mask with the cached P, backward GEMM
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i in range(args.steps):
+        r = i % copies
+        for name, fn in run.stages:
+            if name != "perm_search":
+                fn(r)
+    torch.cuda.synchronize()
+    ms_no_search = (time.perf_counter() - t1) * 1e3 / args.steps
+
     dom_bytes, dom_flops = alg[dominant]["bytes"], alg[dominant]["flops"]
     gbs = dom_bytes / (dom_us * 1e-6) / 1e9
     tfl = dom_flops / (dom_us * 1e-6) / 1e12
@@ -289,6 +423,8 @@ def main():
         "stages_us": {k: {kk: round(vv, 2) for kk, vv in v.items()} for k, v in stage_us.items()},
         "stages_sum_us": round(sum(v["avg"] for v in stage_us.values()), 2),
         "host_enqueue_ms_per_step": round(issue_ms, 5),
+        "amortised": {"delta_t": args.delta_t, "ms_per_step_without_search": round(ms_no_search, 5),
+                      "ms_per_step_search_every_delta_t": round(ms_no_search + max(ms_per_step - ms_no_search, 0.0) / args.delta_t, 5)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layer, data)

@@ -176,6 +176,44 @@ BIMASK_API int bimask_sparse_gemm_bwd(const void *dY, int64_t T, int64_t lddy, c
                            int dtype, int N, int M, void *dX, int64_t lddx,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* Grouped calls: the mask and search steps of n INDEPENDENT layers (all layers of a network,
+ * say) in a few launches instead of 2-3 per layer.  Layers this small are bound by launch
+ * latency, and Alg. 1 treats every layer separately, so a training step can issue them
+ * together: all forward masks first, then all searches, then all backward masks.  Results are
+ * identical to calling the per-layer functions in a loop; all layers of one call share dtype,
+ * N:M and (for the search) the number of candidates K.
+ *   layers   HOST array of n descriptors (read during the call only); the pointers inside
+ *            are device pointers with the meaning, size and alignment rules of the per-layer
+ *            calls:  forward  uses W, I, J, ldw -> B_bits, Wf_values, Wf_index
+ *                    search   uses B_bits, I, J, perms -> scores, best, best_perm (may be
+ *                             NULL), with workspace / workspace_bytes as in bimask_perm_search
+ *                    backward uses W, I, J, ldw, B_bits, best_perm (the permutation; NULL =
+ *                             identity) -> Bbar_bits, Wb_values, Wb_index
+ * Errors: as the per-layer calls; the first failing layer's code is returned and nothing is
+ * launched if any layer fails validation.                                                */
+typedef struct bimask_group_layer {
+    const void *W;
+    int64_t I, J, ldw;
+    uint32_t *B_bits;
+    void *Wf_values;
+    uint32_t *Wf_index;
+    const int32_t *perms;
+    int32_t *scores;
+    int32_t *best;
+    int32_t *best_perm;
+    void *workspace;
+    size_t workspace_bytes;
+    uint32_t *Bbar_bits;
+    void *Wb_values;
+    uint32_t *Wb_index;
+} bimask_group_layer;
+
+BIMASK_API int bimask_forward_mask_compress_group(const bimask_group_layer *layers, int n, int dtype, int N, int M,
+                                       void *stream);
+BIMASK_API int bimask_perm_search_group(const bimask_group_layer *layers, int n, int N, int M, int K, void *stream);
+BIMASK_API int bimask_backward_mask_compress_group(const bimask_group_layer *layers, int n, int dtype, int N, int M,
+                                        void *stream);
+
 /* Buffer sizes of a compressed operand with `rows` x `cols` logical entries: number of
  * elements of `values` and of uint32 words of `index` (0 when no index is written).     */
 BIMASK_API int64_t bimask_operand_elems(int64_t rows, int64_t cols, int N, int M);

@@ -29,6 +29,9 @@ _SIGNATURES = {
     "bimask_compress_nm": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR, _INT, _PTR, _PTR, _PTR]),
     "bimask_sparse_gemm_fwd": (_INT, [_PTR, _I64, _I64, _PTR, _PTR, _I64, _I64, _INT, _INT, _INT, _PTR, _I64, _PTR, _SZ, _PTR]),
     "bimask_sparse_gemm_bwd": (_INT, [_PTR, _I64, _I64, _PTR, _PTR, _PTR, _I64, _I64, _INT, _INT, _INT, _PTR, _I64, _PTR, _SZ, _PTR]),
+    "bimask_forward_mask_compress_group": (_INT, [_PTR, _INT, _INT, _INT, _INT, _PTR]),
+    "bimask_perm_search_group": (_INT, [_PTR, _INT, _INT, _INT, _INT, _PTR]),
+    "bimask_backward_mask_compress_group": (_INT, [_PTR, _INT, _INT, _INT, _INT, _PTR]),
     "bimask_operand_elems": (_I64, [_I64, _I64, _INT, _INT]),
     "bimask_operand_index_words": (_I64, [_I64, _I64, _INT, _INT]),
     "bimask_workspace_bytes": (_SZ, [_INT, _I64, _I64, _I64, _INT, _INT, _INT, _INT]),
@@ -276,3 +279,45 @@ def bimask_sparse_gemm_bwd(dY, perm, Wb_values, Wb_index, I: int, J: int, N: int
            lib().bimask_sparse_gemm_bwd(_ptr(dY), T, lddy, _ptr(perm), _ptr(Wb_values), _ptr(Wb_index), I, J,
                                         _dtype_code(dY), N, M, _ptr(dX), lddx, _ptr(workspace), wsb, _stream()))
     return dX
+
+
+# -- grouped calls: the mask / search steps of several independent layers in a few launches -------
+class GroupLayer(ctypes.Structure):
+    """Mirror of `bimask_group_layer` (include/bimask.h): one layer of a grouped call."""
+    _fields_ = [("W", _PTR), ("I", _I64), ("J", _I64), ("ldw", _I64), ("B_bits", _PTR), ("Wf_values", _PTR),
+                ("Wf_index", _PTR), ("perms", _PTR), ("scores", _PTR), ("best", _PTR), ("best_perm", _PTR),
+                ("workspace", _PTR), ("workspace_bytes", _SZ), ("Bbar_bits", _PTR), ("Wb_values", _PTR),
+                ("Wb_index", _PTR)]
+
+
+def group_layers(entries):
+    """A host array of `bimask_group_layer` from dicts of tensors / ints (argument marshalling only).
+    Keys: W (2-D tensor), B_bits, Wf_values, Wf_index, perms, scores, best, best_perm, workspace, Bbar_bits,
+    Wb_values, Wb_index -- absent keys stay NULL.  The tensors must outlive the calls that use the array."""
+    arr = (GroupLayer * len(entries))()
+    for g, e in zip(arr, entries):
+        W = e["W"]
+        _need_cuda(*[v for v in e.values() if hasattr(v, "is_cuda")])
+        g.W, g.I, g.J, g.ldw = W.data_ptr(), W.shape[0], W.shape[1], _rowmajor(W)
+        for key in ("B_bits", "Wf_values", "Wf_index", "perms", "scores", "best", "best_perm", "Bbar_bits",
+                    "Wb_values", "Wb_index"):
+            setattr(g, key, _ptr(e.get(key)))
+        ws = e.get("workspace")
+        g.workspace = _ptr(ws)
+        g.workspace_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    return arr
+
+
+def bimask_forward_mask_compress_group(layers, dtype: int, N: int, M: int) -> None:
+    _check("bimask_forward_mask_compress_group",
+           lib().bimask_forward_mask_compress_group(ctypes.cast(layers, _PTR), len(layers), dtype, N, M, _stream()))
+
+
+def bimask_perm_search_group(layers, N: int, M: int, K: int) -> None:
+    _check("bimask_perm_search_group",
+           lib().bimask_perm_search_group(ctypes.cast(layers, _PTR), len(layers), N, M, K, _stream()))
+
+
+def bimask_backward_mask_compress_group(layers, dtype: int, N: int, M: int) -> None:
+    _check("bimask_backward_mask_compress_group",
+           lib().bimask_backward_mask_compress_group(ctypes.cast(layers, _PTR), len(layers), dtype, N, M, _stream()))

@@ -121,6 +121,52 @@ int bimask_compress_nm(const void* W, int64_t I, int64_t J, int64_t ldw, int dty
                            as_stream(stream));
 }
 
+int bimask_forward_mask_compress_group(const bimask_group_layer* layers, int n, int dtype, int N, int M,
+                                       void* stream) {
+    if (!layers) return BIMASK_ERR_NULL;
+    if (n <= 0) return BIMASK_ERR_SHAPE;
+    for (int l = 0; l < n; ++l) {
+        const bimask_group_layer& a = layers[l];
+        if (int rc = check_matrix(a.W, a.I, a.J, a.ldw, dtype, N, M)) return rc;
+        if (!a.B_bits || !a.Wf_values) return BIMASK_ERR_NULL;
+        if (uses_sp24(N, M) && !a.Wf_index) return BIMASK_ERR_NULL;
+        if (reinterpret_cast<uintptr_t>(a.Wf_values) % esize(dtype)) return BIMASK_ERR_ALIGN;
+        if (uses_sp24(N, M) && (!aligned16(a.Wf_values) || !aligned16(a.Wf_index))) return BIMASK_ERR_ALIGN;
+    }
+    return launch_forward_group(layers, n, dtype, N, M, as_stream(stream));
+}
+
+int bimask_perm_search_group(const bimask_group_layer* layers, int n, int N, int M, int K, void* stream) {
+    if (!layers) return BIMASK_ERR_NULL;
+    if (n <= 0 || K <= 0) return BIMASK_ERR_SHAPE;
+    if (int rc = check_nm(N, M)) return rc;
+    for (int l = 0; l < n; ++l) {
+        const bimask_group_layer& a = layers[l];
+        if (!a.B_bits || !a.perms || !a.scores || !a.best) return BIMASK_ERR_NULL;
+        if (a.I <= 0 || a.J <= 0 || a.I % M || a.J % M) return BIMASK_ERR_SHAPE;
+        if (a.I > 0x7FFFFFFFll || a.J > 0x7FFFFFFFll) return BIMASK_ERR_SHAPE;
+        if ((a.I / M) * a.J > 0x7FFFFFFFll) return BIMASK_ERR_SHAPE;
+        if (!aligned16(a.perms)) return BIMASK_ERR_ALIGN;
+        if (!a.workspace || a.workspace_bytes < plan_perm_search(a.I, a.J, K, M).ws_bytes) return BIMASK_ERR_WORKSPACE;
+    }
+    return launch_perm_search_group(layers, n, N, M, K, as_stream(stream));
+}
+
+int bimask_backward_mask_compress_group(const bimask_group_layer* layers, int n, int dtype, int N, int M,
+                                        void* stream) {
+    if (!layers) return BIMASK_ERR_NULL;
+    if (n <= 0) return BIMASK_ERR_SHAPE;
+    for (int l = 0; l < n; ++l) {
+        const bimask_group_layer& a = layers[l];
+        if (int rc = check_matrix(a.W, a.I, a.J, a.ldw, dtype, N, M)) return rc;
+        if (!a.B_bits || !a.Bbar_bits || !a.Wb_values) return BIMASK_ERR_NULL;
+        if (uses_sp24(N, M) && !a.Wb_index) return BIMASK_ERR_NULL;
+        if (reinterpret_cast<uintptr_t>(a.Wb_values) % esize(dtype)) return BIMASK_ERR_ALIGN;
+        if (uses_sp24(N, M) && (!aligned16(a.Wb_values) || !aligned16(a.Wb_index))) return BIMASK_ERR_ALIGN;
+    }
+    return launch_backward_group(layers, n, dtype, N, M, as_stream(stream));
+}
+
 int bimask_sparse_gemm_fwd(const void* X, int64_t T, int64_t ldx, const void* Wf_values, const uint32_t* Wf_index,
                            int64_t I, int64_t J, int dtype, int N, int M, void* Y, int64_t ldy, void* workspace,
                            size_t workspace_bytes, void* stream) {

@@ -164,17 +164,17 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
 // mask_in != nullptr: the mask is read instead of selected (stand-alone compression).
 // ---------------------------------------------------------------------------------
 template <typename DT, int M>
-__global__ void __launch_bounds__(kThreads)
-k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t ldw, int N,
-            const uint32_t* __restrict__ mask_in, uint32_t* __restrict__ B_bits,
-            typename DT::raw* __restrict__ values, uint32_t* __restrict__ index,
-            int wpr, int ks, int64_t row_octets, bool vec_in, bool stream_out) {
+__device__ __forceinline__ void
+forward24_body(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t ldw, int N,
+               const uint32_t* __restrict__ mask_in, uint32_t* __restrict__ B_bits,
+               typename DT::raw* __restrict__ values, uint32_t* __restrict__ index,
+               int wpr, int ks, int64_t row_octets, bool vec_in, bool stream_out, int64_t block) {
     using raw = typename DT::raw;
     constexpr int PW = Pack<DT>::kWords;
     constexpr int U = 2;                               // stages per wavefront: 4 loads in flight per lane
     const int lane = threadIdx.x & 63;
     const int ksu = (ks + U - 1) / U;
-    const int64_t unit = static_cast<int64_t>(blockIdx.x) * (kThreads / 64) + (threadIdx.x >> 6);
+    const int64_t unit = block * (kThreads / 64) + (threadIdx.x >> 6);
     if (unit >= row_octets * ksu) return;
     const int64_t r8 = unit / ksu;
     const int st0 = static_cast<int>(unit - r8 * ksu) * U;
@@ -312,6 +312,53 @@ k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_
             if (B_bits && in_row && word < wpr) B_bits[i * wpr + word] = bw;
         }
     }
+}
+
+template <typename DT, int M>
+__global__ void __launch_bounds__(kThreads)
+k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t ldw, int N,
+            const uint32_t* __restrict__ mask_in, uint32_t* __restrict__ B_bits,
+            typename DT::raw* __restrict__ values, uint32_t* __restrict__ index,
+            int wpr, int ks, int64_t row_octets, bool vec_in, bool stream_out) {
+    forward24_body<DT, M>(W, I, J, ldw, N, mask_in, B_bits, values, index, wpr, ks, row_octets, vec_in, stream_out,
+                          static_cast<int64_t>(blockIdx.x));
+}
+
+// Grouped launches: the workgroups of several independent layers in one grid.  The per-layer
+// arguments travel as a table in the kernel arguments; first[l] is the first workgroup of
+// layer l.  Small layers are launch-latency bound, a network has dozens of them.
+constexpr int kGroupMax = 20;
+template <typename P>
+struct GroupTable {
+    int n;
+    unsigned first[kGroupMax + 1];
+    P p[kGroupMax];
+};
+template <typename P>
+__device__ __forceinline__ int group_layer_of(const GroupTable<P>& g, unsigned block) {
+    int l = 0;
+    while (l + 1 < g.n && block >= g.first[l + 1]) ++l;
+    return l;
+}
+
+struct FwdGroupP {
+    const void* W;
+    uint32_t* B_bits;
+    void* values;
+    uint32_t* index;
+    int64_t I, J, ldw, row_octets;
+    int wpr, ks, vec_in, stream_out;
+};
+
+template <typename DT, int M>
+__global__ void __launch_bounds__(kThreads)
+k_forward24_group(const GroupTable<FwdGroupP> g, int N) {
+    using raw = typename DT::raw;
+    const int l = group_layer_of(g, blockIdx.x);
+    const FwdGroupP& p = g.p[l];
+    forward24_body<DT, M>(static_cast<const raw*>(p.W), p.I, p.J, p.ldw, N, nullptr, p.B_bits, static_cast<raw*>(p.values),
+                          p.index, p.wpr, p.ks, p.row_octets, p.vec_in != 0, p.stream_out != 0,
+                          static_cast<int64_t>(blockIdx.x - g.first[l]));
 }
 
 // ---------------------------------------------------------------------------------
@@ -673,6 +720,39 @@ k_backward24_bf16(const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t 
                                    stream_out, active, r0, c0, lds[wave], lane);
 }
 
+struct BwdGroupP {
+    const uint16_t* W;
+    const uint32_t* B_bits;
+    const int32_t* perm;
+    uint32_t* Bbar_bits;
+    uint16_t* values;
+    uint32_t* index;
+    int64_t I, J, ldw, col_tiles, units;
+    int wpr, vec_in, vec_perm, stream_out;
+};
+
+// small bf16 2:4 layers, one wavefront (= one 32 x 64 tile) per workgroup
+__global__ void __launch_bounds__(64)
+k_backward24_bf16_group(const GroupTable<BwdGroupP> g) {
+    __shared__ uint4 lds[128];
+    const int l = group_layer_of(g, blockIdx.x);
+    const BwdGroupP& p = g.p[l];
+    const int lane = threadIdx.x & 63;
+    const int64_t unit = static_cast<int64_t>(blockIdx.x - g.first[l]);
+    const bool active = unit < p.units;
+    const int64_t rg = active ? unit / p.col_tiles : 0;
+    const int c0 = static_cast<int>((active ? unit - rg * p.col_tiles : 0) * 64);
+    const int64_t r0 = rg * 32;
+    const bool fast = __builtin_amdgcn_readfirstlane(
+        static_cast<int>(active && p.vec_in != 0 && r0 + 32 <= p.I && c0 + 64 <= p.J)) != 0;
+    if (fast)
+        backward24_tile<1, true>(p.W, p.I, p.J, p.ldw, p.B_bits, p.perm, p.Bbar_bits, p.values, p.index, p.wpr, p.vec_in != 0,
+                                 p.vec_perm != 0, p.stream_out != 0, active, r0, c0, lds, lane);
+    else
+        backward24_tile<1, false>(p.W, p.I, p.J, p.ldw, p.B_bits, p.perm, p.Bbar_bits, p.values, p.index, p.wpr, p.vec_in != 0,
+                                  p.vec_perm != 0, p.stream_out != 0, active, r0, c0, lds, lane);
+}
+
 template <typename DT, int M>
 int run_forward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const uint32_t* mask_in,
                 uint32_t* B_bits, void* values, uint32_t* index, int mode, hipStream_t s) {
@@ -782,6 +862,101 @@ int launch_forward(const void* W, int64_t I, int64_t J, int64_t ldw, int dtype, 
     }
 #undef BIMASK_FWD
     return BIMASK_ERR_NM;
+}
+
+// ---- grouped launches ------------------------------------------------------------
+namespace {
+
+template <typename DT, int M>
+int run_forward_group(const bimask_group_layer* L, int n, int N, hipStream_t s) {
+    using raw = typename DT::raw;
+    for (int b = 0; b < n; b += kGroupMax) {
+        GroupTable<FwdGroupP> g{};
+        g.n = n - b < kGroupMax ? n - b : kGroupMax;
+        unsigned blocks = 0;
+        for (int l = 0; l < g.n; ++l) {
+            const bimask_group_layer& a = L[b + l];
+            FwdGroupP& p = g.p[l];
+            p.W = a.W; p.B_bits = a.B_bits; p.values = a.Wf_values; p.index = a.Wf_index;
+            p.I = a.I; p.J = a.J; p.ldw = a.ldw;
+            p.wpr = static_cast<int>(ceil_div(a.J, 32));
+            p.ks = static_cast<int>(round_up(a.J, 128) / 128);
+            p.row_octets = round_up(a.I, 32) / 8;
+            p.vec_in = aligned16(a.W) && (a.ldw * sizeof(raw)) % 16 == 0;
+            p.stream_out = static_cast<size_t>(a.I) * a.J * sizeof(raw) / 2 > kL2Keep;
+            g.first[l] = blocks;
+            blocks += static_cast<unsigned>(ceil_div(p.row_octets * ((p.ks + 1) / 2), kThreads / 64));
+        }
+        g.first[g.n] = blocks;
+        hipLaunchKernelGGL((k_forward24_group<DT, M>), dim3(blocks), dim3(kThreads), 0, s, g, N);
+        if (int rc = check_launch()) return rc;
+    }
+    return BIMASK_OK;
+}
+
+}  // namespace
+
+// Forward mask + compressed operand of n independent layers (same dtype and N:M).
+int launch_forward_group(const bimask_group_layer* L, int n, int dtype, int N, int M, hipStream_t s) {
+    if (uses_sp24(N, M)) {
+#define BIMASK_FWDG(DT, MM) return run_forward_group<DT, MM>(L, n, N, s)
+        if (dtype == BIMASK_BF16) {
+            if (M == 4) BIMASK_FWDG(BF16, 4);
+            if (M == 8) BIMASK_FWDG(BF16, 8);
+            if (M == 16) BIMASK_FWDG(BF16, 16);
+        } else {
+            if (M == 4) BIMASK_FWDG(F32, 4);
+            if (M == 8) BIMASK_FWDG(F32, 8);
+            if (M == 16) BIMASK_FWDG(F32, 16);
+        }
+#undef BIMASK_FWDG
+        return BIMASK_ERR_NM;
+    }
+    for (int l = 0; l < n; ++l)                           // dense masked operands: one launch per layer
+        if (int rc = launch_forward(L[l].W, L[l].I, L[l].J, L[l].ldw, dtype, N, M, nullptr, L[l].B_bits, L[l].Wf_values,
+                                    L[l].Wf_index, true, s)) return rc;
+    return BIMASK_OK;
+}
+
+// Backward mask + transposed compressed operand of n independent layers, each with its own
+// permutation (best_perm).  Small bf16 2:4 layers share grouped launches; the others (large
+// enough to fill the chip on their own, or another dtype / ratio) are launched one by one.
+int launch_backward_group(const bimask_group_layer* L, int n, int dtype, int N, int M, hipStream_t s) {
+    const bool fastpath = dtype == BIMASK_BF16 && N == 2 && M == 4;
+    GroupTable<BwdGroupP> g{};
+    unsigned blocks = 0;
+    auto flush = [&]() -> int {
+        if (g.n == 0) return BIMASK_OK;
+        g.first[g.n] = blocks;
+        hipLaunchKernelGGL(k_backward24_bf16_group, dim3(blocks), dim3(64), 0, s, g);
+        g.n = 0;
+        blocks = 0;
+        return check_launch();
+    };
+    for (int l = 0; l < n; ++l) {
+        const bimask_group_layer& a = L[l];
+        const int64_t row_groups = ceil_div(a.I, 128) * 4;
+        if (!fastpath || row_groups * ceil_div(a.J, 128) >= 2048) {
+            if (int rc = launch_backward(a.W, a.I, a.J, a.ldw, dtype, N, M, a.B_bits, nullptr, a.best_perm, a.Bbar_bits,
+                                         a.Wb_values, a.Wb_index, true, s)) return rc;
+            continue;
+        }
+        BwdGroupP& p = g.p[g.n];
+        p.W = static_cast<const uint16_t*>(a.W); p.B_bits = a.B_bits; p.perm = a.best_perm; p.Bbar_bits = a.Bbar_bits;
+        p.values = static_cast<uint16_t*>(a.Wb_values); p.index = a.Wb_index;
+        p.I = a.I; p.J = a.J; p.ldw = a.ldw;
+        p.col_tiles = ceil_div(a.J, 64);
+        p.units = row_groups * p.col_tiles;
+        p.wpr = static_cast<int>(ceil_div(a.J, 32));
+        p.vec_in = aligned16(a.W) && (a.ldw * 2) % 16 == 0;
+        p.vec_perm = a.best_perm && aligned16(a.best_perm);
+        p.stream_out = static_cast<size_t>(a.I) * a.J > kL2Keep;
+        g.first[g.n] = blocks;
+        blocks += static_cast<unsigned>(p.units);
+        if (++g.n == kGroupMax)
+            if (int rc = flush()) return rc;
+    }
+    return flush();
 }
 
 int launch_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,

@@ -26,16 +26,16 @@ template <int M> struct Planes { static constexpr int L = M == 4 ? 3 : (M == 8 ?
 // flight at once.  N2OF4: the 2:4 case, where "more than two of four" is a 7-operation
 // boolean formula instead of a bit-sliced adder.
 template <int M, bool VEC, int CHL, int U, bool N2OF4>
-__global__ void __launch_bounds__(kThreads)
-k_perm_score(const uint32_t* __restrict__ B_bits, int I, int64_t J, int wpr32,
-             const int32_t* __restrict__ perms, int K, int N, int nseg, int sps, int64_t items,
-             int32_t* __restrict__ partial) {
+__device__ __forceinline__ void
+perm_score_body(const uint32_t* __restrict__ B_bits, int I, int64_t J, int wpr32,
+                const int32_t* __restrict__ perms, int K, int N, int nseg, int sps, int64_t items,
+                int32_t* __restrict__ partial, unsigned block, unsigned grid) {
     constexpr int L = Planes<M>::L;
     constexpr int BPS = 64 / CHL;                        // row blocks per load instruction
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // workgroup ids go round-robin over the 8 XCDs: XCD x takes a contiguous range of items
-    const int64_t per_xcd = gridDim.x / 8;
-    const int64_t item = ((blockIdx.x % 8) * per_xcd + blockIdx.x / 8) * (kThreads / 64) + wave;
+    const int64_t per_xcd = grid / 8;
+    const int64_t item = ((block % 8) * per_xcd + block / 8) * (kThreads / 64) + wave;
     if (item >= items) return;
     const int seg = static_cast<int>(item % nseg);
     const int64_t sc = item / nseg;
@@ -132,14 +132,47 @@ k_perm_score(const uint32_t* __restrict__ B_bits, int I, int64_t J, int wpr32,
     if (lane == 0) partial[(static_cast<int64_t>(slice) * nseg + seg) * K + c] = acc;
 }
 
+template <int M, bool VEC, int CHL, int U, bool N2OF4>
+__global__ void __launch_bounds__(kThreads)
+k_perm_score(const uint32_t* __restrict__ B_bits, int I, int64_t J, int wpr32,
+             const int32_t* __restrict__ perms, int K, int N, int nseg, int sps, int64_t items,
+             int32_t* __restrict__ partial) {
+    perm_score_body<M, VEC, CHL, U, N2OF4>(B_bits, I, J, wpr32, perms, K, N, nseg, sps, items, partial, blockIdx.x, gridDim.x);
+}
+
+// Grouped launch: the searches of several independent layers in one grid (first[l] = first
+// workgroup of layer l, a multiple of 8 so that the XCD assignment of a layer's items holds).
+constexpr int kGroupMax = 20;
+struct ScoreGroupP {
+    const uint32_t* B_bits;
+    const int32_t* perms;
+    int32_t* partial;
+    int64_t J, items;
+    int I, wpr32, nseg, sps;
+};
+struct ScoreGroup {
+    int n;
+    unsigned first[kGroupMax + 1];
+    ScoreGroupP p[kGroupMax];
+};
+template <int M, bool VEC, int CHL, int U, bool N2OF4>
+__global__ void __launch_bounds__(kThreads)
+k_perm_score_group(const ScoreGroup g, int K, int N) {
+    int l = 0;
+    while (l + 1 < g.n && blockIdx.x >= g.first[l + 1]) ++l;
+    const ScoreGroupP& p = g.p[l];
+    perm_score_body<M, VEC, CHL, U, N2OF4>(p.B_bits, p.I, p.J, p.wpr32, p.perms, K, N, p.nseg, p.sps, p.items, p.partial,
+                                           blockIdx.x - g.first[l], g.first[l + 1] - g.first[l]);
+}
+
 // Sums the per-tile partial scores, takes the first arg-max and copies the winner.
 // One workgroup of 1024 threads: 128 candidates x 8 tile groups at a time, so every
 // thread issues its few independent loads at once instead of walking all tiles serially.
 constexpr int kFinalThreads = 1024;
-__global__ void __launch_bounds__(kFinalThreads)
-k_perm_final(const int32_t* __restrict__ partial, int ntiles, int K, int64_t I,
-             const int32_t* __restrict__ perms, int32_t* __restrict__ scores,
-             int32_t* __restrict__ best, int32_t* __restrict__ best_perm) {
+__device__ __forceinline__ void
+perm_final_body(const int32_t* __restrict__ partial, int ntiles, int K, int64_t I,
+                const int32_t* __restrict__ perms, int32_t* __restrict__ scores,
+                int32_t* __restrict__ best, int32_t* __restrict__ best_perm) {
     __shared__ int psum[8][128];
     __shared__ long long red[128];
     const int cl = threadIdx.x & 127, part = threadIdx.x >> 7;
@@ -187,6 +220,32 @@ k_perm_final(const int32_t* __restrict__ partial, int ntiles, int K, int64_t I,
     }
 }
 
+__global__ void __launch_bounds__(kFinalThreads)
+k_perm_final(const int32_t* __restrict__ partial, int ntiles, int K, int64_t I,
+             const int32_t* __restrict__ perms, int32_t* __restrict__ scores,
+             int32_t* __restrict__ best, int32_t* __restrict__ best_perm) {
+    perm_final_body(partial, ntiles, K, I, perms, scores, best, best_perm);
+}
+
+struct FinalGroupP {
+    const int32_t* partial;
+    const int32_t* perms;
+    int32_t* scores;
+    int32_t* best;
+    int32_t* best_perm;
+    int64_t I;
+    int ntiles;
+};
+struct FinalGroup {
+    FinalGroupP p[kGroupMax];
+};
+// one workgroup per layer
+__global__ void __launch_bounds__(kFinalThreads)
+k_perm_final_group(const FinalGroup g, int K) {
+    const FinalGroupP& p = g.p[blockIdx.x];
+    perm_final_body(p.partial, p.ntiles, K, p.I, p.perms, p.scores, p.best, p.best_perm);
+}
+
 template <int M>
 int run_score(const uint32_t* B_bits, int64_t I, int64_t J, int N, const int32_t* perms, int K,
               const PermPlan& pl, int32_t* partial, hipStream_t s) {
@@ -228,6 +287,80 @@ PermPlan plan_perm_search(int64_t I, int64_t J, int K, int M) {
     pl.ntiles = pl.nslices * pl.nseg;
     pl.ws_bytes = static_cast<size_t>(pl.ntiles) * K * sizeof(int32_t);
     return pl;
+}
+
+namespace {
+
+// score kernels of the layers that share one instantiation (row alignment, slice width)
+template <int M>
+int run_score_group(const bimask_group_layer* L, const int* which, int cnt, int N, int K, bool vec, int chunks,
+                    hipStream_t s) {
+    constexpr int U = M == 16 ? 1 : 2;
+    ScoreGroup g{};
+    g.n = cnt;
+    unsigned blocks = 0;
+    for (int l = 0; l < cnt; ++l) {
+        const bimask_group_layer& a = L[which[l]];
+        const PermPlan pl = plan_perm_search(a.I, a.J, K, M);
+        ScoreGroupP& p = g.p[l];
+        p.B_bits = a.B_bits; p.perms = a.perms; p.partial = static_cast<int32_t*>(a.workspace);
+        p.J = a.J; p.I = static_cast<int>(a.I);
+        p.wpr32 = static_cast<int>(ceil_div(a.J, 32));
+        p.nseg = pl.nseg; p.sps = pl.sps;
+        p.items = static_cast<int64_t>(pl.ntiles) * K;
+        g.first[l] = blocks;
+        blocks += static_cast<unsigned>(round_up(ceil_div(p.items, kThreads / 64), 8));
+    }
+    g.first[cnt] = blocks;
+#define BIMASK_SCOREG(VEC, CHL)                                                                              \
+    {                                                                                                        \
+        if (M == 4 && N == 2)                                                                                \
+            hipLaunchKernelGGL((k_perm_score_group<M, VEC, CHL, U, M == 4>), dim3(blocks), dim3(kThreads), 0, s, g, K, N); \
+        else                                                                                                 \
+            hipLaunchKernelGGL((k_perm_score_group<M, VEC, CHL, U, false>), dim3(blocks), dim3(kThreads), 0, s, g, K, N);  \
+    }
+    if (chunks == 32) { if (vec) BIMASK_SCOREG(true, 32) else BIMASK_SCOREG(false, 32) }
+    else              { if (vec) BIMASK_SCOREG(true, 8)  else BIMASK_SCOREG(false, 8) }
+#undef BIMASK_SCOREG
+    return check_launch();
+}
+
+}  // namespace
+
+// The searches of n independent layers (same N:M and number of candidates) in a few launches:
+// one scoring launch per kernel instantiation in use, one finalising launch with a workgroup
+// per layer.  Same results as n calls of launch_perm_search.
+int launch_perm_search_group(const bimask_group_layer* L, int n, int N, int M, int K, hipStream_t s) {
+    for (int b = 0; b < n; b += kGroupMax) {
+        const int m = n - b < kGroupMax ? n - b : kGroupMax;
+        for (int cls = 0; cls < 4; ++cls) {              // (rows 16-byte aligned?, 8 or 32 chunks per slice)
+            const bool vec = cls & 1;
+            const int chunks = (cls & 2) ? 32 : 8;
+            int which[kGroupMax], cnt = 0;
+            for (int l = 0; l < m; ++l) {
+                const bimask_group_layer& a = L[b + l];
+                const bool v = aligned16(a.B_bits) && ceil_div(a.J, 32) % 4 == 0;
+                if (v == vec && plan_perm_search(a.I, a.J, K, M).chunks == chunks) which[cnt++] = b + l;
+            }
+            if (cnt == 0) continue;
+            int rc = BIMASK_ERR_NM;
+            if (M == 4) rc = run_score_group<4>(L, which, cnt, N, K, vec, chunks, s);
+            else if (M == 8) rc = run_score_group<8>(L, which, cnt, N, K, vec, chunks, s);
+            else if (M == 16) rc = run_score_group<16>(L, which, cnt, N, K, vec, chunks, s);
+            if (rc != BIMASK_OK) return rc;
+        }
+        FinalGroup f{};
+        for (int l = 0; l < m; ++l) {
+            const bimask_group_layer& a = L[b + l];
+            FinalGroupP& p = f.p[l];
+            p.partial = static_cast<const int32_t*>(a.workspace); p.perms = a.perms; p.scores = a.scores; p.best = a.best;
+            p.best_perm = a.best_perm; p.I = a.I;
+            p.ntiles = plan_perm_search(a.I, a.J, K, M).ntiles;
+        }
+        hipLaunchKernelGGL(k_perm_final_group, dim3(static_cast<unsigned>(m)), dim3(kFinalThreads), 0, s, f, K);
+        if (int rc = check_launch()) return rc;
+    }
+    return BIMASK_OK;
 }
 
 int launch_perm_search(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perms, int K,

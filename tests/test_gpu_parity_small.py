@@ -310,3 +310,65 @@ def test_leading_dimensions_side_stream_many_candidates(I, J, T):
     assert rel_err(Ybig[:, :I].float().cpu().numpy().astype(np.float64), Y_o) <= TOL[dtype]
     assert rel_err(dXbig[:, :J].float().cpu().numpy().astype(np.float64), dX_o) <= TOL[dtype]
     assert bool((Ybig[:, I:] == 3.0).all()) and bool((dXbig[:, J:] == 3.0).all()), "output padding was written"
+
+
+GROUP_SHAPES = [(64, 148), (64, 64), (64, 576), (256, 64), (128, 1152), (512, 128), (32, 36), (8, 8), (256, 2304),
+                (1024, 256), (100, 260), (64, 4100), (2048, 512), (16, 1028), (96, 96), (384, 384), (40, 44),
+                (1000, 2048), (128, 256), (512, 256), (4096, 2048), (12, 20), (64, 256)]
+
+
+@pytest.mark.parametrize("N,M,dtype,nl", [(2, 4, synth.BF16, len(GROUP_SHAPES)), (1, 4, synth.BF16, 9), (2, 8, synth.BF16, 6),
+                                          (2, 4, synth.F32, 7), (4, 8, synth.BF16, 5)])
+def test_grouped_calls_equal_per_layer_calls(N, M, dtype, nl):
+    """The grouped entry points (all layers of a network in a few launches) give bit-identical results
+    to the per-layer calls (which the tests above tie to the oracle); one layer is also checked against
+    the oracle directly.  23 layers > 20 per launch: the table is cut in two; the 4096 x 2048 layer is
+    large enough to be launched on its own inside the grouped backward call."""
+    import torch
+    K = 12
+    code = bm.BF16 if dtype == synth.BF16 else bm.F32
+    tdt = torch.bfloat16 if dtype == synth.BF16 else torch.float32
+    shapes = [(-(-I // M) * M, -(-J // M) * M) for I, J in GROUP_SHAPES[:nl]]
+    entries, singles, hosts = [], [], []
+    for li, (I, J) in enumerate(shapes):
+        Wh = make_w(I, J, dtype, 3000 + li, "integers" if li % 5 == 4 else "normal")
+        perms = perms_of(I, K, 3100 + li, identity_first=(li % 2 == 0))
+        W, Pd = to_dev(Wh, dtype), i32_dev(perms)
+        hosts.append((Wh, perms))
+        # per-layer reference results
+        B, vf, xf = bm.bimask_forward_mask_compress(W, N, M)
+        scores, best, P = bm.bimask_perm_search(B, I, J, N, M, Pd)
+        Bbar, vb, xb = bm.bimask_backward_mask_compress(W, N, M, B, P)
+        singles.append((B, vf, xf, scores, best, P, Bbar, vb, xb))
+        dev = W.device
+        z = lambda t: None if t is None else torch.full_like(t, 0x55 if t.dtype == torch.int32 else 1.0)
+        ws = torch.empty((max(16, bm.workspace_bytes(bm.WS_PERM_SEARCH, I, J, 0, K, code, N, M)),), dtype=torch.uint8, device=dev)
+        entries.append(dict(W=W, B_bits=z(B), Wf_values=z(vf), Wf_index=z(xf), perms=Pd, scores=z(scores), best=z(best),
+                            best_perm=z(P), workspace=ws, Bbar_bits=z(Bbar), Wb_values=z(vb), Wb_index=z(xb)))
+    layers = bm.group_layers(entries)
+    bm.bimask_forward_mask_compress_group(layers, code, N, M)
+    bm.bimask_perm_search_group(layers, N, M, K)
+    bm.bimask_backward_mask_compress_group(layers, code, N, M)
+    torch.cuda.synchronize()
+    names = ("B_bits", "Wf_values", "Wf_index", "scores", "best", "best_perm", "Bbar_bits", "Wb_values", "Wb_index")
+    for li, (e, ref) in enumerate(zip(entries, singles)):
+        for name, r in zip(names, ref):
+            if r is None:
+                continue
+            got = e[name]
+            a = got.view(torch.int16) if got.dtype == torch.bfloat16 else (got.view(torch.int32) if got.dtype == torch.float32 else got)
+            b = r.view(torch.int16) if r.dtype == torch.bfloat16 else (r.view(torch.int32) if r.dtype == torch.float32 else r)
+            assert torch.equal(a, b), f"layer {li} {shapes[li]}: {name}"
+    # one layer straight against the oracle
+    li = 2
+    I, J = shapes[li]
+    Wh, perms = hosts[li]
+    W64 = synth.to_f64(Wh, dtype)
+    B_o = oracle.forward_mask(W64, N, M)
+    assert (words(entries[li]["B_bits"]) == oracle.pack_bits(B_o)).all()
+    sc_o = oracle.perm_scores(B_o, perms, N, M)
+    assert (entries[li]["scores"].cpu().numpy().astype(np.int64) == sc_o).all()
+    best_o = oracle.argmax_first(sc_o)
+    assert int(entries[li]["best"].item()) == best_o
+    Bbar_o, _ = oracle.backward_mask(W64, B_o, perms[best_o], N, M)
+    assert (words(entries[li]["Bbar_bits"]) == oracle.pack_bits(Bbar_o)).all()
