@@ -49,6 +49,9 @@ def parse():
                     help="network aggregate: time every layer of the configuration and print per-stage totals")
     ap.add_argument("--grouped", action="store_true",
                     help="mask and search steps of ALL layers of the configuration through the grouped entry points")
+    ap.add_argument("--gradient-gap", action="store_true",
+                    help="diagnostic: relative gap between the approximate input gradient of Eq. (10) and the exact one of "
+                         "Eq. (5), identity vs best-of-K permutation, K = 10, 100, 1000")
     ap.add_argument("--search-table", action="store_true",
                     help="permutation search over all ResNet-50 layers for 2:4, 4:8, 1:4, 2:8, 1:16 (the shape of the paper's Table 6)")
     ap.add_argument("--delta-t", type=int, default=100,
@@ -274,6 +277,49 @@ def grouped_network(args):
                       "sum_grouped_us": round(sum(v[1] for v in res.values()), 1)}), flush=True)
 
 
+def gradient_gap(args):
+    """What the permutation is for (Sec. 3.3): g-bar(X) of Eq. (10) against g(X) = g(Y) (B .* W) of Eq. (5) on one
+    layer, for the identity and for the best of K random permutations, with the share of eligible N:M
+    blocks.  Masks, search and g-bar(X) come from the library; the exact gradient is a plain fp32 matmul."""
+    import torch
+    import paper_2302_06058_amd as bm
+    from paper_2302_06058_amd import synth
+    from helpers import to_dev, i32_dev
+    L = synth.get_config(args.config)[args.layer]
+    N, M, I, J = L.N, L.M, L.I, L.J
+    T = min(L.T, 4096)
+    W = to_dev(synth.gen_weights(L), L.dtype)
+    dY = to_dev(synth.gen_out_grad(L, T), L.dtype)
+    B = bm.bimask_forward_mask(W, N, M)
+    shifts = torch.arange(32, device=W.device, dtype=torch.int32)
+    unpack = lambda bits: ((bits.unsqueeze(-1) >> shifts) & 1).reshape(bits.shape[0], -1)[:, :J].float()
+    exact = dY.float() @ (W.float() * unpack(B))                      # Eq. (5)
+    den = float(exact.norm())
+    rows = []
+
+    def gap(P):
+        Bbar, vb, ib = bm.bimask_backward_mask_compress(W, N, M, B, P)
+        approx = bm.bimask_sparse_gemm_bwd(dY, P, vb, ib, I, J, N, M).float()
+        kept = float(unpack(Bbar).sum() / unpack(B).sum())
+        return float((approx - exact).norm()) / den, kept
+
+    g0, kept0 = gap(None)
+    ident = torch.arange(I, dtype=torch.int32, device=W.device).reshape(1, I)
+    sc0, _, _ = bm.bimask_perm_search(B, I, J, N, M, ident)
+    blocks = (I // M) * J
+    rows.append({"permutation": "identity", "eligible_block_share": round(int(sc0[0]) / blocks, 4),
+                 "kept_share_of_forward_mask": round(kept0, 4), "relative_gap": round(g0, 4)})
+    rng = np.random.default_rng([L.seed, 99])
+    for K in (10, 100, 1000):
+        perms = i32_dev(np.stack([rng.permutation(I) for _ in range(K)]).astype(np.int32))
+        scores, best, P = bm.bimask_perm_search(B, I, J, N, M, perms)
+        g, kept = gap(P)
+        rows.append({"permutation": f"best of {K}", "eligible_block_share": round(int(scores.max()) / blocks, 4),
+                     "kept_share_of_forward_mask": round(kept, 4), "relative_gap": round(g, 4)})
+    print(json.dumps({"metric": "||g-bar(X) - g(X)|| / ||g(X)||  (Eq. 10 vs Eq. 5)", "layer": L.name, "I": I, "J": J, "T": T,
+                      "nm": f"{N}:{M}", "rows": rows}), flush=True)
+
+
 def search_table(args):
     """Whole-network permutation search (forward mask given, K = 100 candidates scored and the best
     picked, per layer) for the five N:M patterns of the paper's Table 6, on the ResNet-50 layer
@@ -338,6 +384,8 @@ def main():
         return search_table(args)
     if args.grouped:
         return grouped_network(args)
+    if args.gradient_gap:
+        return gradient_gap(args)
     layer = synth.get_config(args.config)[args.layer]
     data = synth.gen_layer(layer)
     e = 2 if layer.dtype == "bf16" else 4
