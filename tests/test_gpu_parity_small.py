@@ -372,3 +372,28 @@ def test_grouped_calls_equal_per_layer_calls(N, M, dtype, nl):
     assert int(entries[li]["best"].item()) == best_o
     Bbar_o, _ = oracle.backward_mask(W64, B_o, perms[best_o], N, M)
     assert (words(entries[li]["Bbar_bits"]) == oracle.pack_bits(Bbar_o)).all()
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8)])
+def test_other_binarisation_criteria_through_the_same_calls(N, M):
+    """The criteria the paper compares for the backward mask (Sec. 4.4, "Binarization Criteria": gradient
+    magnitude, random) need no other kernel: the mask call ranks whatever matrix it is given, so the
+    criterion matrix G goes in where W went, and the stand-alone compression then packs W with that mask."""
+    dtype, I, J, T = synth.BF16, 128, 192, 70
+    Wh = make_w(I, J, dtype, 4001)
+    Gh = make_w(I, J, dtype, 4002)                    # stands for |dL/dW| (or random keys)
+    W64, G64 = synth.to_f64(Wh, dtype), synth.to_f64(Gh, dtype)
+    P_h = perms_of(I, 1, 4003)[0]
+    W, G, P = to_dev(Wh, dtype), to_dev(Gh, dtype), i32_dev(P_h)
+    B = bm.bimask_forward_mask(W, N, M)
+    B_o = oracle.forward_mask(W64, N, M)
+    Bbar = bm.bimask_backward_mask(G, N, M, B, P)
+    Bbar_o, _ = oracle.backward_mask(G64, B_o, P_h, N, M)
+    assert (words(Bbar) == oracle.pack_bits(Bbar_o)).all()
+    assert (Bbar_o <= B_o[P_h, :]).all() and (Bbar_o.reshape(I // M, M, J).sum(1) <= N).all()
+    vb, ib = bm.bimask_compress_nm(W, N, M, Bbar, P, 1)
+    r = np.random.default_rng(4004)
+    dYh = synth.store(r.standard_normal((T, I), dtype=np.float32), dtype)
+    dX = bm.bimask_sparse_gemm_bwd(to_dev(dYh, dtype), P, vb, ib, I, J, N, M)
+    dX_o = oracle.gemm_bwd(synth.to_f64(dYh, dtype), W64, Bbar_o, P_h)
+    assert rel_err(from_dev_f64(dX, dtype), dX_o) <= TOL[dtype]
