@@ -104,3 +104,42 @@ def test_product_never_imports_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"^\s*(import|from)\s+oracle\b", text, flags=re.M), f
                 assert "oracle/" not in text and "liboracle" not in text, f
+
+
+def test_grouped_calls_validate_every_layer_before_any_launch():
+    """The grouped entry points check each descriptor like the per-layer calls and launch nothing on error."""
+    fake = 0x10000
+    def layer(**kw):
+        g = bm.GroupLayer()
+        g.W, g.I, g.J, g.ldw = fake, 64, 128, 128
+        for f in ("B_bits", "Wf_values", "Wf_index", "perms", "scores", "best", "best_perm", "workspace", "Bbar_bits",
+                  "Wb_values", "Wb_index"):
+            setattr(g, f, fake)
+        g.workspace_bytes = 1 << 20
+        for k, v in kw.items():
+            setattr(g, k, v)
+        return g
+    def arr(*ls):
+        a = (bm.GroupLayer * len(ls))(*ls)
+        return ctypes.cast(a, ctypes.c_void_p), a
+    L = bm.lib()
+    p, keep = arr(layer(), layer())
+    assert L.bimask_forward_mask_compress_group(None, 2, bm.BF16, 2, 4, None) == 1
+    assert L.bimask_forward_mask_compress_group(p, 0, bm.BF16, 2, 4, None) == 2
+    assert L.bimask_forward_mask_compress_group(p, 2, bm.BF16, 2, 5, None) == 3
+    assert L.bimask_forward_mask_compress_group(p, 2, 9, 2, 4, None) == 4
+    p, keep = arr(layer(), layer(J=130, ldw=130))                   # second layer: J % M
+    assert L.bimask_forward_mask_compress_group(p, 2, bm.BF16, 2, 4, None) == 2
+    p, keep = arr(layer(), layer(Wf_index=None))
+    assert L.bimask_forward_mask_compress_group(p, 2, bm.BF16, 2, 4, None) == 1
+    p, keep = arr(layer(workspace_bytes=8))
+    assert L.bimask_perm_search_group(p, 1, 2, 4, 100, None) == 6
+    p, keep = arr(layer(perms=0x10004))
+    assert L.bimask_perm_search_group(p, 1, 2, 4, 100, None) == 7
+    p, keep = arr(layer(scores=None))
+    assert L.bimask_perm_search_group(p, 1, 2, 4, 100, None) == 1
+    assert L.bimask_perm_search_group(p, 1, 2, 4, 0, None) == 2
+    p, keep = arr(layer(), layer(Bbar_bits=None))
+    assert L.bimask_backward_mask_compress_group(p, 2, bm.BF16, 2, 4, None) == 1
+    p, keep = arr(layer(Wb_values=0x10002))
+    assert L.bimask_backward_mask_compress_group(p, 1, bm.BF16, 2, 4, None) == 7
