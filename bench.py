@@ -49,6 +49,9 @@ def parse():
                     help="network aggregate: time every layer of the configuration and print per-stage totals")
     ap.add_argument("--grouped", action="store_true",
                     help="mask and search steps of ALL layers of the configuration through the grouped entry points")
+    ap.add_argument("--network-step", action="store_true",
+                    help="one Bi-Mask step over ALL layers of the configuration end to end: grouped masks and searches, "
+                         "one GEMM call per layer and direction")
     ap.add_argument("--gradient-gap", action="store_true",
                     help="diagnostic: relative gap between the approximate input gradient of Eq. (10) and the exact one of "
                          "Eq. (5), identity vs best-of-K permutation, K = 10, 100, 1000")
@@ -277,6 +280,58 @@ def grouped_network(args):
                       "sum_grouped_us": round(sum(v[1] for v in res.values()), 1)}), flush=True)
 
 
+def network_step(args):
+    """The hot path over a whole network, end to end, the way a training step issues it: forward masks of
+    all layers (grouped), forward GEMM per layer, searches (grouped), backward masks (grouped), backward
+    GEMM per layer.  All layers' buffers are resident (one copy each: a pass moves far more than the
+    last-level cache holds).  Milliseconds per pass, with and without the search."""
+    import torch
+    import paper_2302_06058_amd as bm
+    from paper_2302_06058_amd import synth
+    layers = synth.get_config(args.config)
+    runs = [LayerRun(L, synth.gen_layer(L), 1) for L in layers]
+    groups = {}
+    for r in runs:
+        L = r.layer
+        groups.setdefault((L.N, L.M, r.dt, L.K), []).append(r)
+    garr = {}
+    for key, rs in groups.items():
+        garr[key] = bm.group_layers([dict(W=r.W, B_bits=r.B, Wf_values=r.vf, Wf_index=r.xf, perms=r.perms, scores=r.scores,
+                                          best=r.best, best_perm=r.P, workspace=r.ws_perm, Bbar_bits=r.Bbar,
+                                          Wb_values=r.vb, Wb_index=r.xb) for r in rs])
+
+    def one_pass(search):
+        for (N, M, dt, K), arr in garr.items():
+            bm.bimask_forward_mask_compress_group(arr, dt, N, M)
+        for r in runs:
+            r.c_gemm_fwd[0]()
+        for (N, M, dt, K), arr in garr.items():
+            if search:
+                bm.bimask_perm_search_group(arr, N, M, K)
+            bm.bimask_backward_mask_compress_group(arr, dt, N, M)
+        for r in runs:
+            r.c_gemm_bwd[0]()
+
+    def timed(search):
+        for _ in range(max(2, args.warmup // 4)):
+            one_pass(search)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            one_pass(search)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    one_pass(True)
+    ms_with, ms_without = timed(True), timed(False)
+    flops = sum(2 * 2 * L.T * L.I * L.J for L in layers)
+    print(json.dumps({"metric": "Bi-Mask step over all layers of the configuration (grouped masks + searches, per-layer GEMMs)",
+                      "unit": "ms", "config": args.config, "n_layers": len(layers), "steps": args.steps,
+                      "ms_per_pass": round(ms_with, 4), "ms_per_pass_without_search": round(ms_without, 4),
+                      "ms_per_pass_search_every_delta_t": round(ms_without + (ms_with - ms_without) / args.delta_t, 4),
+                      "dense_equiv_tflops": round(flops / (ms_with * 1e-3) / 1e12, 1)}), flush=True)
+
+
 def gradient_gap(args):
     """What the permutation is for (Sec. 3.3): g-bar(X) of Eq. (10) against g(X) = g(Y) (B .* W) of Eq. (5) on one
     layer, for the identity and for the best of K random permutations, with the share of eligible N:M
@@ -400,6 +455,8 @@ def main():
         return grouped_network(args)
     if args.gradient_gap:
         return gradient_gap(args)
+    if args.network_step:
+        return network_step(args)
     layer = synth.get_config(args.config)[args.layer]
     data = synth.gen_layer(layer)
     e = 2 if layer.dtype == "bf16" else 4
