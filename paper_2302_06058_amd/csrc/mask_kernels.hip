@@ -327,7 +327,6 @@ k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_
 // Grouped launches: the workgroups of several independent layers in one grid.  The per-layer
 // arguments travel as a table in the kernel arguments; first[l] is the first workgroup of
 // layer l.  Small layers are launch-latency bound, a network has dozens of them.
-constexpr int kGroupMax = 20;
 template <typename P>
 struct GroupTable {
     int n;
@@ -377,12 +376,12 @@ template <int TC> __host__ __device__ constexpr int img_elems() { return TC / 32
 template <typename DT> __host__ __device__ constexpr int lds_stride_m2() { return kTR + 16 / (int)sizeof(typename DT::raw); }
 
 template <typename DT, int M, int TC>
-__global__ void __launch_bounds__(kThreads)
-k_backward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t ldw, int N,
-           const uint32_t* __restrict__ B_bits, const uint32_t* __restrict__ Bbar_in,
-           const int32_t* __restrict__ perm, uint32_t* __restrict__ Bbar_bits,
-           typename DT::raw* __restrict__ values, uint32_t* __restrict__ index, int mode,
-           int wpr, bool vec_in, bool vec_out) {
+__device__ __forceinline__ void
+backward_body(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t ldw, int N,
+              const uint32_t* __restrict__ B_bits, const uint32_t* __restrict__ Bbar_in,
+              const int32_t* __restrict__ perm, uint32_t* __restrict__ Bbar_bits,
+              typename DT::raw* __restrict__ values, uint32_t* __restrict__ index, int mode,
+              int wpr, bool vec_in, bool vec_out, unsigned block_x, unsigned block_y) {
     using raw = typename DT::raw;
     constexpr int PW = Pack<DT>::kWords;
     constexpr int NB = kTR / M;                         // row blocks per tile
@@ -392,8 +391,8 @@ k_backward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t
     constexpr int CPT = TC / 8;                         // 8-column chunks per tile row
     uint8_t* lds_meta = reinterpret_cast<uint8_t*>(lds_val + img_elems<TC>());  // mode 1 only: [TC][32] nibbles
 
-    const int64_t r0 = static_cast<int64_t>(blockIdx.y) * kTR;
-    const int64_t c0 = static_cast<int64_t>(blockIdx.x) * TC;
+    const int64_t r0 = static_cast<int64_t>(block_y) * kTR;
+    const int64_t c0 = static_cast<int64_t>(block_x) * TC;
     const int ch = threadIdx.x % CPT;
     const int64_t j0 = c0 + ch * 8;
 
@@ -519,6 +518,42 @@ k_backward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t
             }
         }
     }
+}
+
+template <typename DT, int M, int TC>
+__global__ void __launch_bounds__(kThreads)
+k_backward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t ldw, int N,
+           const uint32_t* __restrict__ B_bits, const uint32_t* __restrict__ Bbar_in,
+           const int32_t* __restrict__ perm, uint32_t* __restrict__ Bbar_bits,
+           typename DT::raw* __restrict__ values, uint32_t* __restrict__ index, int mode,
+           int wpr, bool vec_in, bool vec_out) {
+    backward_body<DT, M, TC>(W, I, J, ldw, N, B_bits, Bbar_in, perm, Bbar_bits, values, index, mode, wpr, vec_in, vec_out,
+                             blockIdx.x, blockIdx.y);
+}
+
+struct BwdGenGroupP {
+    const void* W;
+    const uint32_t* B_bits;
+    const int32_t* perm;
+    uint32_t* Bbar_bits;
+    void* values;
+    uint32_t* index;
+    int64_t I, J, ldw;
+    int wpr, vec_in, vec_out;
+    unsigned gx;                                        // column tiles of the layer
+};
+
+// small layers of any dtype / ratio: 128 permuted rows x 32 columns per workgroup
+template <typename DT, int M>
+__global__ void __launch_bounds__(kThreads)
+k_backward_group(const GroupTable<BwdGenGroupP> g, int N, int mode) {
+    using raw = typename DT::raw;
+    const int l = group_layer_of(g, blockIdx.x);
+    const BwdGenGroupP& p = g.p[l];
+    const unsigned local = blockIdx.x - g.first[l];
+    backward_body<DT, M, 32>(static_cast<const raw*>(p.W), p.I, p.J, p.ldw, N, p.B_bits, nullptr, p.perm, p.Bbar_bits,
+                             static_cast<raw*>(p.values), p.index, mode, p.wpr, p.vec_in != 0, p.vec_out != 0,
+                             local % p.gx, local / p.gx);
 }
 
 // ---------------------------------------------------------------------------------
@@ -918,11 +953,48 @@ int launch_forward_group(const bimask_group_layer* L, int n, int dtype, int N, i
     return BIMASK_OK;
 }
 
+namespace {
+
+// small layers on the general kernel (any dtype / ratio): 128 x 32 tiles, 20 layers per launch
+template <typename DT, int M>
+int run_backward_group_general(const bimask_group_layer* L, const int* which, int cnt, int N, int mode, hipStream_t s) {
+    using raw = typename DT::raw;
+    constexpr int TC = 32;
+    const size_t lds = mode == 1 ? static_cast<size_t>(img_elems<TC>()) * sizeof(raw) + TC * 32
+                                 : static_cast<size_t>(TC) * lds_stride_m2<DT>() * sizeof(raw);
+    for (int b = 0; b < cnt; b += kGroupMax) {
+        GroupTable<BwdGenGroupP> g{};
+        g.n = cnt - b < kGroupMax ? cnt - b : kGroupMax;
+        unsigned blocks = 0;
+        for (int l = 0; l < g.n; ++l) {
+            const bimask_group_layer& a = L[which[b + l]];
+            BwdGenGroupP& p = g.p[l];
+            p.W = a.W; p.B_bits = a.B_bits; p.perm = a.best_perm; p.Bbar_bits = a.Bbar_bits;
+            p.values = a.Wb_values; p.index = a.Wb_index;
+            p.I = a.I; p.J = a.J; p.ldw = a.ldw;
+            p.wpr = static_cast<int>(ceil_div(a.J, 32));
+            p.vec_in = aligned16(a.W) && (a.ldw * sizeof(raw)) % 16 == 0;
+            p.vec_out = mode == 2 && aligned16(a.Wb_values) && (a.I * sizeof(raw)) % 16 == 0;
+            p.gx = static_cast<unsigned>(ceil_div(a.J, TC));
+            g.first[l] = blocks;
+            blocks += p.gx * static_cast<unsigned>(ceil_div(a.I, kTR));
+        }
+        g.first[g.n] = blocks;
+        hipLaunchKernelGGL((k_backward_group<DT, M>), dim3(blocks), dim3(kThreads), lds, s, g, N, mode);
+        if (int rc = check_launch()) return rc;
+    }
+    return BIMASK_OK;
+}
+
+}  // namespace
+
 // Backward mask + transposed compressed operand of n independent layers, each with its own
-// permutation (best_perm).  Small bf16 2:4 layers share grouped launches; the others (large
-// enough to fill the chip on their own, or another dtype / ratio) are launched one by one.
+// permutation (best_perm).  Small layers share grouped launches (bf16 2:4: the wavefront-tile
+// kernel; everything else: the general kernel); layers large enough to fill the chip on their
+// own are launched one by one.
 int launch_backward_group(const bimask_group_layer* L, int n, int dtype, int N, int M, hipStream_t s) {
     const bool fastpath = dtype == BIMASK_BF16 && N == 2 && M == 4;
+    const int mode = uses_sp24(N, M) ? 1 : 2;
     GroupTable<BwdGroupP> g{};
     unsigned blocks = 0;
     auto flush = [&]() -> int {
@@ -933,12 +1005,18 @@ int launch_backward_group(const bimask_group_layer* L, int n, int dtype, int N, 
         blocks = 0;
         return check_launch();
     };
+    int general[1024], n_general = 0;
     for (int l = 0; l < n; ++l) {
         const bimask_group_layer& a = L[l];
         const int64_t row_groups = ceil_div(a.I, 128) * 4;
-        if (!fastpath || row_groups * ceil_div(a.J, 128) >= 2048) {
+        const bool big = fastpath ? row_groups * ceil_div(a.J, 128) >= 2048 : ceil_div(a.J, 128) * ceil_div(a.I, kTR) >= 256;
+        if (big || (!fastpath && n_general == 1024)) {
             if (int rc = launch_backward(a.W, a.I, a.J, a.ldw, dtype, N, M, a.B_bits, nullptr, a.best_perm, a.Bbar_bits,
                                          a.Wb_values, a.Wb_index, true, s)) return rc;
+            continue;
+        }
+        if (!fastpath) {
+            general[n_general++] = l;
             continue;
         }
         BwdGroupP& p = g.p[g.n];
@@ -956,7 +1034,22 @@ int launch_backward_group(const bimask_group_layer* L, int n, int dtype, int N, 
         if (++g.n == kGroupMax)
             if (int rc = flush()) return rc;
     }
-    return flush();
+    if (int rc = flush()) return rc;
+    if (n_general > 0) {
+#define BIMASK_BWDG(DT, MM) return run_backward_group_general<DT, MM>(L, general, n_general, N, mode, s)
+        if (dtype == BIMASK_BF16) {
+            if (M == 4) BIMASK_BWDG(BF16, 4);
+            if (M == 8) BIMASK_BWDG(BF16, 8);
+            if (M == 16) BIMASK_BWDG(BF16, 16);
+        } else {
+            if (M == 4) BIMASK_BWDG(F32, 4);
+            if (M == 8) BIMASK_BWDG(F32, 8);
+            if (M == 16) BIMASK_BWDG(F32, 16);
+        }
+#undef BIMASK_BWDG
+        return BIMASK_ERR_NM;
+    }
+    return BIMASK_OK;
 }
 
 int launch_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,

@@ -142,7 +142,6 @@ k_perm_score(const uint32_t* __restrict__ B_bits, int I, int64_t J, int wpr32,
 
 // Grouped launch: the searches of several independent layers in one grid (first[l] = first
 // workgroup of layer l, a multiple of 8 so that the XCD assignment of a layer's items holds).
-constexpr int kGroupMax = 20;
 struct ScoreGroupP {
     const uint32_t* B_bits;
     const int32_t* perms;
