@@ -128,7 +128,7 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
                 const void* Bm, int64_t T, int64_t ldb, void* C, int64_t ldc, int dtype, hipStream_t s);
 
 // workgroup tile (weight rows x tokens) of the streaming 2:4 kernel
-enum class Sp24Tile { k256x64, k128x64, k256x128 };
+enum class Sp24Tile { k256x64, k128x64, k256x128, k64x64 };
 int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
                      int64_t ldb, void* C, int64_t ldc, Sp24Tile tile, hipStream_t s);
 

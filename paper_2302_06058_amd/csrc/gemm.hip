@@ -475,7 +475,8 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
         const bool narrow = (w256 - w128) * 5 >= w256;
         // few tokens and few weight tiles: 256-row tiles would leave CUs idle
         const bool underfilled = ceil_div(Adim, 256) * ceil_div(T, 64) <= 128;
-        const Sp24Tile tile = narrow || underfilled ? Sp24Tile::k128x64 : (big ? Sp24Tile::k256x128 : Sp24Tile::k256x64);
+        const Sp24Tile tile = Adim <= 64 ? Sp24Tile::k64x64
+                            : (narrow || underfilled ? Sp24Tile::k128x64 : (big ? Sp24Tile::k256x128 : Sp24Tile::k256x64));
         return launch_gemm_sp24(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, tile, s);
     }
     return run_dense(A_values, Adim, K, Bm, T, ldb, C, ldc, s);

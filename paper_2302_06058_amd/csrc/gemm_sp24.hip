@@ -297,6 +297,7 @@ int run_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const
 //   256 x 64, 4 wavefronts, 2 stages prefetched: mid-size problems (the grid covers the chip)
 //   128 x 64, 4 wavefronts: weight dimensions that would leave 256-row tiles largely empty, or few tokens
 //   256 x 128, 8 wavefronts, 1 stage prefetched: large problems (half the weight traffic per token)
+//   64 x 64, 4 wavefronts of 32 x 32: at most 64 weight rows (no matrix work or fragment reads on padding rows)
 int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
                      int64_t ldb, void* C, int64_t ldc, Sp24Tile tile, hipStream_t s) {
     if (!aligned16(A) || !aligned16(meta)) return BIMASK_ERR_ALIGN;
@@ -304,6 +305,7 @@ int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t 
         case Sp24Tile::k256x64: return run_sp24<256, 64, 4, 1, 2, true>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
         case Sp24Tile::k128x64: return run_sp24<128, 64, 4, 1, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
         case Sp24Tile::k256x128: return run_sp24<256, 128, 8, 1, 1>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+        case Sp24Tile::k64x64: return run_sp24<64, 64, 2, 2, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
     }
     return BIMASK_ERR_UNSUPPORTED;
 }
