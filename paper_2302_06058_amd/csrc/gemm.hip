@@ -464,8 +464,15 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
     }
     if (sparse24) {
         if (K <= 512) {
-            const int rc = launch_gemm_sp24_resident(A_values, A_index, Adim, K, Bm, ldb, nullptr, T, C, ldc, s);
+            // narrow weights: wavefront-private tiles; short contractions or many weight rows: token tile
+            // resident in LDS (reused by every weight tile); otherwise (contraction 256-512, at most 512
+            // weight rows: 128 x 512 forward 30 -> 20 us) the streaming kernel below
+            int rc = launch_gemm_sp24_narrow(A_values, A_index, Adim, K, Bm, ldb, nullptr, T, C, ldc, s);
             if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
+            if (!(K >= 256 && Adim <= 512)) {
+                rc = launch_gemm_sp24_resident(A_values, A_index, Adim, K, Bm, ldb, nullptr, T, C, ldc, s);
+                if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
+            }
         }
         // large problems: 256 x 128 tiles on 8 wavefronts (half the weight traffic per token);
         // otherwise 256 x 64 tiles so that the grid still covers the chip; weight dimensions that
