@@ -464,12 +464,12 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
     }
     if (sparse24) {
         if (K <= 512) {
-            // narrow weights: wavefront-private tiles; short contractions or many weight rows: token tile
-            // resident in LDS (reused by every weight tile); otherwise (contraction 256-512, at most 512
-            // weight rows: 128 x 512 forward 30 -> 20 us) the streaming kernel below
+            // narrow weights: wavefront-private tiles; short contractions (below 256, or below 384 with more
+            // than 512 weight rows): token tile resident in LDS, reused by every weight tile; otherwise the
+            // streaming kernel below (measured per layer shape: 128 x 512 forward 30 -> 20 us, 2048 x 512 14 -> 10 us)
             int rc = launch_gemm_sp24_narrow(A_values, A_index, Adim, K, Bm, ldb, nullptr, T, C, ldc, s);
             if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
-            if (!(K >= 256 && Adim <= 512)) {
+            if (K < 256 || (K < 384 && Adim > 512)) {
                 rc = launch_gemm_sp24_resident(A_values, A_index, Adim, K, Bm, ldb, nullptr, T, C, ldc, s);
                 if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
             }
@@ -477,7 +477,7 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
         // large problems: 256 x 128 tiles on 8 wavefronts (half the weight traffic per token);
         // otherwise 256 x 64 tiles so that the grid still covers the chip; weight dimensions that
         // would leave a fifth or more of the 256-row tiles empty (384 = 1.5 tiles) take 128-row tiles
-        const bool big = ceil_div(Adim, 256) * ceil_div(T, 128) >= 512;
+        const bool big = ceil_div(Adim, 256) * ceil_div(T, 128) >= 190;
         const int64_t w256 = round_up(Adim, 256), w128 = round_up(Adim, 128);
         const bool narrow = (w256 - w128) * 5 >= w256;
         // few tokens and few weight tiles: 256-row tiles would leave CUs idle
