@@ -75,6 +75,31 @@ __device__ __forceinline__ void top2_of4_bf16(uint32_t w0, uint32_t w1, uint32_t
     p1 = 3u - min(a, b);
 }
 
+// One group of four bf16 weights (w0 = e1:e0, w1 = e3:e2): mask bits, index nibble and the two
+// slot values (packed) for 2:4 (the two largest magnitudes) or 1:4 (the largest; the other slot
+// is the lowest remaining position and carries zero).  Selector byte 0x0C of the byte-permute
+// instruction yields 0x00.
+__device__ __forceinline__ void select_compress4_bf16(uint32_t w0, uint32_t w1, int N, uint32_t& bits,
+                                                      uint32_t& nib, uint32_t& vals) {
+    if (N == 2) {
+        uint32_t p0, p1;
+        top2_of4_bf16(w0, w1, p0, p1);
+        bits = (1u << p0) | (1u << p1);
+        nib = p0 | (p1 << 2);
+        // bytes (2 p0, 2 p0 + 1, 2 p1, 2 p1 + 1) of the 8-byte group
+        vals = __builtin_amdgcn_perm(w1, w0, 0x01000100u + p0 * 0x0202u + p1 * 0x02020000u);
+    } else {
+        const uint32_t k0 = ((w0 & 0x7FFFu) << 2) | 3u;
+        const uint32_t k1 = (((w0 >> 16) & 0x7FFFu) << 2) | 2u;
+        const uint32_t k2 = ((w1 & 0x7FFFu) << 2) | 1u;
+        const uint32_t k3 = ((w1 >> 16) & 0x7FFFu) << 2;
+        const uint32_t p = 3u - (max(max(k0, k1), max(k2, k3)) & 3u);     // lowest index among equals
+        bits = 1u << p;
+        nib = p == 0 ? 4u : (p << 2);                                      // slots (0, 1) or (0, p)
+        vals = __builtin_amdgcn_perm(w1, w0, p == 0 ? 0x0C0C0100u : (0x0C0Cu | ((0x0100u + p * 0x0202u) << 16)));
+    }
+}
+
 // ---------------------------------------------------------------------------------
 // Forward direction: one thread owns CH consecutive columns of one row.
 //   MODE 0: mask only   2: + dense masked values   (2-of-4 compression: k_forward24 below)
@@ -189,7 +214,7 @@ forward24_body(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int
     // bounds checks, neighbour exchange by a DPP quad swap.  Everything else takes the guarded
     // path below.
     const bool fast = __builtin_amdgcn_readfirstlane(static_cast<int>(
-        sizeof(raw) == 2 && M == 4 && N == 2 && !mask_in && vec_in && r8 * 8 + 8 <= I && static_cast<int64_t>(st0 + U) * 128 <= J)) != 0;
+        sizeof(raw) == 2 && M == 4 && N <= 2 && !mask_in && vec_in && r8 * 8 + 8 <= I && static_cast<int64_t>(st0 + U) * 128 <= J)) != 0;
     if constexpr (sizeof(raw) == 2) {
         if (fast) {
             u32x4 t[U][2];
@@ -206,11 +231,11 @@ forward24_body(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const uint32_t w0 = t[u][g >> 1][(g & 1) * 2], w1 = t[u][g >> 1][(g & 1) * 2 + 1];
-                    uint32_t p0, p1;
-                    top2_of4_bf16(w0, w1, p0, p1);
-                    bits |= ((1u << p0) | (1u << p1)) << (4 * g);
-                    nibs |= (p0 | (p1 << 2)) << (4 * g);
-                    ov[g] = __builtin_amdgcn_perm(w1, w0, 0x01000100u + p0 * 0x0202u + p1 * 0x02020000u);
+                    uint32_t b4, n4, v2;
+                    select_compress4_bf16(w0, w1, N, b4, n4, v2);
+                    bits |= b4 << (4 * g);
+                    nibs |= n4 << (4 * g);
+                    ov[g] = v2;
                 }
                 raw* dst = values + ((((i >> 5) * ks + st) * 4 + (q & 3)) * 64 + (i & 31) + 32 * (q >> 2)) * 8;
                 if (stream_out) __builtin_nontemporal_store(ov, reinterpret_cast<u32x4*>(dst));
@@ -244,17 +269,15 @@ forward24_body(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int
         raw* dst = values + ((((i >> 5) * ks + st) * 4 + (q & 3)) * 64 + (i & 31) + 32 * (q >> 2)) * 8;
         bool done = false;
         if constexpr (sizeof(raw) == 2 && M == 4) {
-            if (!mask_in && N == 2) {                      // wave-uniform: select and compress in one go
+            if (!mask_in && N <= 2) {                      // wave-uniform: select and compress in one go
                 uint32_t ow[4];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const uint32_t w0 = w[u][g >> 1][(g & 1) * 2], w1 = w[u][g >> 1][(g & 1) * 2 + 1];
-                    uint32_t p0, p1;
-                    top2_of4_bf16(w0, w1, p0, p1);
-                    bits |= ((1u << p0) | (1u << p1)) << (4 * g);
-                    nibs |= (p0 | (p1 << 2)) << (4 * g);
-                    // bytes (2 p0, 2 p0 + 1, 2 p1, 2 p1 + 1) of the 8-byte group
-                    ow[g] = __builtin_amdgcn_perm(w1, w0, 0x01000100u + p0 * 0x0202u + p1 * 0x02020000u);
+                    uint32_t b4, n4;
+                    select_compress4_bf16(w0, w1, N, b4, n4, ow[g]);
+                    bits |= b4 << (4 * g);
+                    nibs |= n4 << (4 * g);
                 }
                 // groups at or beyond the row end (zero padding): no mask bits, index 0
                 const int64_t left = (Jr - j0) >> 2;
