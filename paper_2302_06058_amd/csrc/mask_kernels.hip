@@ -629,7 +629,7 @@ __device__ __forceinline__ void backward24_tile(
         const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t ldw, const uint32_t* __restrict__ B_bits,
         const int32_t* __restrict__ perm, uint32_t* __restrict__ Bbar_bits, uint16_t* __restrict__ values,
         uint32_t* __restrict__ index, int wpr, bool vec_in, bool vec_perm, bool stream_out, bool active,
-        int64_t r0, int c0, uint4* lds_wave, int lane) {
+        int64_t r0, int c0, uint4* lds_wave, int lane, int N) {
     const int c = lane & 7, k = lane >> 3;
     const int64_t rb = r0 + 4 * k;
     const bool row_ok = FAST || (active && rb < I);
@@ -703,11 +703,11 @@ __device__ __forceinline__ void backward24_tile(
             const uint32_t half = (q & 1) ? 0x07060302u : 0x05040100u;
             const uint32_t e01 = __builtin_amdgcn_perm(w[1][o2][j], w[0][o2][j], half);   // (row 1 : row 0)
             const uint32_t e23 = __builtin_amdgcn_perm(w[3][o2][j], w[2][o2][j], half);   // (row 3 : row 2)
-            uint32_t p0, p1;
-            top2_of4_bf16(e01, e23, p0, p1);
-            const uint32_t ow = __builtin_amdgcn_perm(e23, e01, 0x01000100u + p0 * 0x0202u + p1 * 0x02020000u);
-            nib[o2] |= (p0 | (p1 << 2)) << (4 * q);
-            R[o2] |= (1u << (8 * p0 + q)) | (1u << (8 * p1 + q));       // byte m: columns that select row m
+            uint32_t b4, n4, ow;
+            select_compress4_bf16(e01, e23, N, b4, n4, ow);              // top N of the column's 4 masked weights
+            nib[o2] |= n4 << (4 * q);
+            // byte m: columns that select row m
+            R[o2] |= ((b4 & 1u) | ((b4 & 2u) << 7) | ((b4 & 4u) << 14) | ((b4 & 8u) << 21)) << q;
             // output row = this column; slots 2kb, 2kb+1 of the stage (kb = row block in the stage)
             const int ul = ul0 + o2 * 128 + q;
             lds32[((ul ^ ((ul >> 4) & 7)) << 2) + (k & 3)] = ow;
@@ -758,7 +758,7 @@ k_backward24_bf16(const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t 
                   const uint32_t* __restrict__ B_bits, const int32_t* __restrict__ perm,
                   uint32_t* __restrict__ Bbar_bits, uint16_t* __restrict__ values,
                   uint32_t* __restrict__ index, int wpr, int64_t col_tiles, int64_t units,
-                  bool vec_in, bool vec_perm, bool stream_out) {
+                  bool vec_in, bool vec_perm, bool stream_out, int N) {
     constexpr int TC = 64 * NO;
     // per wavefront: 2*NO output row tiles x 2 instruction slots x 32 lanes x 16 bytes
     __shared__ uint4 lds[kThreads / 64][NO * 128];
@@ -772,10 +772,10 @@ k_backward24_bf16(const uint16_t* __restrict__ W, int64_t I, int64_t J, int64_t 
         static_cast<int>(active && vec_in && r0 + 32 <= I && c0 + TC <= J)) != 0;
     if (fast)
         backward24_tile<NO, true>(W, I, J, ldw, B_bits, perm, Bbar_bits, values, index, wpr, vec_in, vec_perm,
-                                  stream_out, active, r0, c0, lds[wave], lane);
+                                  stream_out, active, r0, c0, lds[wave], lane, N);
     else
         backward24_tile<NO, false>(W, I, J, ldw, B_bits, perm, Bbar_bits, values, index, wpr, vec_in, vec_perm,
-                                   stream_out, active, r0, c0, lds[wave], lane);
+                                   stream_out, active, r0, c0, lds[wave], lane, N);
 }
 
 struct BwdGroupP {
@@ -791,7 +791,7 @@ struct BwdGroupP {
 
 // small bf16 2:4 layers, one wavefront (= one 32 x 64 tile) per workgroup
 __global__ void __launch_bounds__(64)
-k_backward24_bf16_group(const GroupTable<BwdGroupP> g) {
+k_backward24_bf16_group(const GroupTable<BwdGroupP> g, int N) {
     __shared__ uint4 lds[128];
     const int l = group_layer_of(g, blockIdx.x);
     const BwdGroupP& p = g.p[l];
@@ -805,10 +805,10 @@ k_backward24_bf16_group(const GroupTable<BwdGroupP> g) {
         static_cast<int>(active && p.vec_in != 0 && r0 + 32 <= p.I && c0 + 64 <= p.J)) != 0;
     if (fast)
         backward24_tile<1, true>(p.W, p.I, p.J, p.ldw, p.B_bits, p.perm, p.Bbar_bits, p.values, p.index, p.wpr, p.vec_in != 0,
-                                 p.vec_perm != 0, p.stream_out != 0, active, r0, c0, lds, lane);
+                                 p.vec_perm != 0, p.stream_out != 0, active, r0, c0, lds, lane, N);
     else
         backward24_tile<1, false>(p.W, p.I, p.J, p.ldw, p.B_bits, p.perm, p.Bbar_bits, p.values, p.index, p.wpr, p.vec_in != 0,
-                                  p.vec_perm != 0, p.stream_out != 0, active, r0, c0, lds, lane);
+                                  p.vec_perm != 0, p.stream_out != 0, active, r0, c0, lds, lane, N);
 }
 
 template <typename DT, int M>
@@ -873,7 +873,7 @@ int run_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const 
                  const uint32_t* Bbar_in, const int32_t* perm, uint32_t* Bbar_bits, void* values,
                  uint32_t* index, int mode, hipStream_t s) {
     if constexpr (std::is_same<DT, BF16>::value && M == 4) {
-        if (mode == 1 && !Bbar_in && N == 2) {
+        if (mode == 1 && !Bbar_in && N <= 2) {
             if (!aligned16(values) || !aligned16(index)) return BIMASK_ERR_ALIGN;
             const int wpr = static_cast<int>(ceil_div(J, 32));
             const bool vec_in = aligned16(W) && (ldw * 2) % 16 == 0;
@@ -886,12 +886,12 @@ int run_backward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const 
             if (row_groups * ceil_div(J, 128) >= 2048) {
                 const int64_t ct = ceil_div(J, 128), units = row_groups * ct;
                 hipLaunchKernelGGL((k_backward24_bf16<2>), dim3(static_cast<unsigned>(ceil_div(units, 4))), dim3(kThreads),
-                                   0, s, Wp, I, J, ldw, B_bits, perm, Bbar_bits, vp, index, wpr, ct, units, vec_in, vec_perm, stream_out);
+                                   0, s, Wp, I, J, ldw, B_bits, perm, Bbar_bits, vp, index, wpr, ct, units, vec_in, vec_perm, stream_out, N);
             } else {
                 // small matrices: one wavefront per workgroup so that the tiles spread over all CUs
                 const int64_t ct = ceil_div(J, 64), units = row_groups * ct;
                 hipLaunchKernelGGL((k_backward24_bf16<1>), dim3(static_cast<unsigned>(units)), dim3(64),
-                                   0, s, Wp, I, J, ldw, B_bits, perm, Bbar_bits, vp, index, wpr, ct, units, vec_in, vec_perm, stream_out);
+                                   0, s, Wp, I, J, ldw, B_bits, perm, Bbar_bits, vp, index, wpr, ct, units, vec_in, vec_perm, stream_out, N);
             }
             return check_launch();
         }
@@ -1016,14 +1016,14 @@ int run_backward_group_general(const bimask_group_layer* L, const int* which, in
 // kernel; everything else: the general kernel); layers large enough to fill the chip on their
 // own are launched one by one.
 int launch_backward_group(const bimask_group_layer* L, int n, int dtype, int N, int M, hipStream_t s) {
-    const bool fastpath = dtype == BIMASK_BF16 && N == 2 && M == 4;
+    const bool fastpath = dtype == BIMASK_BF16 && N <= 2 && M == 4;
     const int mode = uses_sp24(N, M) ? 1 : 2;
     GroupTable<BwdGroupP> g{};
     unsigned blocks = 0;
     auto flush = [&]() -> int {
         if (g.n == 0) return BIMASK_OK;
         g.first[g.n] = blocks;
-        hipLaunchKernelGGL(k_backward24_bf16_group, dim3(blocks), dim3(64), 0, s, g);
+        hipLaunchKernelGGL(k_backward24_bf16_group, dim3(blocks), dim3(64), 0, s, g, N);
         g.n = 0;
         blocks = 0;
         return check_launch();
