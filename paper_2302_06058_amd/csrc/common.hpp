@@ -115,8 +115,9 @@ int launch_perm_search(const uint32_t* B_bits, int64_t I, int64_t J, int N, int 
                        int32_t* scores, int32_t* best, int32_t* best_perm, void* ws, hipStream_t s);
 
 // grouped variants: n independent layers, few launches (see include/bimask.h); the per-layer argument
-// tables travel in the kernel arguments, kGroupMax layers per launch
-constexpr int kGroupMax = 20;
+// tables travel in the kernel arguments (kept below 4 KB): this many layers per launch for an entry of
+// `entry_bytes` plus a 4-byte first-workgroup index
+constexpr int group_capacity(size_t entry_bytes) { return static_cast<int>((3840 - 16) / (entry_bytes + 4)); }
 int launch_forward_group(const bimask_group_layer* L, int n, int dtype, int N, int M, hipStream_t s);
 int launch_perm_search_group(const bimask_group_layer* L, int n, int N, int M, int K, hipStream_t s);
 int launch_backward_group(const bimask_group_layer* L, int n, int dtype, int N, int M, hipStream_t s);

@@ -353,8 +353,9 @@ k_forward24(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_
 template <typename P>
 struct GroupTable {
     int n;
-    unsigned first[kGroupMax + 1];
-    P p[kGroupMax];
+    static constexpr int kCap = group_capacity(sizeof(P));
+    unsigned first[kCap + 1];
+    P p[kCap];
 };
 template <typename P>
 __device__ __forceinline__ int group_layer_of(const GroupTable<P>& g, unsigned block) {
@@ -928,9 +929,10 @@ namespace {
 template <typename DT, int M>
 int run_forward_group(const bimask_group_layer* L, int n, int N, hipStream_t s) {
     using raw = typename DT::raw;
-    for (int b = 0; b < n; b += kGroupMax) {
+    constexpr int kCap = GroupTable<FwdGroupP>::kCap;
+    for (int b = 0; b < n; b += kCap) {
         GroupTable<FwdGroupP> g{};
-        g.n = n - b < kGroupMax ? n - b : kGroupMax;
+        g.n = n - b < kCap ? n - b : kCap;
         unsigned blocks = 0;
         for (int l = 0; l < g.n; ++l) {
             const bimask_group_layer& a = L[b + l];
@@ -978,16 +980,17 @@ int launch_forward_group(const bimask_group_layer* L, int n, int dtype, int N, i
 
 namespace {
 
-// small layers on the general kernel (any dtype / ratio): 128 x 32 tiles, 20 layers per launch
+// small layers on the general kernel (any dtype / ratio): 128 x 32 tiles
 template <typename DT, int M>
 int run_backward_group_general(const bimask_group_layer* L, const int* which, int cnt, int N, int mode, hipStream_t s) {
     using raw = typename DT::raw;
     constexpr int TC = 32;
     const size_t lds = mode == 1 ? static_cast<size_t>(img_elems<TC>()) * sizeof(raw) + TC * 32
                                  : static_cast<size_t>(TC) * lds_stride_m2<DT>() * sizeof(raw);
-    for (int b = 0; b < cnt; b += kGroupMax) {
+    constexpr int kCap = GroupTable<BwdGenGroupP>::kCap;
+    for (int b = 0; b < cnt; b += kCap) {
         GroupTable<BwdGenGroupP> g{};
-        g.n = cnt - b < kGroupMax ? cnt - b : kGroupMax;
+        g.n = cnt - b < kCap ? cnt - b : kCap;
         unsigned blocks = 0;
         for (int l = 0; l < g.n; ++l) {
             const bimask_group_layer& a = L[which[b + l]];
@@ -1054,7 +1057,7 @@ int launch_backward_group(const bimask_group_layer* L, int n, int dtype, int N, 
         p.stream_out = static_cast<size_t>(a.I) * a.J > kL2Keep;
         g.first[g.n] = blocks;
         blocks += static_cast<unsigned>(p.units);
-        if (++g.n == kGroupMax)
+        if (++g.n == GroupTable<BwdGroupP>::kCap)
             if (int rc = flush()) return rc;
     }
     if (int rc = flush()) return rc;

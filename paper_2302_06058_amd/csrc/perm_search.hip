@@ -149,10 +149,11 @@ struct ScoreGroupP {
     int64_t J, items;
     int I, wpr32, nseg, sps;
 };
+constexpr int kSearchGroupCap = group_capacity(sizeof(ScoreGroupP));     // 56-byte entries: 63 layers
 struct ScoreGroup {
     int n;
-    unsigned first[kGroupMax + 1];
-    ScoreGroupP p[kGroupMax];
+    unsigned first[kSearchGroupCap + 1];
+    ScoreGroupP p[kSearchGroupCap];
 };
 template <int M, bool VEC, int CHL, int U, bool N2OF4>
 __global__ void __launch_bounds__(kThreads)
@@ -236,7 +237,7 @@ struct FinalGroupP {
     int ntiles;
 };
 struct FinalGroup {
-    FinalGroupP p[kGroupMax];
+    FinalGroupP p[kSearchGroupCap];
 };
 // one workgroup per layer
 __global__ void __launch_bounds__(kFinalThreads)
@@ -330,12 +331,13 @@ int run_score_group(const bimask_group_layer* L, const int* which, int cnt, int 
 // one scoring launch per kernel instantiation in use, one finalising launch with a workgroup
 // per layer.  Same results as n calls of launch_perm_search.
 int launch_perm_search_group(const bimask_group_layer* L, int n, int N, int M, int K, hipStream_t s) {
-    for (int b = 0; b < n; b += kGroupMax) {
-        const int m = n - b < kGroupMax ? n - b : kGroupMax;
+    static_assert(sizeof(FinalGroup) <= 3840 && sizeof(ScoreGroup) <= 3840, "argument tables must fit the kernel arguments");
+    for (int b = 0; b < n; b += kSearchGroupCap) {
+        const int m = n - b < kSearchGroupCap ? n - b : kSearchGroupCap;
         for (int cls = 0; cls < 4; ++cls) {              // (rows 16-byte aligned?, 8 or 32 chunks per slice)
             const bool vec = cls & 1;
             const int chunks = (cls & 2) ? 32 : 8;
-            int which[kGroupMax], cnt = 0;
+            int which[kSearchGroupCap], cnt = 0;
             for (int l = 0; l < m; ++l) {
                 const bimask_group_layer& a = L[b + l];
                 const bool v = aligned16(a.B_bits) && ceil_div(a.J, 32) % 4 == 0;

@@ -316,6 +316,7 @@ def test_leading_dimensions_side_stream_many_candidates(I, J, T):
 GROUP_SHAPES = [(64, 148), (64, 64), (64, 576), (256, 64), (128, 1152), (512, 128), (32, 36), (8, 8), (256, 2304),
                 (1024, 256), (100, 260), (64, 4100), (2048, 512), (16, 1028), (96, 96), (384, 384), (40, 44),
                 (1000, 2048), (128, 256), (512, 256), (4096, 2048), (12, 20), (64, 256)]
+GROUP_SHAPES += [(16 + 8 * (i % 7), 24 + 12 * (i % 11)) for i in range(50)]       # 73 layers: more than one launch holds
 
 
 @pytest.mark.parametrize("N,M,dtype,nl", [(2, 4, synth.BF16, len(GROUP_SHAPES)), (1, 4, synth.BF16, 9), (2, 8, synth.BF16, 6),
@@ -323,7 +324,7 @@ GROUP_SHAPES = [(64, 148), (64, 64), (64, 576), (256, 64), (128, 1152), (512, 12
 def test_grouped_calls_equal_per_layer_calls(N, M, dtype, nl):
     """The grouped entry points (all layers of a network in a few launches) give bit-identical results
     to the per-layer calls (which the tests above tie to the oracle); one layer is also checked against
-    the oracle directly.  23 layers > 20 per launch: the table is cut in two; the 4096 x 2048 layer is
+    the oracle directly.  73 layers are more than one launch's argument table holds (35-63 entries); the 4096 x 2048 layer is
     large enough to be launched on its own inside the grouped backward call."""
     import torch
     K = 12
