@@ -28,8 +28,8 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 # scaled by the factors a plain copy of known size shows for the same counters (2.0 / 1.0);
 # see profiles/bench_config2_hbm_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
-    (2, "sparse_gemm_fwd"): int((30913 * 2.0 + 6272) * 1024),
-    (2, "sparse_gemm_bwd"): int((5861 * 2.0 + 56449) * 1024),
+    (2, "sparse_gemm_fwd"): int((30909 * 2.0 + 6272) * 1024),
+    (2, "sparse_gemm_bwd"): int((5861 * 2.0 + 56450) * 1024),
 }
 EVENT_EVERY = 4                # the dominant stage is bracketed by HIP events in one step out of this many
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
