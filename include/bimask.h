@@ -170,7 +170,10 @@ BIMASK_API int bimask_sparse_gemm_fwd(const void *X, int64_t T, int64_t ldx, con
  * weight operand given in transposed compressed form (transposed = 1); perm = NULL is Eq. (8).
  *   dY  in  T x I (lddy >= I);   dX  out  T x J (lddx >= J).
  *   workspace: bimask_workspace_bytes(BIMASK_WS_GEMM_BWD, ...) bytes (holds dY[:,P] when the
- *   gather is not fused into the GEMM; 0 = none needed).                                 */
+ *   gather is not fused into the GEMM; 0 = none needed).  bf16 with N <= 2 fuses it for
+ *   I <= 512 and for 512 < I <= 2048 with J <= min(I, 512), I and J multiples of 8; the
+ *   second range moves rows in 16-byte pieces: dY, dX 16-byte aligned, lddy, lddx
+ *   multiples of 8, else BIMASK_ERR_ALIGN.                                               */
 BIMASK_API int bimask_sparse_gemm_bwd(const void *dY, int64_t T, int64_t lddy, const int32_t *perm,
                            const void *Wb_values, const uint32_t *Wb_index, int64_t I, int64_t J,
                            int dtype, int N, int M, void *dX, int64_t lddx,

@@ -183,9 +183,12 @@ int bimask_sparse_gemm_bwd(const void* dY, int64_t T, int64_t lddy, const int32_
     const bool sp = uses_sp24(N, M);
     const void* act = dY;
     int64_t ldact = lddy;
-    if (perm && !gemm_bwd_needs_gather(I, dtype, N, M)) {
-        // short contraction: the column gather is fused into the GEMM's token-tile load
-        return launch_gemm_sp24_resident(Wb_values, Wb_index, J, I, dY, lddy, perm, T, dX, lddx, as_stream(stream));
+    if (perm && !gemm_bwd_needs_gather(I, J, dtype, N, M)) {
+        if (I <= 512)      // short contraction: the column gather is fused into the GEMM's token-tile load
+            return launch_gemm_sp24_resident(Wb_values, Wb_index, J, I, dY, lddy, perm, T, dX, lddx, as_stream(stream));
+        // longer rows of g(Y) that still fit LDS whole: gather fused as well, rows move in 16-byte pieces
+        if (!aligned16(dY) || !aligned16(dX) || lddy % 8 || lddx % 8) return BIMASK_ERR_ALIGN;
+        return launch_gemm_sp24_rowres(Wb_values, Wb_index, J, I, dY, lddy, perm, T, dX, lddx, as_stream(stream));
     }
     if (perm) {
         const size_t need = bimask_workspace_bytes(BIMASK_WS_GEMM_BWD, I, J, T, 0, dtype, N, M);
@@ -221,7 +224,7 @@ size_t bimask_workspace_bytes(int kind, int64_t I, int64_t J, int64_t T, int K, 
         case BIMASK_WS_GEMM_FWD:
             return 0;
         case BIMASK_WS_GEMM_BWD:
-            if (!gemm_bwd_needs_gather(I, dtype, N, M)) return 0;
+            if (!gemm_bwd_needs_gather(I, J, dtype, N, M)) return 0;
             return T > 0 ? static_cast<size_t>(T) * static_cast<size_t>(I) * esize(dtype) : 0;
         default:
             return 0;

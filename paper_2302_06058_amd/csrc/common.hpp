@@ -139,7 +139,13 @@ int launch_gemm_sp24_resident(const void* A, const uint32_t* meta, int64_t Adim,
 // wavefront-private variant for narrow weights (Adim <= 256 with K <= 128, Adim <= 64 with K <= 256); BIMASK_ERR_UNSUPPORTED otherwise
 int launch_gemm_sp24_narrow(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc,
                             int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, hipStream_t s);
+// backward GEMM with whole rows of g(Y) resident in LDS (512 < K <= 2048, Adim <= 512): gather fused;
+// BIMASK_ERR_UNSUPPORTED otherwise
+int launch_gemm_sp24_rowres(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc,
+                            int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, hipStream_t s);
 // true when the backward GEMM needs the gathered copy of g(Y) in the workspace
-bool gemm_bwd_needs_gather(int64_t I, int dtype, int N, int M);
+bool gemm_bwd_needs_gather(int64_t I, int64_t J, int dtype, int N, int M);
+// Shapes (output rows Adim, contraction K) the row-resident backward kernel takes.
+bool gemm_sp24_rowres_shape(int64_t Adim, int64_t K);
 
 }  // namespace bimask

@@ -446,8 +446,9 @@ int launch_gather_cols(const void* dY, int64_t T, int64_t ld, const int32_t* per
     return check_launch();
 }
 
-bool gemm_bwd_needs_gather(int64_t I, int dtype, int N, int M) {
-    return !(dtype == BIMASK_BF16 && uses_sp24(N, M) && I <= 512);
+bool gemm_bwd_needs_gather(int64_t I, int64_t J, int dtype, int N, int M) {
+    if (dtype != BIMASK_BF16 || !uses_sp24(N, M)) return true;
+    return !(I <= 512 || gemm_sp24_rowres_shape(J, I));
 }
 
 int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int64_t K, bool sparse24,

@@ -29,8 +29,11 @@ def test_status_strings():
 
 
 def test_workspace_bytes():
-    # long contractions (I > 512) gather g(Y) into the workspace, short bf16 2:4 ones fuse the gather
-    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 1024, 256, 12544, 0, bm.BF16, 2, 4) == 12544 * 1024 * 2
+    # rows of g(Y) that do not fit LDS (or wide outputs) gather into the workspace, the others fuse the gather
+    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 4096, 256, 12544, 0, bm.BF16, 2, 4) == 12544 * 4096 * 2
+    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 1024, 1024, 12544, 0, bm.BF16, 2, 4) == 12544 * 1024 * 2
+    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 1024, 256, 12544, 0, bm.BF16, 2, 4) == 0
+    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 1024, 256, 12544, 0, bm.BF16, 4, 8) == 12544 * 1024 * 2
     assert bm.workspace_bytes(bm.WS_GEMM_BWD, 256, 2304, 12544, 0, bm.BF16, 2, 4) == 0
     assert bm.workspace_bytes(bm.WS_GEMM_BWD, 256, 2304, 12544, 0, bm.BF16, 1, 4) == 0       # N <= 2: sparse cores too
     assert bm.workspace_bytes(bm.WS_GEMM_BWD, 256, 2304, 12544, 0, bm.BF16, 4, 8) == 12544 * 256 * 2
@@ -81,8 +84,9 @@ def test_workspace_bytes():
     ("bimask_sparse_gemm_fwd", (FAKE, 32, 128, FAKE, None, 64, 128, bm.BF16, 2, 4, FAKE, 64, None, 0, None), 1),
     ("bimask_sparse_gemm_fwd", (FAKE, 32, 129, FAKE, FAKE, 64, 128, bm.BF16, 2, 4, FAKE, 64, None, 0, None), 7),
     ("bimask_sparse_gemm_fwd", (FAKE, 0, 128, FAKE, FAKE, 64, 128, bm.BF16, 2, 4, FAKE, 64, None, 0, None), 2),
-    ("bimask_sparse_gemm_bwd", (FAKE, 32, 1024, FAKE, FAKE, FAKE, 1024, 128, bm.BF16, 2, 4, FAKE, 128, None, 0, None), 6),
-    ("bimask_sparse_gemm_bwd", (FAKE, 32, 1024, FAKE, FAKE, FAKE, 1024, 128, bm.BF16, 2, 4, FAKE, 128, FAKE, 16, None), 6),
+    ("bimask_sparse_gemm_bwd", (FAKE, 32, 4096, FAKE, FAKE, FAKE, 4096, 128, bm.BF16, 2, 4, FAKE, 128, None, 0, None), 6),
+    ("bimask_sparse_gemm_bwd", (FAKE, 32, 4096, FAKE, FAKE, FAKE, 4096, 128, bm.BF16, 2, 4, FAKE, 128, FAKE, 16, None), 6),
+    ("bimask_sparse_gemm_bwd", (FAKE, 32, 1028, FAKE, FAKE, FAKE, 1024, 128, bm.BF16, 2, 4, FAKE, 128, None, 0, None), 7),  # fused rows: ld % 8
     ("bimask_sparse_gemm_bwd", (FAKE, 32, 60, None, FAKE, FAKE, 64, 128, bm.BF16, 2, 4, FAKE, 128, None, 0, None), 2),
 ])
 def test_argument_errors_are_reported_before_any_launch(call, args, want):

@@ -249,9 +249,13 @@ def test_streaming_gemm_shapes(I, J, T):
     check_layer(I=I, J=J, N=2, M=4, dtype=synth.BF16, K=6, seed=800 + I + J, T=T)
 
 
-@pytest.mark.parametrize("I,J,T", [(1024, 128, 70), (640, 256, 100), (2560, 128, 70), (2100, 64, 45)])
+@pytest.mark.parametrize("I,J,T", [(1024, 128, 70), (640, 256, 100), (2560, 128, 70), (2100, 64, 45),
+                                   (1024, 256, 333), (1536, 384, 130), (2048, 512, 45), (520, 40, 77), (1152, 384, 1),
+                                   (1024, 1028, 40)])
 def test_long_contraction_backward_uses_gather_pass(I, J, T):
-    # I > 512: g(Y)[:, P] is gathered into the workspace, then the streaming kernel runs;
+    # 512 < I <= 2048 with J <= 512: whole rows of g(Y) resident in LDS, gather fused (520: ragged last
+    # stage; 333 / 130 / 77 tokens: ragged last tile; J = 1028: too wide, falls back to the gather pass).
+    # Otherwise g(Y)[:, P] is gathered into the workspace, then the streaming kernel runs;
     # I > 2048: the gather keeps its permutation entries in registers (2100: ragged last 16 bytes)
     check_layer(I=I, J=J, N=2, M=4, dtype=synth.BF16, K=4, seed=900 + I, T=T)
 
