@@ -95,6 +95,23 @@ def perm_scores(B, perms, N: int, M: int) -> np.ndarray:
     return scores
 
 
+def perm_refine(B, P, swaps, N: int, M: int):
+    """Limitations (future work): hill climbing on Sec. 3.3's objective by proposed exchanges of two
+    positions of P, each kept iff the eligible-block count grows.  Returns (P', score before,
+    score after, proposals kept)."""
+    B = _u8(B)
+    I, J = B.shape
+    _check_nm(I, J, N, M, cols_grouped=False, rows_grouped=True)
+    P = np.arange(I, dtype=np.int32) if P is None else np.array(P, dtype=np.int32, copy=True)
+    assert P.shape == (I,)
+    swaps = np.ascontiguousarray(np.asarray(swaps, dtype=np.int32).reshape(-1, 2))
+    score = np.zeros(2, dtype=np.int64)
+    acc = np.zeros(1, dtype=np.int64)
+    _load().oracle_perm_refine(_p(B), ctypes.c_int64(I), ctypes.c_int64(J), N, M, _p(P), _p(swaps),
+                               ctypes.c_int64(swaps.shape[0]), _p(score), _p(acc))
+    return P, int(score[0]), int(score[1]), int(acc[0])
+
+
 def argmax_first(scores) -> int:
     """Alg. 1: best candidate, first among equals."""
     scores = _i64(scores)

@@ -71,6 +71,37 @@ void oracle_perm_scores(const uint8_t *B, int64_t I, int64_t J, int N, int M,
     }
 }
 
+/* Refinement of a permutation (the Limitations section leaves "a better permutation than a
+ * random one" to future work; this is hill climbing on the objective Sec. 3.3 / Alg. 1 already
+ * use).  Proposal t exchanges the entries at positions a_t and b_t of P; it is kept if and
+ * only if the number of eligible blocks of the whole matrix grows strictly.  Proposals are
+ * taken one after the other, each against the permutation the earlier ones left.  A
+ * proposal naming a position outside [0, I) changes nothing.
+ * score[0] = eligible blocks before, score[1] = after; *accepted = proposals kept.
+ * Every proposal is scored by counting the whole matrix again: no shortcut. */
+void oracle_perm_refine(const uint8_t *B, int64_t I, int64_t J, int N, int M, int32_t *P,
+                        const int32_t *swaps, int64_t S, int64_t *score, int64_t *accepted)
+{
+    int64_t cur;
+    oracle_perm_scores(B, I, J, N, M, P, 1, &cur);
+    score[0] = cur;
+    *accepted = 0;
+    for (int64_t t = 0; t < S; ++t) {
+        const int64_t a = swaps[2 * t], b = swaps[2 * t + 1];
+        if (a < 0 || a >= I || b < 0 || b >= I) continue;
+        int32_t tmp = P[a]; P[a] = P[b]; P[b] = tmp;
+        int64_t cand;
+        oracle_perm_scores(B, I, J, N, M, P, 1, &cand);
+        if (cand > cur) {
+            cur = cand;
+            ++*accepted;
+        } else {
+            tmp = P[a]; P[a] = P[b]; P[b] = tmp;                /* undo */
+        }
+    }
+    score[1] = cur;
+}
+
 /* Alg. 1: the candidate with the most eligible blocks; first one among equals. */
 int oracle_argmax(const int64_t *scores, int K)
 {

@@ -454,3 +454,81 @@ def test_backward_compress_equals_generic_rule_on_bbar(N, M):
     valb, idxb = oracle.compress_bwd(W, B, P, N, M)
     val2, idx2 = oracle.compress_fwd(np.ascontiguousarray(W[P, :].T), np.ascontiguousarray(Bbar.T), N, M)
     assert (idxb == idx2).all() and (valb == val2).all()
+
+
+# ----------------------------------------------------------------------------
+# refinement of a permutation by proposed exchanges (Limitations: future work)
+# ----------------------------------------------------------------------------
+def _read_refine_case():
+    rows, swaps, exp, perm = [], [], None, None
+    for line in open(os.path.join(GOLDEN, "perm_refine_hand_case.txt")):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        v = [int(x) for x in t[1:]]
+        if t[0] == "B":
+            rows.append(v)
+        elif t[0] == "S":
+            swaps.append(v)
+        elif t[0] == "E":
+            exp = v
+        elif t[0] == "P":
+            perm = v
+    return np.array(rows, dtype=np.uint8), np.array(swaps, dtype=np.int32), exp, perm
+
+
+def test_refine_hand_case():
+    B, swaps, exp, perm = _read_refine_case()
+    P, before, after, kept = oracle.perm_refine(B, None, swaps, 2, 4)
+    assert [before, after, kept] == exp
+    assert P.tolist() == perm
+    # the order of the proposals matters: "2 7" alone is dropped
+    P1, b1, a1, k1 = oracle.perm_refine(B, None, swaps[:1], 2, 4)
+    assert (P1.tolist(), b1, a1, k1) == (list(range(8)), 3, 3, 0)
+
+
+@pytest.mark.parametrize("N,M", NMS)
+def test_refine_invariants(N, M):
+    r = rng_of(61)
+    I, J = 6 * M, 5 * M
+    B = oracle.forward_mask(r.standard_normal((I, J)), N, M)
+    P0 = r.permutation(I).astype(np.int32)
+    swaps = r.integers(0, I, size=(150, 2)).astype(np.int32)
+    P, before, after, kept = oracle.perm_refine(B, P0, swaps, N, M)
+    assert sorted(P.tolist()) == list(range(I))
+    assert before == brute_scores(B, P0[None], N, M)[0]
+    assert after == brute_scores(B, P[None], N, M)[0]
+    assert after >= before + kept and kept <= len(swaps)      # every kept proposal gains at least one block
+    assert (kept == 0) == (P.tolist() == P0.tolist())
+    # no proposals / proposals inside one block / positions that do not exist: nothing changes
+    for sw in (np.zeros((0, 2), np.int32),
+               np.array([[k * M + a, k * M + b] for k in range(I // M) for a in range(M) for b in range(M)], np.int32),
+               np.array([[-1, 0], [0, I], [I + 5, -3]], np.int32)):
+        Q, b, a, k = oracle.perm_refine(B, P0, sw, N, M)
+        assert Q.tolist() == P0.tolist() and b == a == before and k == 0
+    # the input permutation is not modified
+    assert sorted(P0.tolist()) == list(range(I))
+
+
+def test_refine_reaches_a_local_optimum_and_never_beats_the_global_one():
+    r = rng_of(62)
+    N, M, I, J = 2, 4, 8, 12
+    B = (r.random((I, J)) < 0.55).astype(np.uint8)
+    pairs = np.array([(a, b) for a in range(I) for b in range(a + 1, I)], dtype=np.int32)
+    P, before = np.arange(I, dtype=np.int32), None
+    for _ in range(20):                                        # sweeps over all exchanges until one keeps nothing
+        P, b, a, kept = oracle.perm_refine(B, P, pairs, N, M)
+        before = b if before is None else before
+        if kept == 0:
+            break
+    assert kept == 0
+    here = brute_scores(B, P[None], N, M)[0]
+    assert here == a >= before
+    for x, y in pairs:                                         # no single exchange improves it
+        Q = P.copy()
+        Q[x], Q[y] = Q[y], Q[x]
+        assert brute_scores(B, Q[None], N, M)[0] <= here
+    # all 35 ways of splitting 8 rows into two blocks of 4
+    best = max(brute_scores(B, np.array([list(c) + [i for i in range(I) if i not in c]]), N, M)[0]
+               for c in itertools.combinations(range(I), 4) if 0 in c)
+    assert here <= best
