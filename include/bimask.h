@@ -179,6 +179,24 @@ BIMASK_API int bimask_sparse_gemm_bwd(const void *dY, int64_t T, int64_t lddy, c
                            int dtype, int N, int M, void *dX, int64_t lddx,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* Refinement of a permutation by proposed exchanges.  The paper's Limitations leave "a better
+ * permutation than a random one" to future work; this is hill climbing on the objective its
+ * search already uses (Sec. 3.3 / Alg. 1: the number of (block of M permuted rows, column)
+ * pairs of B[P,:] holding at most N ones).  Proposal t exchanges P[swaps[2t]] and
+ * P[swaps[2t+1]]; it is kept iff the count grows strictly.  Proposals are taken in order,
+ * each against the permutation the earlier ones left; a proposal naming a position outside
+ * [0, I) is skipped.  The library draws no random numbers: the caller supplies the proposals.
+ *   B_bits    in   I x ceil(J/32) words (as written by bimask_forward_mask)
+ *   perm_in   in   I int32, or NULL for the identity (may be the same buffer as perm_out)
+ *   swaps     in   S x 2 int32 positions, device memory; S >= 0 (NULL allowed when S == 0)
+ *   perm_out  out  I int32
+ *   result    out  int32[2], device memory: gain in the count, number of proposals kept
+ * One workgroup keeps the permutation in LDS: I <= 32768 and a mask below 2^31 words, else
+ * BIMASK_ERR_UNSUPPORTED.  Cost per proposal: 2M mask rows, independent of I.              */
+BIMASK_API int bimask_perm_refine(const uint32_t *B_bits, int64_t I, int64_t J, int N, int M,
+                       const int32_t *perm_in, const int32_t *swaps, int64_t S,
+                       int32_t *perm_out, int32_t *result, void *stream);
+
 /* Grouped calls: the mask and search steps of n INDEPENDENT layers (all layers of a network,
  * say) in a few launches instead of 2-3 per layer.  Layers this small are bound by launch
  * latency, and Alg. 1 treats every layer separately, so a training step can issue them

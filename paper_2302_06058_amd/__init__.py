@@ -24,6 +24,7 @@ _SIGNATURES = {
     "bimask_forward_mask": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR]),
     "bimask_forward_mask_compress": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR, _PTR, _PTR]),
     "bimask_perm_search": (_INT, [_PTR, _I64, _I64, _INT, _INT, _PTR, _INT, _PTR, _PTR, _PTR, _PTR, _SZ, _PTR]),
+    "bimask_perm_refine": (_INT, [_PTR, _I64, _I64, _INT, _INT, _PTR, _PTR, _I64, _PTR, _PTR, _PTR]),
     "bimask_backward_mask": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR, _PTR, _PTR]),
     "bimask_backward_mask_compress": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR, _PTR, _PTR, _PTR, _PTR]),
     "bimask_compress_nm": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR, _INT, _PTR, _PTR, _PTR]),
@@ -201,6 +202,25 @@ def bimask_perm_search(B_bits, I: int, J: int, N: int, M: int, perms, scores=Non
                                     _ptr(best_perm), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                     _stream()))
     return scores, best, best_perm
+
+
+def bimask_perm_refine(B_bits, I: int, J: int, N: int, M: int, swaps, perm=None, perm_out=None, result=None):
+    """Hill climbing over proposed exchanges of two positions; returns (perm_out, result) with
+    result = [gain in eligible blocks, proposals kept]."""
+    import torch
+    _need_cuda(B_bits, swaps, perm, perm_out, result)
+    if swaps.dtype != torch.int32 or not swaps.is_contiguous() or swaps.dim() != 2 or swaps.shape[1] != 2:
+        raise ValueError("swaps must be a contiguous S x 2 int32 tensor")
+    if perm is not None and (perm.dtype != torch.int32 or not perm.is_contiguous() or perm.numel() != I):
+        raise ValueError("perm must be a contiguous int32 tensor of I entries")
+    if perm_out is None:
+        perm_out = _empty((I,), torch.int32, B_bits)
+    if result is None:
+        result = _empty((2,), torch.int32, B_bits)
+    _check("bimask_perm_refine",
+           lib().bimask_perm_refine(_ptr(B_bits), I, J, N, M, _ptr(perm), _ptr(swaps) if swaps.shape[0] else None,
+                                    swaps.shape[0], _ptr(perm_out), _ptr(result), _stream()))
+    return perm_out, result
 
 
 def bimask_backward_mask(W, N: int, M: int, B_bits, perm=None, Bbar_bits=None):

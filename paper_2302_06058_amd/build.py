@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbimask.so")
-SOURCES = ["api.hip", "mask_kernels.hip", "perm_search.hip", "gemm.hip", "gemm_sp24.hip", "gemm_sp24_resident.hip",
+SOURCES = ["api.hip", "mask_kernels.hip", "perm_search.hip", "perm_refine.hip", "gemm.hip", "gemm_sp24.hip", "gemm_sp24_resident.hip",
            "gemm_sp24_narrow.hip", "gemm_sp24_rowres.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",

@@ -84,6 +84,16 @@ int bimask_perm_search(const uint32_t* B_bits, int64_t I, int64_t J, int N, int 
     return launch_perm_search(B_bits, I, J, N, M, perms, K, scores, best, best_perm, workspace, as_stream(stream));
 }
 
+int bimask_perm_refine(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perm_in,
+                       const int32_t* swaps, int64_t S, int32_t* perm_out, int32_t* result, void* stream) {
+    if (!B_bits || !perm_out || !result || (S > 0 && !swaps)) return BIMASK_ERR_NULL;
+    if (int rc = check_nm(N, M)) return rc;
+    if (I <= 0 || J <= 0 || S < 0 || I % M || J % M) return BIMASK_ERR_SHAPE;
+    if (I > 0x7FFFFFFFll || J > 0x7FFFFFFFll || (I / M) * J > 0x7FFFFFFFll) return BIMASK_ERR_SHAPE;
+    if (!aligned4(perm_in) || !aligned4(swaps) || !aligned4(perm_out) || !aligned4(result)) return BIMASK_ERR_ALIGN;
+    return launch_perm_refine(B_bits, I, J, N, M, perm_in, swaps, S, perm_out, result, as_stream(stream));
+}
+
 int bimask_backward_mask(const void* W, int64_t I, int64_t J, int64_t ldw, int dtype, int N, int M,
                          const uint32_t* B_bits, const int32_t* perm, uint32_t* Bbar_bits, void* stream) {
     if (int rc = check_matrix(W, I, J, ldw, dtype, N, M)) return rc;

@@ -144,6 +144,10 @@ int launch_gemm_sp24_narrow(const void* A, const uint32_t* meta, int64_t Adim, i
 int launch_gemm_sp24_rowres(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc,
                             int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, hipStream_t s);
 // true when the backward GEMM needs the gathered copy of g(Y) in the workspace
+// Refinement of a permutation by proposed exchanges; the permutation lives in LDS.
+constexpr int64_t kRefineMaxRows = 32768;
+int launch_perm_refine(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perm_in,
+                       const int32_t* swaps, int64_t S, int32_t* perm_out, int32_t* result, hipStream_t s);
 bool gemm_bwd_needs_gather(int64_t I, int64_t J, int dtype, int N, int M);
 // Shapes (output rows Adim, contraction K) the row-resident backward kernel takes.
 bool gemm_sp24_rowres_shape(int64_t Adim, int64_t K);

@@ -68,6 +68,15 @@ def test_workspace_bytes():
     ("bimask_perm_search", (FAKE, 64, 128, 2, 4, FAKE, 4, FAKE, FAKE, None, None, 0, None), 6),
     ("bimask_perm_search", (FAKE, 64, 128, 2, 4, FAKE, 4, FAKE, FAKE, None, FAKE, 8, None), 6),
     ("bimask_perm_search", (FAKE, 64, 128, 2, 4, ctypes.c_void_p(0x1004), 4, FAKE, FAKE, None, FAKE, 1 << 20, None), 7),
+    # refinement
+    ("bimask_perm_refine", (None, 64, 128, 2, 4, None, FAKE, 10, FAKE, FAKE, None), 1),
+    ("bimask_perm_refine", (FAKE, 64, 128, 2, 4, None, None, 10, FAKE, FAKE, None), 1),
+    ("bimask_perm_refine", (FAKE, 64, 128, 2, 4, None, FAKE, 10, FAKE, None, None), 1),
+    ("bimask_perm_refine", (FAKE, 62, 128, 2, 4, None, FAKE, 10, FAKE, FAKE, None), 2),
+    ("bimask_perm_refine", (FAKE, 64, 128, 2, 4, None, FAKE, -1, FAKE, FAKE, None), 2),
+    ("bimask_perm_refine", (FAKE, 64, 128, 4, 4, None, FAKE, 10, FAKE, FAKE, None), 3),
+    ("bimask_perm_refine", (FAKE, 32772, 128, 2, 4, None, FAKE, 10, FAKE, FAKE, None), 5),
+    ("bimask_perm_refine", (FAKE, 64, 128, 2, 4, None, ctypes.c_void_p(0x1002), 10, FAKE, FAKE, None), 7),
     # backward mask
     ("bimask_backward_mask", (FAKE, 64, 128, 128, bm.F32, 2, 4, None, None, FAKE, None), 1),
     ("bimask_backward_mask", (FAKE, 64, 128, 128, bm.F32, 2, 4, FAKE, None, None, None), 1),

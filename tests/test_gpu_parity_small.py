@@ -403,3 +403,95 @@ def test_other_binarisation_criteria_through_the_same_calls(N, M):
     dX = bm.bimask_sparse_gemm_bwd(to_dev(dYh, dtype), P, vb, ib, I, J, N, M)
     dX_o = oracle.gemm_bwd(synth.to_f64(dYh, dtype), W64, Bbar_o, P_h)
     assert rel_err(from_dev_f64(dX, dtype), dX_o) <= TOL[dtype]
+
+
+# ---------------------------------------------------------------------------------------------
+# refinement of a permutation by proposed exchanges (Limitations: future work)
+# ---------------------------------------------------------------------------------------------
+def _mask_with_n_per_group(I, J, N, M, seed, density=1.0):
+    """A forward-mask-shaped 0/1 matrix: exactly N ones per group of M columns (fewer with density < 1)."""
+    rng = np.random.default_rng(seed)
+    Bo = np.zeros((I, J), dtype=np.uint8)
+    for g in range(J // M):
+        idx = np.argsort(rng.random((I, M)), axis=1)[:, :N]
+        np.put_along_axis(Bo[:, g * M:(g + 1) * M], idx, 1, axis=1)
+    if density < 1.0:
+        Bo &= (rng.random((I, J)) < density).astype(np.uint8)
+    return Bo
+
+
+def _pack_mask(Bo):
+    I, J = Bo.shape
+    wpr = (J + 31) // 32
+    bits = np.zeros((I, wpr * 32), dtype=np.uint8)
+    bits[:, :J] = Bo
+    w = (bits.reshape(I, wpr, 32).astype(np.uint64) << np.arange(32, dtype=np.uint64)).sum(axis=2).astype(np.uint32)
+    return i32_dev(w.view(np.int32))
+
+
+def _refine_both(Bo, N, M, P0, swaps):
+    I, J = Bo.shape
+    perm_dev = None if P0 is None else i32_dev(P0)
+    out, res = bm.bimask_perm_refine(_pack_mask(Bo), I, J, N, M, i32_dev(swaps), perm=perm_dev)
+    P_o, before, after, kept = oracle.perm_refine(Bo, P0, swaps, N, M)
+    got = out.cpu().numpy()
+    assert (got == P_o).all(), np.flatnonzero(got != P_o)[:8]
+    assert res.cpu().numpy().tolist() == [after - before, kept]
+    return kept, after - before
+
+
+@pytest.mark.parametrize("I,J,N,M,S", [
+    (64, 128, 2, 4, 700),        # few blocks: almost every round of 16 proposals meets a stale one
+    (256, 2304, 2, 4, 1500),     # the config-2 layer
+    (512, 100, 2, 4, 1200),      # ragged last word
+    (128, 36, 1, 4, 600),
+    (256, 4200, 4, 8, 900),      # more than 64 words per row: two passes of the lanes
+    (192, 264, 2, 8, 900),
+    (320, 208, 1, 16, 900),
+    (4096, 64, 2, 4, 2500),      # many blocks: whole rounds without a stale proposal
+])
+def test_perm_refine_equals_one_by_one_hill_climbing(I, J, N, M, S):
+    rng = np.random.default_rng(900 + I + J)
+    Bo = _mask_with_n_per_group(I, J, N, M, 901 + J)
+    swaps = rng.integers(0, I, size=(S, 2)).astype(np.int32)
+    swaps[5] = (-1, 3)                                      # positions that do not exist are skipped
+    swaps[6] = (2, I)
+    swaps[7] = (M, M + 1)                                   # inside one block: never kept
+    P0 = rng.permutation(I).astype(np.int32)
+    kept, gain = _refine_both(Bo, N, M, P0, swaps)
+    assert kept > 0 and gain >= kept
+    _refine_both(Bo, N, M, None, swaps[:40])                # NULL = identity
+
+
+def test_perm_refine_edge_cases():
+    N, M, I, J = 2, 4, 64, 64
+    Bo = _mask_with_n_per_group(I, J, N, M, 950)
+    B = _pack_mask(Bo)
+    P0 = np.random.default_rng(951).permutation(I).astype(np.int32)
+    # no proposals: a copy
+    out, res = bm.bimask_perm_refine(B, I, J, N, M, i32_dev(np.zeros((0, 2), np.int32)), perm=i32_dev(P0))
+    assert (out.cpu().numpy() == P0).all() and res.cpu().numpy().tolist() == [0, 0]
+    # in place, one proposal, and a number of proposals that is no multiple of the round or the staging chunk
+    for S in (1, 15, 17, 1023, 1025, 2050):
+        swaps = np.random.default_rng(952 + S).integers(0, I, size=(S, 2)).astype(np.int32)
+        buf = i32_dev(P0)
+        out, res = bm.bimask_perm_refine(B, I, J, N, M, i32_dev(swaps), perm=buf, perm_out=buf)
+        P_o, before, after, kept = oracle.perm_refine(Bo, P0, swaps, N, M)
+        assert (out.cpu().numpy() == P_o).all() and res.cpu().numpy().tolist() == [after - before, kept]
+    # the same proposal many times in a row: kept once at most
+    swaps = np.tile(np.array([[1, 9]], np.int32), (40, 1))
+    _refine_both(Bo, N, M, P0, swaps)
+    # an all-zero mask: every block is eligible already, nothing can grow
+    Z = np.zeros((I, J), np.uint8)
+    kept, gain = _refine_both(Z, N, M, P0, np.random.default_rng(953).integers(0, I, size=(100, 2)).astype(np.int32))
+    assert kept == 0 and gain == 0
+
+
+def test_perm_refine_largest_permutation_and_limit():
+    N, M, I, J = 2, 4, 32768, 32                           # the whole 128 KB of permutation in LDS
+    Bo = _mask_with_n_per_group(I, J, N, M, 960)
+    swaps = np.random.default_rng(961).integers(0, I, size=(200, 2)).astype(np.int32)
+    _refine_both(Bo, N, M, None, swaps)
+    with pytest.raises(bm.BimaskError) as e:
+        bm.bimask_perm_refine(_pack_mask(np.zeros((32768 + 4, 32), np.uint8)), 32768 + 4, 32, N, M, i32_dev(swaps))
+    assert e.value.status == 5
