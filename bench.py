@@ -56,6 +56,9 @@ def parse():
     ap.add_argument("--gradient-gap", action="store_true",
                     help="diagnostic: relative gap between the approximate input gradient of Eq. (10) and the exact one of "
                          "Eq. (5), identity vs best-of-K permutation, K = 10, 100, 1000")
+    ap.add_argument("--refine", action="store_true",
+                    help="diagnostic: hill-climbing refinement of the search's winner by random exchange proposals "
+                         "(time, eligible-block share, gradient gap)")
     ap.add_argument("--search-table", action="store_true",
                     help="permutation search over all ResNet-50 layers for 2:4, 4:8, 1:4, 2:8, 1:16 (the shape of the paper's Table 6)")
     ap.add_argument("--delta-t", type=int, default=100,
@@ -376,6 +379,65 @@ def gradient_gap(args):
                       "nm": f"{N}:{M}", "rows": rows}), flush=True)
 
 
+def refine_report(args):
+    """A permutation better than the best of K random ones (the paper's Limitations name it as future work): hill
+    climbing over S random exchange proposals from the search's winner, on one layer.  Reports the time of the
+    refinement call, the eligible-block share and the gap of Eq. (10)'s g-bar(X) to Eq. (5)'s g(X)."""
+    import torch
+    import paper_2302_06058_amd as bm
+    from paper_2302_06058_amd import synth
+    from helpers import to_dev, i32_dev
+    L = synth.get_config(args.config)[args.layer]
+    N, M, I, J = L.N, L.M, L.I, L.J
+    T = min(L.T, 4096)
+    W = to_dev(synth.gen_weights(L), L.dtype)
+    dY = to_dev(synth.gen_out_grad(L, T), L.dtype)
+    B = bm.bimask_forward_mask(W, N, M)
+    shifts = torch.arange(32, device=W.device, dtype=torch.int32)
+    unpack = lambda bits: ((bits.unsqueeze(-1) >> shifts) & 1).reshape(bits.shape[0], -1)[:, :J].float()
+    exact = dY.float() @ (W.float() * unpack(B))                      # Eq. (5)
+    den = float(exact.norm())
+    blocks = (I // M) * J
+
+    def gap(P):
+        Bbar, vb, ib = bm.bimask_backward_mask_compress(W, N, M, B, P)
+        approx = bm.bimask_sparse_gemm_bwd(dY, P, vb, ib, I, J, N, M).float()
+        return float((approx - exact).norm()) / den, float(unpack(Bbar).sum() / unpack(B).sum())
+
+    rng = np.random.default_rng([L.seed, 99])
+    perms = i32_dev(np.stack([rng.permutation(I) for _ in range(L.K)]).astype(np.int32))
+    scores, best, P = bm.bimask_perm_search(B, I, J, N, M, perms)
+    start = int(scores.max())
+    g, kept = gap(P)
+    rows = [{"proposals": 0, "us": 0.0, "kept": 0, "eligible_block_share": round(start / blocks, 4),
+             "kept_share_of_forward_mask": round(kept, 4), "relative_gap": round(g, 4)}]
+    out = torch.empty_like(P)
+    res = torch.empty((2,), dtype=torch.int32, device=W.device)
+    for mult in (1, 4, 16, 64):
+        S = mult * I
+        swaps = i32_dev(rng.integers(0, I, size=(S, 2)).astype(np.int32))
+        call = bm.prepare("bimask_perm_refine", B, I, J, N, M, P, swaps, S, out, res,
+                          torch.cuda.current_stream().cuda_stream)
+        for _ in range(2):
+            call()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(args.steps):
+            call()
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / args.steps
+        g, kept = gap(out)
+        r = res.cpu().numpy()
+        rows.append({"proposals": S, "us": round(us, 1), "proposals_per_us": round(S / us, 2), "kept": int(r[1]),
+                     "eligible_block_share": round((start + int(r[0])) / blocks, 4),
+                     "kept_share_of_forward_mask": round(kept, 4), "relative_gap": round(g, 4)})
+    print(json.dumps({"metric": "refinement of the best of K = %d random permutations by S random exchange proposals" % L.K,
+                      "layer": L.name, "I": I, "J": J, "T": T, "nm": f"{N}:{M}", "steps": args.steps, "rows": rows}),
+          flush=True)
+
+
 def search_table(args):
     """Whole-network permutation search (forward mask given, K = 100 candidates scored and the best
     picked, per layer) for the five N:M patterns of the paper's Table 6, on the ResNet-50 layer
@@ -456,6 +518,8 @@ def main():
         return grouped_network(args)
     if args.gradient_gap:
         return gradient_gap(args)
+    if args.refine:
+        return refine_report(args)
     if args.network_step:
         return network_step(args)
     layer = synth.get_config(args.config)[args.layer]

@@ -5,9 +5,9 @@
 // permutation the earlier ones left.
 //
 // An exchange between blocks A and B of M permuted rows changes the count of those two blocks
-// only, so a proposal costs 2M mask rows, not the matrix.  One workgroup of 16 wavefronts owns
-// the permutation (in LDS).  Each round, wavefront w evaluates proposal base + w against the
-// current permutation: lanes stride over the 32-column words of the 2M rows, add the M - 1
+// only, so a proposal costs 2M mask rows, not the matrix.  One workgroup of 8 wavefronts owns
+// the permutation (in LDS).  Each round, wavefront w evaluates up to 8 proposals (base + 8w ..)
+// against the current permutation: lanes stride over the 32-column words of the 2M rows, add the M - 1
 // unchanged rows of each block bit-sliced, add either exchanged row on top, compare with N and
 // pop-count the four eligibility words; a wavefront reduction gives the change of the count.
 // Then every wavefront walks the round's results in proposal order: a proposal that shares a block
@@ -23,7 +23,7 @@
 namespace bimask {
 namespace {
 
-constexpr int kRefineThreads = 1024;
+constexpr int kRefineThreads = 512;
 constexpr int kRefineWaves = kRefineThreads / 64;
 constexpr int kRefineChunk = 1024;                       // proposals staged in LDS at a time
 
@@ -57,6 +57,13 @@ __device__ __forceinline__ uint32_t at_most(const uint32_t (&c)[L], uint32_t w, 
     return ~gt;
 }
 
+// PPW proposals per wavefront and round, all their loads in flight together: 8 for M = 4, 4 for
+// M = 8, 2 for M = 16 keeps the kernel within the 256 registers a 512-thread workgroup leaves per lane.
+template <int M> struct RefineShape {
+    static constexpr int PPW = M == 4 ? 8 : (M == 8 ? 4 : 2);
+    static constexpr int ROUND = kRefineWaves * PPW;     // proposals per round, at most 64
+};
+
 template <int M>
 __global__ void __launch_bounds__(kRefineThreads)
 k_perm_refine(const uint32_t* __restrict__ Bm, int I, int words, int N, const int32_t* __restrict__ perm_in,
@@ -64,9 +71,10 @@ k_perm_refine(const uint32_t* __restrict__ Bm, int I, int words, int N, const in
               int32_t* __restrict__ result) {
     constexpr int L = RefinePlanes<M>::L;
     constexpr int SH = M == 4 ? 2 : (M == 8 ? 3 : 4);
+    constexpr int PPW = RefineShape<M>::PPW, ROUND = RefineShape<M>::ROUND;
     extern __shared__ int32_t sP[];                      // the permutation, I entries
     __shared__ int32_t sSw[2 * kRefineChunk];
-    __shared__ int sDelta[kRefineWaves], sKa[kRefineWaves], sKb[kRefineWaves], sPa[kRefineWaves], sPb[kRefineWaves];
+    __shared__ int sDelta[ROUND], sKa[ROUND], sKb[ROUND], sPa[ROUND], sPb[ROUND];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
     for (int r = tid; r < I; r += kRefineThreads) sP[r] = perm_in ? perm_in[r] : r;
@@ -74,54 +82,83 @@ k_perm_refine(const uint32_t* __restrict__ Bm, int I, int words, int N, const in
     int gain = 0, kept = 0;
     int64_t base = 0, chunk0 = 0, chunk1 = 0;            // staged proposals: [chunk0, chunk1)
     while (base < S) {                                   // uniform over the workgroup
-        if (base + kRefineWaves > chunk1 && chunk1 < S) {
+        if (base + ROUND > chunk1 && chunk1 < S) {
             __syncthreads();                             // everyone is done with the old chunk
             chunk0 = base;
             chunk1 = base + kRefineChunk < S ? base + kRefineChunk : S;
             for (int64_t e = tid; e < 2 * (chunk1 - chunk0); e += kRefineThreads) sSw[e] = swaps[2 * chunk0 + e];
         }
         __syncthreads();                                 // permutation and proposals are in place
-        const int nb = S - base < kRefineWaves ? static_cast<int>(S - base) : kRefineWaves;
-        if (wave < nb) {
-            const int a = sSw[2 * (base - chunk0 + wave)], b = sSw[2 * (base - chunk0 + wave) + 1];
-            const bool valid = a >= 0 && a < I && b >= 0 && b < I;
-            int ka = valid ? a >> SH : -1, kb = valid ? b >> SH : -1;
-            int d = 0;
-            if (valid && ka != kb) {
+        const int nb = S - base < ROUND ? static_cast<int>(S - base) : ROUND;
+        if (wave * PPW < nb) {
+            // proposals wave * PPW + p; one that changes nothing (outside [0, I), both positions in one
+            // block, beyond the round) is evaluated on positions 0 and 0 and its result dropped
+            int a[PPW], b[PPW], ka[PPW], kb[PPW], d[PPW];
+            bool live[PPW];
+            uint32_t ra[PPW][M], rb[PPW][M];
+#pragma unroll
+            for (int p = 0; p < PPW; ++p) {
+                const int q = wave * PPW + p;
+                const int e = q < nb ? static_cast<int>(base - chunk0) + q : static_cast<int>(base - chunk0);
+                a[p] = sSw[2 * e];
+                b[p] = sSw[2 * e + 1];
+                const bool valid = q < nb && a[p] >= 0 && a[p] < I && b[p] >= 0 && b[p] < I;
+                live[p] = valid && (a[p] >> SH) != (b[p] >> SH);
+                const int ac = live[p] ? a[p] : 0, bc = live[p] ? b[p] : 0;
+                ka[p] = ac >> SH;
+                kb[p] = bc >> SH;
                 // word offsets of the rows: I * words < 2^31 is checked on the host
-                const uint32_t rowa = static_cast<uint32_t>(sP[a]) * words, rowb = static_cast<uint32_t>(sP[b]) * words;
-                uint32_t ra[M], rb[M];
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
-                    ra[m] = static_cast<uint32_t>(sP[ka * M + m]) * words;
-                    rb[m] = static_cast<uint32_t>(sP[kb * M + m]) * words;
+                    ra[p][m] = static_cast<uint32_t>(sP[ka[p] * M + m]) * words;
+                    rb[p][m] = static_cast<uint32_t>(sP[kb[p] * M + m]) * words;
                 }
-                const int ma = a & (M - 1), mb = b & (M - 1);
-                for (int w = lane; w < words; w += 64) {
-                    const uint32_t wa = Bm[rowa + w], wb = Bm[rowb + w];
-                    uint32_t cA[L], cB[L];
+                d[p] = 0;
+            }
+            for (int w0 = 0; w0 < words; w0 += 64) {     // uniform trip count
+                const bool in = w0 + lane < words;
+                const uint32_t w = in ? w0 + lane : 0;
+                // all loads of the round first, then the arithmetic: a round costs one memory round trip
+                uint32_t xa[PPW][M], xb[PPW][M];
+#pragma unroll
+                for (int p = 0; p < PPW; ++p) {
+#pragma unroll
+                    for (int m = 0; m < M; ++m) {
+                        xa[p][m] = Bm[ra[p][m] + w];
+                        xb[p][m] = Bm[rb[p][m] + w];
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int p = 0; p < PPW; ++p) {
+                    const int ma = a[p] & (M - 1), mb = b[p] & (M - 1);
+                    uint32_t cA[L], cB[L], wa = 0u, wb = 0u;   // wa, wb: the two exchanged rows
 #pragma unroll
                     for (int k = 0; k < L; ++k) cA[k] = cB[k] = 0u;
 #pragma unroll
                     for (int m = 0; m < M; ++m) {
-                        const uint32_t xa = Bm[ra[m] + w], xb = Bm[rb[m] + w];
-                        add_word<L>(cA, m == ma ? 0u : xa);
-                        add_word<L>(cB, m == mb ? 0u : xb);
+                        add_word<L>(cA, m == ma ? 0u : xa[p][m]);
+                        add_word<L>(cB, m == mb ? 0u : xb[p][m]);
+                        wa |= m == ma ? xa[p][m] : 0u;
+                        wb |= m == mb ? xb[p][m] : 0u;
                     }
-                    d += __popc(at_most<L>(cA, wb, N)) + __popc(at_most<L>(cB, wa, N))
-                       - __popc(at_most<L>(cA, wa, N)) - __popc(at_most<L>(cB, wb, N));
+                    const int dd = __popc(at_most<L>(cA, wb, N)) + __popc(at_most<L>(cB, wa, N))
+                                 - __popc(at_most<L>(cA, wa, N)) - __popc(at_most<L>(cB, wb, N));
+                    d[p] += in ? dd : 0;
                 }
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) d += __shfl_xor(d, off, 64);
-            } else {
-                ka = kb = -1;                            // changes nothing: never in anyone's way
             }
-            if (lane == 0) {
-                sDelta[wave] = d;
-                sKa[wave] = ka;
-                sKb[wave] = kb;
-                sPa[wave] = a;
-                sPb[wave] = b;
+#pragma unroll
+            for (int p = 0; p < PPW; ++p) {
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) d[p] += __shfl_xor(d[p], off, 64);
+                const int q = wave * PPW + p;
+                if (lane == 0 && q < nb) {
+                    sDelta[q] = live[p] ? d[p] : 0;
+                    sKa[q] = live[p] ? ka[p] : -1;       // changes nothing: never in anyone's way
+                    sKb[q] = live[p] ? kb[p] : -1;
+                    sPa[q] = a[p];
+                    sPb[q] = b[p];
+                }
             }
         }
         __syncthreads();
@@ -130,25 +167,25 @@ k_perm_refine(const uint32_t* __restrict__ Bm, int I, int words, int N, const in
         const int kaL = lane < nb ? sKa[lane] : -1;
         const int kbL = lane < nb ? sKb[lane] : -1;
         int stop = nb;
-        uint32_t keep = 0u;
+        uint64_t keep = 0u;
         for (int i = 0; i < nb; ++i) {
             const int ka = __builtin_amdgcn_readlane(kaL, i), kb = __builtin_amdgcn_readlane(kbL, i);
             bool stale = false;
             if (ka >= 0)
-                for (uint32_t k = keep; k; k &= k - 1) {
-                    const int j = __builtin_ctz(k);
+                for (uint64_t k = keep; k; k &= k - 1) {
+                    const int j = __builtin_ctzll(k);
                     const int ja = __builtin_amdgcn_readlane(kaL, j), jb = __builtin_amdgcn_readlane(kbL, j);
                     stale |= ka == ja || ka == jb || kb == ja || kb == jb;
                 }
             if (stale) { stop = i; break; }
             const int d = __builtin_amdgcn_readlane(dL, i);
             if (d > 0) {
-                keep |= 1u << i;
+                keep |= 1ull << i;
                 gain += d;
                 ++kept;
             }
         }
-        if (wave == 0 && lane < nb && ((keep >> lane) & 1u)) {   // disjoint blocks: disjoint positions
+        if (wave == 0 && lane < nb && ((keep >> lane) & 1ull)) {   // disjoint blocks: disjoint positions
             const int a = sPa[lane], b = sPb[lane];
             const int32_t t = sP[a];
             sP[a] = sP[b];

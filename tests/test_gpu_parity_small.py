@@ -472,7 +472,7 @@ def test_perm_refine_edge_cases():
     out, res = bm.bimask_perm_refine(B, I, J, N, M, i32_dev(np.zeros((0, 2), np.int32)), perm=i32_dev(P0))
     assert (out.cpu().numpy() == P0).all() and res.cpu().numpy().tolist() == [0, 0]
     # in place, one proposal, and a number of proposals that is no multiple of the round or the staging chunk
-    for S in (1, 15, 17, 1023, 1025, 2050):
+    for S in (1, 15, 17, 63, 65, 129, 1023, 1025, 2050):
         swaps = np.random.default_rng(952 + S).integers(0, I, size=(S, 2)).astype(np.int32)
         buf = i32_dev(P0)
         out, res = bm.bimask_perm_refine(B, I, J, N, M, i32_dev(swaps), perm=buf, perm_out=buf)
