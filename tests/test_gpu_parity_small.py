@@ -495,3 +495,76 @@ def test_perm_refine_largest_permutation_and_limit():
     with pytest.raises(bm.BimaskError) as e:
         bm.bimask_perm_refine(_pack_mask(np.zeros((32768 + 4, 32), np.uint8)), 32768 + 4, 32, N, M, i32_dev(swaps))
     assert e.value.status == 5
+
+
+@pytest.mark.parametrize("I,J,T,N,M", [(128, 256, 200, 2, 4), (1024, 256, 150, 2, 4), (64, 128, 96, 4, 8)])
+def test_whole_step_recorded_as_a_hip_graph_replays_like_eager_calls(I, J, T, N, M):
+    """The library allocates nothing and records no memset, so a whole step can be captured into a HIP
+    graph.  Replayed several times, with new weights and activations written (eager work on the same
+    stream) between the replays, every replay must give what the eager calls give on the same inputs,
+    and those agree with the oracle."""
+    import torch
+    dtype, K = synth.BF16, 20
+    perms_h = perms_of(I, K, 1302)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        W = to_dev(make_w(I, J, dtype, 1301), dtype)
+        X = torch.empty((T, J), dtype=torch.bfloat16, device="cuda")
+        dY = torch.empty((T, I), dtype=torch.bfloat16, device="cuda")
+        perms = i32_dev(perms_h)
+        # every output and workspace allocated before the capture
+        B, vals, index = bm.bimask_forward_mask_compress(W, N, M)
+        scores, best, P = bm.bimask_perm_search(B, I, J, N, M, perms)
+        ws = torch.empty((max(16, bm.workspace_bytes(bm.WS_PERM_SEARCH, I, J, 0, K, bm.BF16, N, M)),), dtype=torch.uint8, device="cuda")
+        Bbar, vb, ib = bm.bimask_backward_mask_compress(W, N, M, B, P)
+        Y = torch.empty((T, I), dtype=torch.bfloat16, device="cuda")
+        dX = torch.empty((T, J), dtype=torch.bfloat16, device="cuda")
+        wsb = torch.empty((max(16, bm.workspace_bytes(bm.WS_GEMM_BWD, I, J, T, 0, bm.BF16, N, M)),), dtype=torch.uint8, device="cuda")
+
+        def step():
+            bm.bimask_forward_mask_compress(W, N, M, B_bits=B, values=vals, index=index)
+            bm.bimask_sparse_gemm_fwd(X, vals, index, I, J, N, M, Y=Y)
+            bm.bimask_perm_search(B, I, J, N, M, perms, scores=scores, best=best, best_perm=P, workspace=ws)
+            bm.bimask_backward_mask_compress(W, N, M, B, P, Bbar_bits=Bbar, values=vb, index=ib)
+            bm.bimask_sparse_gemm_bwd(dY, P, vb, ib, I, J, N, M, dX=dX, workspace=wsb)
+
+        def fill(seed):
+            r = np.random.default_rng(seed)
+            Wn = make_w(I, J, dtype, seed)
+            Xn = synth.store(r.standard_normal((T, J), dtype=np.float32), dtype)
+            dYn = synth.store(r.standard_normal((T, I), dtype=np.float32), dtype)
+            W.copy_(to_dev(Wn, dtype)); X.copy_(to_dev(Xn, dtype)); dY.copy_(to_dev(dYn, dtype))
+            return Wn, Xn, dYn
+
+        outputs = (B, vals, scores, best, P, Bbar, vb, Y, dX)
+        fill(1310)
+        step()                                               # warm-up: one-time set-up calls happen here
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        for rep in range(3):
+            Wn, Xn, dYn = fill(1320 + rep)
+            step()
+            side.synchronize()
+            want = [t.clone() for t in outputs]
+            for t in outputs:
+                t.fill_(0)                                   # a replay must rewrite everything
+            side.synchronize()
+            graph.replay()
+            side.synchronize()
+            for got, w in zip(outputs, want):
+                assert torch.equal(got, w), rep
+        # the last replay against the oracle
+        W64 = synth.to_f64(Wn, dtype)
+        B_o = oracle.forward_mask(W64, N, M)
+        sc_o = oracle.perm_scores(B_o, perms_h, N, M)
+        best_o = oracle.argmax_first(sc_o)
+        assert (words(B) == oracle.pack_bits(B_o)).all()
+        assert (scores.cpu().numpy() == sc_o).all() and int(best.item()) == best_o
+        Bbar_o, _ = oracle.backward_mask(W64, B_o, perms_h[best_o], N, M)
+        assert (words(Bbar) == oracle.pack_bits(Bbar_o)).all()
+        assert rel_err(Y.float().cpu().numpy().astype(np.float64), oracle.gemm_fwd(synth.to_f64(Xn, dtype), W64, B_o)) <= TOL[dtype]
+        assert rel_err(dX.float().cpu().numpy().astype(np.float64),
+                       oracle.gemm_bwd(synth.to_f64(dYn, dtype), W64, Bbar_o, perms_h[best_o])) <= TOL[dtype]
