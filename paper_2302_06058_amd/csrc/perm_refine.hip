@@ -5,17 +5,19 @@
 // permutation the earlier ones left.
 //
 // An exchange between blocks A and B of M permuted rows changes the count of those two blocks
-// only, so a proposal costs 2M mask rows, not the matrix.  One workgroup of 8 wavefronts owns
-// the permutation (in LDS).  Each round, wavefront w evaluates up to 8 proposals (base + 8w ..)
-// against the current permutation: lanes stride over the 32-column words of the 2M rows, add the M - 1
-// unchanged rows of each block bit-sliced, add either exchanged row on top, compare with N and
-// pop-count the four eligibility words; a wavefront reduction gives the change of the count.
-// Then every wavefront walks the round's results in proposal order: a proposal that shares a block
-// with one kept earlier in the same round was evaluated against a stale permutation, so the
-// round ends there and the next one starts at it; otherwise it is kept if its change is
-// positive.  Kept proposals of a round touch disjoint blocks, so their exchanges commute and the
-// result equals taking the proposals one by one.  Every round consumes at least its first
-// proposal, so the loop ends.  Integer only: the result is bit-reproducible.
+// only, so a proposal costs 2M mask rows, not the matrix, and two proposals that share no block
+// commute.  One workgroup of 8 wavefronts owns the permutation (in LDS).  Each round takes up to
+// 64 proposals in order: wavefront w evaluates up to 8 of them against the current permutation
+// (lanes stride over the 32-column words of the 2M rows, add the M - 1 unchanged rows of each
+// block bit-sliced, add either exchanged row on top, compare with N and pop-count the four
+// eligibility words; a wavefront reduction gives the change of the count).  Then every wavefront
+// decides the round the same way, in order: a proposal that shares a block with an earlier
+// proposal of the round that was kept (its evaluation is stale) or deferred (it must not
+// overtake it) is deferred; any other is kept if its change is positive and dropped otherwise.
+// Deferred proposals open the next round, in their order, ahead of fresh ones.  Proposals that
+// share a block therefore never change their relative order, the ones that do not commute, so the
+// result equals taking the proposals one by one.  The first proposal of a round is always
+// decided, so the loop ends.  Integer only: the result is bit-reproducible.
 #include <atomic>
 
 #include "common.hpp"
@@ -57,6 +59,87 @@ __device__ __forceinline__ uint32_t at_most(const uint32_t (&c)[L], uint32_t w, 
     return ~gt;
 }
 
+// Change of the eligible-block count for the proposals wave * PPWX + p (p < PPWX) of a round of nb, evaluated
+// against the permutation in sP; results to the round's LDS arrays.  The round's first npend proposals are the
+// ones deferred by the round before (sPend), the others come from the staged stream (sSw, from `first`).
+template <int M, int PPWX>
+__device__ __forceinline__ void refine_evaluate(const uint32_t* __restrict__ Bm, int I, int words, int N,
+                                                const int32_t* sP, const int32_t* sPend, int npend,
+                                                const int32_t* sSw, int first, int nb, int wave, int lane,
+                                                int* sDelta, int* sKa, int* sKb, int* sPa, int* sPb) {
+    constexpr int L = RefinePlanes<M>::L;
+    constexpr int SH = M == 4 ? 2 : (M == 8 ? 3 : 4);
+    // proposals wave * PPWX + p; one that changes nothing (outside [0, I), both positions in one
+    // block, beyond the round) is evaluated on positions 0 and 0 and its result dropped
+    int a[PPWX], b[PPWX], ka[PPWX], kb[PPWX], d[PPWX];
+    bool live[PPWX];
+    uint32_t ra[PPWX][M], rb[PPWX][M];
+#pragma unroll
+    for (int p = 0; p < PPWX; ++p) {
+        const int q = wave * PPWX + p;
+        const int32_t* src = q < npend ? sPend + 2 * q : sSw + 2 * (first + q - npend);
+        a[p] = q < nb ? src[0] : -1;
+        b[p] = q < nb ? src[1] : -1;
+        const bool valid = a[p] >= 0 && a[p] < I && b[p] >= 0 && b[p] < I;
+        live[p] = valid && (a[p] >> SH) != (b[p] >> SH);
+        const int ac = live[p] ? a[p] : 0, bc = live[p] ? b[p] : 0;
+        ka[p] = ac >> SH;
+        kb[p] = bc >> SH;
+        // word offsets of the rows: I * words < 2^31 is checked on the host
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            ra[p][m] = static_cast<uint32_t>(sP[ka[p] * M + m]) * words;
+            rb[p][m] = static_cast<uint32_t>(sP[kb[p] * M + m]) * words;
+        }
+        d[p] = 0;
+    }
+    for (int w0 = 0; w0 < words; w0 += 64) {     // uniform trip count
+        const bool in = w0 + lane < words;
+        const uint32_t w = in ? w0 + lane : 0;
+        // all loads of the round first, then the arithmetic: a round costs one memory round trip
+        uint32_t xa[PPWX][M], xb[PPWX][M];
+#pragma unroll
+        for (int p = 0; p < PPWX; ++p) {
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                xa[p][m] = Bm[ra[p][m] + w];
+                xb[p][m] = Bm[rb[p][m] + w];
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int p = 0; p < PPWX; ++p) {
+            const int ma = a[p] & (M - 1), mb = b[p] & (M - 1);
+            uint32_t cA[L], cB[L], wa = 0u, wb = 0u;   // wa, wb: the two exchanged rows
+#pragma unroll
+            for (int k = 0; k < L; ++k) cA[k] = cB[k] = 0u;
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                add_word<L>(cA, m == ma ? 0u : xa[p][m]);
+                add_word<L>(cB, m == mb ? 0u : xb[p][m]);
+                wa |= m == ma ? xa[p][m] : 0u;
+                wb |= m == mb ? xb[p][m] : 0u;
+            }
+            const int dd = __popc(at_most<L>(cA, wb, N)) + __popc(at_most<L>(cB, wa, N))
+                         - __popc(at_most<L>(cA, wa, N)) - __popc(at_most<L>(cB, wb, N));
+            d[p] += in ? dd : 0;
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < PPWX; ++p) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) d[p] += __shfl_xor(d[p], off, 64);
+        const int q = wave * PPWX + p;
+        if (lane == 0 && q < nb) {
+            sDelta[q] = live[p] ? d[p] : 0;
+            sKa[q] = live[p] ? ka[p] : -1;       // changes nothing: never in anyone's way
+            sKb[q] = live[p] ? kb[p] : -1;
+            sPa[q] = a[p];
+            sPb[q] = b[p];
+        }
+    }
+}
+
 // PPW proposals per wavefront and round, all their loads in flight together: 8 for M = 4, 4 for
 // M = 8, 2 for M = 16 keeps the kernel within the 256 registers a 512-thread workgroup leaves per lane.
 template <int M> struct RefineShape {
@@ -69,129 +152,95 @@ __global__ void __launch_bounds__(kRefineThreads)
 k_perm_refine(const uint32_t* __restrict__ Bm, int I, int words, int N, const int32_t* __restrict__ perm_in,
               const int32_t* __restrict__ swaps, int64_t S, int32_t* __restrict__ perm_out,
               int32_t* __restrict__ result) {
-    constexpr int L = RefinePlanes<M>::L;
-    constexpr int SH = M == 4 ? 2 : (M == 8 ? 3 : 4);
     constexpr int PPW = RefineShape<M>::PPW, ROUND = RefineShape<M>::ROUND;
     extern __shared__ int32_t sP[];                      // the permutation, I entries
     __shared__ int32_t sSw[2 * kRefineChunk];
     __shared__ int sDelta[ROUND], sKa[ROUND], sKb[ROUND], sPa[ROUND], sPb[ROUND];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    __shared__ int32_t sPend[2 * ROUND];
+    __shared__ uint2 sC[kRefineWaves][64];
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
 
     for (int r = tid; r < I; r += kRefineThreads) sP[r] = perm_in ? perm_in[r] : r;
 
-    int gain = 0, kept = 0;
+    int gain = 0, kept = 0, npend = 0;                   // npend: proposals deferred by the round before
     int64_t base = 0, chunk0 = 0, chunk1 = 0;            // staged proposals: [chunk0, chunk1)
-    while (base < S) {                                   // uniform over the workgroup
+    while (base < S || npend > 0) {                      // uniform over the workgroup
         if (base + ROUND > chunk1 && chunk1 < S) {
             __syncthreads();                             // everyone is done with the old chunk
             chunk0 = base;
             chunk1 = base + kRefineChunk < S ? base + kRefineChunk : S;
             for (int64_t e = tid; e < 2 * (chunk1 - chunk0); e += kRefineThreads) sSw[e] = swaps[2 * chunk0 + e];
         }
-        __syncthreads();                                 // permutation and proposals are in place
-        const int nb = S - base < ROUND ? static_cast<int>(S - base) : ROUND;
-        if (wave * PPW < nb) {
-            // proposals wave * PPW + p; one that changes nothing (outside [0, I), both positions in one
-            // block, beyond the round) is evaluated on positions 0 and 0 and its result dropped
-            int a[PPW], b[PPW], ka[PPW], kb[PPW], d[PPW];
-            bool live[PPW];
-            uint32_t ra[PPW][M], rb[PPW][M];
-#pragma unroll
-            for (int p = 0; p < PPW; ++p) {
-                const int q = wave * PPW + p;
-                const int e = q < nb ? static_cast<int>(base - chunk0) + q : static_cast<int>(base - chunk0);
-                a[p] = sSw[2 * e];
-                b[p] = sSw[2 * e + 1];
-                const bool valid = q < nb && a[p] >= 0 && a[p] < I && b[p] >= 0 && b[p] < I;
-                live[p] = valid && (a[p] >> SH) != (b[p] >> SH);
-                const int ac = live[p] ? a[p] : 0, bc = live[p] ? b[p] : 0;
-                ka[p] = ac >> SH;
-                kb[p] = bc >> SH;
-                // word offsets of the rows: I * words < 2^31 is checked on the host
-#pragma unroll
-                for (int m = 0; m < M; ++m) {
-                    ra[p][m] = static_cast<uint32_t>(sP[ka[p] * M + m]) * words;
-                    rb[p][m] = static_cast<uint32_t>(sP[kb[p] * M + m]) * words;
-                }
-                d[p] = 0;
-            }
-            for (int w0 = 0; w0 < words; w0 += 64) {     // uniform trip count
-                const bool in = w0 + lane < words;
-                const uint32_t w = in ? w0 + lane : 0;
-                // all loads of the round first, then the arithmetic: a round costs one memory round trip
-                uint32_t xa[PPW][M], xb[PPW][M];
-#pragma unroll
-                for (int p = 0; p < PPW; ++p) {
-#pragma unroll
-                    for (int m = 0; m < M; ++m) {
-                        xa[p][m] = Bm[ra[p][m] + w];
-                        xb[p][m] = Bm[rb[p][m] + w];
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int p = 0; p < PPW; ++p) {
-                    const int ma = a[p] & (M - 1), mb = b[p] & (M - 1);
-                    uint32_t cA[L], cB[L], wa = 0u, wb = 0u;   // wa, wb: the two exchanged rows
-#pragma unroll
-                    for (int k = 0; k < L; ++k) cA[k] = cB[k] = 0u;
-#pragma unroll
-                    for (int m = 0; m < M; ++m) {
-                        add_word<L>(cA, m == ma ? 0u : xa[p][m]);
-                        add_word<L>(cB, m == mb ? 0u : xb[p][m]);
-                        wa |= m == ma ? xa[p][m] : 0u;
-                        wb |= m == mb ? xb[p][m] : 0u;
-                    }
-                    const int dd = __popc(at_most<L>(cA, wb, N)) + __popc(at_most<L>(cB, wa, N))
-                                 - __popc(at_most<L>(cA, wa, N)) - __popc(at_most<L>(cB, wb, N));
-                    d[p] += in ? dd : 0;
-                }
-            }
-#pragma unroll
-            for (int p = 0; p < PPW; ++p) {
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) d[p] += __shfl_xor(d[p], off, 64);
-                const int q = wave * PPW + p;
-                if (lane == 0 && q < nb) {
-                    sDelta[q] = live[p] ? d[p] : 0;
-                    sKa[q] = live[p] ? ka[p] : -1;       // changes nothing: never in anyone's way
-                    sKb[q] = live[p] ? kb[p] : -1;
-                    sPa[q] = a[p];
-                    sPb[q] = b[p];
-                }
-            }
-        }
+        __syncthreads();                                 // permutation, deferred and staged proposals are in place
+        const int room = ROUND - npend;
+        const int nfresh = S - base < room ? static_cast<int>(S - base) : room;
+        const int nb = npend + nfresh;                   // >= 1
+        const int first = static_cast<int>(base - chunk0);
+        if (wave * PPW < nb)
+            refine_evaluate<M, PPW>(Bm, I, words, N, sP, sPend, npend, sSw, first, nb, wave, lane, sDelta, sKa, sKb,
+                                    sPa, sPb);
         __syncthreads();
-        // every wavefront takes the same walk over the round's results, in scalar registers
+        // Every wavefront decides the round the same way, in registers.  Lane i: which earlier proposals of
+        // the round share a block with proposal i.
         const int dL = lane < nb ? sDelta[lane] : 0;
         const int kaL = lane < nb ? sKa[lane] : -1;
         const int kbL = lane < nb ? sKb[lane] : -1;
-        int stop = nb;
-        uint64_t keep = 0u;
-        for (int i = 0; i < nb; ++i) {
-            const int ka = __builtin_amdgcn_readlane(kaL, i), kb = __builtin_amdgcn_readlane(kbL, i);
-            bool stale = false;
-            if (ka >= 0)
-                for (uint64_t k = keep; k; k &= k - 1) {
-                    const int j = __builtin_ctzll(k);
+        uint64_t keep = 0u, pend = 0u;
+        if (__ballot(dL > 0) != 0ull) {                  // else nothing can be kept, so nothing is deferred either
+            // the comparisons are split over the wavefronts (columns j of wavefront w: w * JW ..) and OR-ed via LDS
+            constexpr int JW = ROUND / kRefineWaves;
+            uint32_t clo = 0u, chi = 0u;
+#pragma unroll
+            for (int jj = 0; jj < JW; ++jj) {
+                const int j = wave * JW + jj;            // wave-uniform
+                if (j < nb) {
                     const int ja = __builtin_amdgcn_readlane(kaL, j), jb = __builtin_amdgcn_readlane(kbL, j);
-                    stale |= ka == ja || ka == jb || kb == ja || kb == jb;
+                    const bool hit = j < lane && kaL >= 0 && ja >= 0 && (kaL == ja || kaL == jb || kbL == ja || kbL == jb);
+                    if (j < 32) clo |= hit ? 1u << j : 0u;
+                    else chi |= hit ? 1u << (j - 32) : 0u;
                 }
-            if (stale) { stop = i; break; }
-            const int d = __builtin_amdgcn_readlane(dL, i);
-            if (d > 0) {
-                keep |= 1ull << i;
-                gain += d;
-                ++kept;
+            }
+            sC[wave][lane] = make_uint2(clo, chi);
+            __syncthreads();
+            clo = chi = 0u;
+#pragma unroll
+            for (int w = 0; w < kRefineWaves; ++w) {
+                const uint2 c = sC[w][lane];
+                clo |= c.x;
+                chi |= c.y;
+            }
+            // In order: a proposal that shares a block with an earlier one that was kept (its evaluation is
+            // stale) or deferred (it must not overtake it) is deferred; any other is decided now.
+            for (int i = 0; i < nb; ++i) {
+                const uint64_t ci = (static_cast<uint64_t>(__builtin_amdgcn_readlane(chi, i)) << 32) |
+                                    static_cast<uint32_t>(__builtin_amdgcn_readlane(clo, i));
+                if (ci & (keep | pend)) {
+                    pend |= 1ull << i;
+                } else {
+                    const int d = __builtin_amdgcn_readlane(dL, i);
+                    if (d > 0) {
+                        keep |= 1ull << i;
+                        gain += d;
+                        ++kept;
+                    }
+                }
             }
         }
-        if (wave == 0 && lane < nb && ((keep >> lane) & 1ull)) {   // disjoint blocks: disjoint positions
+        if (wave == 0 && lane < nb) {
             const int a = sPa[lane], b = sPb[lane];
-            const int32_t t = sP[a];
-            sP[a] = sP[b];
-            sP[b] = t;
+            if ((keep >> lane) & 1ull) {                 // kept proposals touch disjoint blocks: disjoint positions
+                const int32_t t = sP[a];
+                sP[a] = sP[b];
+                sP[b] = t;
+            }
+            if ((pend >> lane) & 1ull) {                 // deferred proposals open the next round, in order
+                const int slot = __builtin_popcountll(pend & ((1ull << lane) - 1ull));
+                sPend[2 * slot] = a;
+                sPend[2 * slot + 1] = b;
+            }
         }
-        base += stop;                                    // stop >= 1: the first proposal is never stale
+        base += nfresh;
+        npend = __builtin_popcountll(pend);              // < nb: the round's first proposal is always decided
     }
     __syncthreads();
     for (int r = tid; r < I; r += kRefineThreads) perm_out[r] = sP[r];
