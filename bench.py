@@ -585,6 +585,16 @@ def main():
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     dom_us = sum(a.elapsed_time(b) for a, b in dom_pairs) * 1e3 / len(dom_pairs)
+    # what an event pair reads with nothing between its two records, in the same queue state (right after a
+    # kernel): the part of dom_us that is marker processing, not kernel time.  Reported, never subtracted from `achieved`.
+    empty_pairs = []
+    for i in range(20):
+        run.stages[0][1](i % copies)
+        a, b = ev(), ev()
+        a.record(); b.record()
+        empty_pairs.append((a, b))
+    torch.cuda.synchronize()
+    empty_us = sorted(a.elapsed_time(b) * 1e3 for a, b in empty_pairs)[len(empty_pairs) // 2]
 
     # -- secondary figure: the step as Alg. 1 runs it between two searches (P kept for delta-T steps):
     #    forward mask, forward GEMM, backward mask with the cached P, backward GEMM
@@ -609,6 +619,7 @@ def main():
         roof = {"bound": "mfma", "achieved": round(tfl, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(tfl / MFMA_BF16_PEAK_TFLOPS, 4)}
     roof.update({"traffic": MEASURED_TRAFFIC_BYTES.get((args.config, dominant)), "kernel": dominant, "avg_us": round(dom_us, 2),
+                 "empty_event_pair_us": round(empty_us, 2),
                  "algorithmic_bytes": int(dom_bytes), "dense_equiv_tflops": round(tfl, 1)})
 
     out = {
