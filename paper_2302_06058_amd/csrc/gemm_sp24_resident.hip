@@ -355,6 +355,13 @@ int launch_gemm_sp24_resident(const void* A, const uint32_t* meta, int64_t Adim,
         const int rc = launch_gemm_sp24_narrow(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, s);
         if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
     }
+    if (perm && K > 128 && ceil_div(T, 32) >= 512) {
+        // Eq. (10)'s gather with many tokens: whole rows of g(Y) in LDS, 16-32 rows per workgroup (512 x 128
+        // backward at 50176 tokens 41 -> 29 us, 384 x 384 at 25216 tokens 22 -> 20 us; fewer tokens: 512 x 512
+        // at 12544 was 15 -> 16.5 us, hence the bound); takes aligned operands only, else the kernels below
+        const int rc = launch_gemm_sp24_rowres(A, meta, Adim, K, Bsrc, ldb, perm, T, C, ldc, s);
+        if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
+    }
     const int nstg = static_cast<int>(ceil_div(K, 128));
     if (Adim <= 128 && nstg <= 2) {
         // one narrow weight tile: the workgroup is a latency chain (fill, multiply, store), so

@@ -1,5 +1,6 @@
 // 2:4-sparse bf16 backward GEMM with the column gather of Eq. (10) fused, for out-feature
-// counts too long for the resident-token kernel (512 < I <= 2048) and few in-features:
+// counts too long for the resident-token kernel (512 < I <= 2048; with many tokens also
+// 128 < I <= 512, where it is the faster of the two) and few in-features:
 //     dX[t][j] = sum_r dY[t][P[r]] * Wb[j][r],   j < J <= 512,  r < I
 // (arXiv 2302.06058, Eq. (10); the shapes are the 1x1 "expand" convolutions of a ResNet
 // bottleneck, I = 4 J, and the wide linear layers of a transformer block seen from behind.)
@@ -10,7 +11,7 @@
 // positions with 2-byte LDS stores (the inverse permutation sits in LDS), so the gather costs
 // no memory traffic at all.  The four wavefronts then walk over the weight-row tiles (64
 // rows per pass, at most two passes each), streaming the fragment-major compressed weights
-// from L2 three stages ahead and reading every token fragment with two 8-byte LDS loads
+// from L2 two stages ahead and reading every token fragment with two 8-byte LDS loads
 // (row pitch = 2 I + 8 bytes: 32 lanes hit 64 distinct banks).  The output tile is regrouped
 // through the same LDS area and leaves as whole rows.
 #include "common.hpp"
@@ -231,16 +232,21 @@ k_gemm_sp24_rowres(const uint16_t* __restrict__ A, const uint32_t* __restrict__ 
 
 }  // namespace
 
-bool gemm_sp24_rowres_shape(int64_t Adim, int64_t K) {
-    return K > 512 && K <= 2048 && K % 8 == 0 && Adim >= 8 && Adim <= 512 && Adim % 8 == 0 && Adim <= K;
+namespace {
+// what the kernel itself takes; contractions up to 512 reach it through launch_gemm_sp24_resident
+bool rowres_takes(int64_t Adim, int64_t K) {
+    return K > 128 && K <= 2048 && K % 8 == 0 && Adim >= 8 && Adim <= 512 && Adim % 8 == 0 && Adim <= K;
 }
+}  // namespace
+
+bool gemm_sp24_rowres_shape(int64_t Adim, int64_t K) { return K > 512 && rowres_takes(Adim, K); }
 
 // Returns BIMASK_ERR_UNSUPPORTED when the shape / alignment is outside this kernel (the caller then
 // gathers g(Y)[:, P] into the workspace and runs the streaming kernel).
 int launch_gemm_sp24_rowres(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc,
                             int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, hipStream_t s) {
     if (!perm || T < 1) return BIMASK_ERR_UNSUPPORTED;
-    if (!gemm_sp24_rowres_shape(Adim, K)) return BIMASK_ERR_UNSUPPORTED;
+    if (!rowres_takes(Adim, K)) return BIMASK_ERR_UNSUPPORTED;
     if (!aligned16(A) || !aligned16(meta) || !aligned16(Bsrc) || !aligned16(C) || ldb % 8 != 0 || ldc % 8 != 0)
         return BIMASK_ERR_UNSUPPORTED;
     // rows per token tile (<= 32): the fewest sequential tile slots per CU, then the tallest tile

@@ -260,6 +260,15 @@ def test_long_contraction_backward_uses_gather_pass(I, J, T):
     check_layer(I=I, J=J, N=2, M=4, dtype=synth.BF16, K=4, seed=900 + I, T=T)
 
 
+@pytest.mark.parametrize("I,J,T", [(384, 128, 16400), (256, 256, 16385), (512, 40, 16390), (136, 72, 16400),
+                                   (512, 512, 16384), (260, 128, 16400)])
+def test_short_contraction_backward_with_many_tokens(I, J, T):
+    # 128 < I <= 512 and at least 512 tiles of 32 tokens: the backward GEMM keeps whole rows of g(Y) in LDS
+    # (ragged last tile: 16400 = 512 x 32 + 16, 16385 = 512 x 32 + 1; I = 136: ragged second stage;
+    # I = 260 is no multiple of 8: that one stays with the token-resident kernel)
+    check_layer(I=I, J=J, N=2, M=4, dtype=synth.BF16, K=4, seed=950 + I, T=T)
+
+
 @pytest.mark.parametrize("I,J,T", [(64, 148, 131), (68, 148, 131), (132, 260, 77), (64, 148, 4100), (36, 12, 9),
                                    (64, 64, 1), (224, 64, 31), (192, 96, 65), (64, 256, 8200)])
 def test_narrow_weights_and_unaligned_contiguous_rows(I, J, T):
