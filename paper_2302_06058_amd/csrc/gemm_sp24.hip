@@ -58,11 +58,13 @@ __device__ __forceinline__ u32x4 load_guarded(const uint16_t* row, int64_t k, in
 
 // BGUARD: token rows are not 16-byte aligned or K is not a multiple of 128; every token
 // load is then bounds-checked against K (the weight operand is zero-padded by its format).
+// KTAIL (without BGUARD): rows are 16-byte aligned and K is a multiple of 8 but not of 128: 16-byte token loads as on
+// the fast path, the granules of the last stage that lie beyond K are fetched from the row's start and zeroed.
 // BHALF: only the first half of the wavefronts fetch the token tile (twice as much each).  The
 // token rows come from HBM, the weights from L2; a wavefront's loads complete in order, so weight
 // loads queued behind token loads inherit their latency -- with BHALF half of the wavefronts
 // carry nothing but L2 hits.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD, bool BHALF>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD, bool BHALF, bool KTAIL>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int64_t K,
             const uint16_t* __restrict__ Bm, int64_t T, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
@@ -113,6 +115,7 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
     }
     const uint16_t* pb[NB_];
     int sb_off[NB_];
+    const int g8 = 8 * (tid & 15);                      // first element of this thread's granule within a stage (NTB is a multiple of 16)
 #pragma unroll
     for (int it = 0; it < NB_; ++it) {
         const int q = (BHALF ? tid & (NTB - 1) : tid) + NTB * it, row = q >> 4, g = q & 15;
@@ -140,7 +143,11 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
         if (bfetch) _Pragma("unroll") for (int it = 0; it < NB_; ++it) {                        \
             if constexpr (BGUARD)                                                                \
                 rb[slot][it] = load_guarded(pb[it], kk + 8 * ((tid + NTB * it) & 15), K);       \
-            else                                                                                 \
+            else if constexpr (KTAIL) {                                                          \
+                const bool in = kk + g8 < K;                                                     \
+                const u32x4 v = *reinterpret_cast<const u32x4*>(pb[it] + (in ? kk : -static_cast<int64_t>(g8))); \
+                rb[slot][it] = in ? v : (u32x4){0u, 0u, 0u, 0u};                                 \
+            } else                                                                               \
                 rb[slot][it] = *reinterpret_cast<const u32x4*>(pb[it] + kk);                     \
         }                                                                                        \
         _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                         \
@@ -264,11 +271,11 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD, bool BHALF>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD, bool BHALF, bool KTAIL = false>
 int run_sp24_t(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb,
              void* C, int64_t ldc, hipStream_t s) {
     using S = SpSmem<BM, BN>;
-    auto kern = k_gemm_sp24<BM, BN, WAVES_M, WAVES_N, PF, BGUARD, BHALF>;
+    auto kern = k_gemm_sp24<BM, BN, WAVES_M, WAVES_N, PF, BGUARD, BHALF, KTAIL>;
     if (S::kTotal > 48 * 1024) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 S::kTotal) != hipSuccess) return BIMASK_ERR_HIP;
@@ -286,8 +293,9 @@ int run_sp24_t(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, con
 template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BHALF = false>
 int run_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb,
              void* C, int64_t ldc, hipStream_t s) {
-    const bool fastb = K % SK == 0 && aligned16(Bm) && (ldb * 2) % 16 == 0;
-    if (fastb) return run_sp24_t<BM, BN, WAVES_M, WAVES_N, PF, false, BHALF>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+    const bool rows16 = aligned16(Bm) && (ldb * 2) % 16 == 0;
+    if (rows16 && K % SK == 0) return run_sp24_t<BM, BN, WAVES_M, WAVES_N, PF, false, BHALF>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
+    if (rows16 && K % 8 == 0) return run_sp24_t<BM, BN, WAVES_M, WAVES_N, PF, false, BHALF, true>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
     return run_sp24_t<BM, BN, WAVES_M, WAVES_N, 1, true, false>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
 }
 

@@ -242,7 +242,8 @@ def test_results_are_reproducible_bit_for_bit():
 @pytest.mark.parametrize("I,J,T", [(256, 384, 200), (384, 256, 130), (128, 1152, 64), (640, 128, 333),
                                    (384, 640, 150), (640, 384, 90),    # 384 weight rows: 128-row tiles
                                    (512, 128, 150), (384, 64, 100),    # narrow backward operand, 3-4 stages
-                                   (64, 640, 150), (48, 768, 70), (1024, 64, 90)])   # <= 64 weight rows, long contraction: 64 x 64 tiles
+                                   (64, 640, 150), (48, 768, 70), (1024, 64, 90),    # <= 64 weight rows, long contraction: 64 x 64 tiles
+                                   (64, 576, 150), (256, 328, 100), (576, 1032, 70), (320, 840, 90)])   # aligned rows, ragged last stage
 def test_streaming_gemm_shapes(I, J, T):
     # contraction lengths that are multiples of 128 take the streaming 2:4 kernel in both
     # directions; ragged token counts and weight-row counts exercise its edge tiles
