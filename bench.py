@@ -59,6 +59,8 @@ def parse():
     ap.add_argument("--refine", action="store_true",
                     help="diagnostic: hill-climbing refinement of the search's winner by random exchange proposals "
                          "(time, eligible-block share, gradient gap)")
+    ap.add_argument("--refine-network", action="store_true",
+                    help="refinement of every layer's permutation: one call per layer against the grouped call")
     ap.add_argument("--search-table", action="store_true",
                     help="permutation search over all ResNet-50 layers for 2:4, 4:8, 1:4, 2:8, 1:16 (the shape of the paper's Table 6)")
     ap.add_argument("--delta-t", type=int, default=100,
@@ -454,6 +456,73 @@ def refine_report(args):
           flush=True)
 
 
+def refine_network(args):
+    """Refinement of every layer's permutation after the search, S = 4 I random exchange proposals per layer:
+    one call per layer (one workgroup busy at a time) against one grouped call (one workgroup per layer, all at once)."""
+    import torch
+    import paper_2302_06058_amd as bm
+    from paper_2302_06058_amd import synth
+    from helpers import to_dev, i32_dev
+    layers = synth.get_config(args.config)
+    by_nm = {}
+    for L in layers:
+        by_nm.setdefault((L.N, L.M, L.K), []).append(L)
+    out = {}
+    for (N, M, K), Ls in by_nm.items():
+        entries, calls = [], []
+        blocks = gain0 = 0
+        for L in Ls:
+            W = to_dev(synth.gen_weights(L), L.dtype)
+            rng = np.random.default_rng([L.seed, 55])
+            perms = i32_dev(np.stack([rng.permutation(L.I) for _ in range(K)]).astype(np.int32))
+            swaps = i32_dev(rng.integers(0, L.I, size=(4 * L.I, 2)).astype(np.int32))
+            e = dict(W=W, B_bits=bm.bimask_forward_mask(W, N, M), perms=perms, swaps=swaps,
+                     scores=torch.empty((K,), dtype=torch.int32, device=W.device),
+                     best=torch.empty((1,), dtype=torch.int32, device=W.device),
+                     best_perm=torch.empty((L.I,), dtype=torch.int32, device=W.device),
+                     refine_result=torch.empty((2,), dtype=torch.int32, device=W.device),
+                     workspace=torch.empty((max(16, bm.workspace_bytes(bm.WS_PERM_SEARCH, L.I, L.J, 0, K, bm.BF16, N, M)),),
+                                           dtype=torch.uint8, device=W.device))
+            entries.append(e)
+            blocks += (L.I // M) * L.J
+        arr = bm.group_layers(entries)
+        bm.bimask_perm_search_group(arr, N, M, K)
+        torch.cuda.synchronize()
+        start = [e["best_perm"].clone() for e in entries]
+        base = sum(int(e["scores"].max()) for e in entries)
+        st = torch.cuda.current_stream().cuda_stream
+        for e, L in zip(entries, Ls):
+            calls.append(bm.prepare("bimask_perm_refine", e["B_bits"], L.I, L.J, N, M, e["best_perm"], e["swaps"],
+                                    4 * L.I, e["best_perm"], e["refine_result"], st))
+
+        def reset():
+            for e, p0 in zip(entries, start):
+                e["best_perm"].copy_(p0)
+
+        def timed(fn):
+            ts = []
+            for _ in range(max(2, args.steps)):
+                reset()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                a.record(); fn(); b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            return sorted(ts)[len(ts) // 2]
+
+        ms_each = timed(lambda: [c() for c in calls])
+        per_layer = [e["best_perm"].clone() for e in entries]
+        ms_group = timed(lambda: bm.bimask_perm_refine_group(arr, N, M))
+        same = all(torch.equal(e["best_perm"], p) for e, p in zip(entries, per_layer))
+        gain = sum(int(e["refine_result"][0]) for e in entries)
+        out[f"{N}:{M}"] = {"layers": len(Ls), "proposals": sum(4 * L.I for L in Ls), "ms_one_call_per_layer": round(ms_each, 3),
+                           "ms_grouped_call": round(ms_group, 3), "grouped_equals_per_layer": bool(same),
+                           "eligible_block_share_before": round(base / blocks, 4),
+                           "eligible_block_share_after": round((base + gain) / blocks, 4)}
+    print(json.dumps({"metric": "refinement of all layers' permutations (4 I proposals per layer, after the K-candidate search)",
+                      "unit": "ms", "config": args.config, "steps": args.steps, "by_pattern": out}), flush=True)
+
+
 def search_table(args):
     """Whole-network permutation search (forward mask given, K = 100 candidates scored and the best
     picked, per layer) for the five N:M patterns of the paper's Table 6, on the ResNet-50 layer
@@ -536,6 +605,8 @@ def main():
         return gradient_gap(args)
     if args.refine:
         return refine_report(args)
+    if args.refine_network:
+        return refine_network(args)
     if args.network_step:
         return network_step(args)
     layer = synth.get_config(args.config)[args.layer]

@@ -210,6 +210,9 @@ BIMASK_API int bimask_perm_refine(const uint32_t *B_bits, int64_t I, int64_t J, 
  *                             NULL), with workspace / workspace_bytes as in bimask_perm_search
  *                    backward uses W, I, J, ldw, B_bits, best_perm (the permutation; NULL =
  *                             identity) -> Bbar_bits, Wb_values, Wb_index
+ *                    refine   uses B_bits, I, J, swaps, n_swaps -> best_perm (refined IN PLACE,
+ *                             must not be NULL), refine_result; one workgroup per layer, all
+ *                             layers at once (limits as bimask_perm_refine)
  * Errors: as the per-layer calls; the first failing layer's code is returned and nothing is
  * launched if any layer fails validation.                                                */
 typedef struct bimask_group_layer {
@@ -227,6 +230,9 @@ typedef struct bimask_group_layer {
     uint32_t *Bbar_bits;
     void *Wb_values;
     uint32_t *Wb_index;
+    const int32_t *swaps;       /* n_swaps x 2 proposed exchanges (bimask_perm_refine) */
+    int64_t n_swaps;
+    int32_t *refine_result;     /* int32[2]: gain, proposals kept */
 } bimask_group_layer;
 
 BIMASK_API int bimask_forward_mask_compress_group(const bimask_group_layer *layers, int n, int dtype, int N, int M,
@@ -234,6 +240,7 @@ BIMASK_API int bimask_forward_mask_compress_group(const bimask_group_layer *laye
 BIMASK_API int bimask_perm_search_group(const bimask_group_layer *layers, int n, int N, int M, int K, void *stream);
 BIMASK_API int bimask_backward_mask_compress_group(const bimask_group_layer *layers, int n, int dtype, int N, int M,
                                         void *stream);
+BIMASK_API int bimask_perm_refine_group(const bimask_group_layer *layers, int n, int N, int M, void *stream);
 
 /* Buffer sizes of a compressed operand with `rows` x `cols` logical entries: number of
  * elements of `values` and of uint32 words of `index` (0 when no index is written).     */

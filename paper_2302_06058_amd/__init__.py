@@ -33,6 +33,7 @@ _SIGNATURES = {
     "bimask_forward_mask_compress_group": (_INT, [_PTR, _INT, _INT, _INT, _INT, _PTR]),
     "bimask_perm_search_group": (_INT, [_PTR, _INT, _INT, _INT, _INT, _PTR]),
     "bimask_backward_mask_compress_group": (_INT, [_PTR, _INT, _INT, _INT, _INT, _PTR]),
+    "bimask_perm_refine_group": (_INT, [_PTR, _INT, _INT, _INT, _PTR]),
     "bimask_operand_elems": (_I64, [_I64, _I64, _INT, _INT]),
     "bimask_operand_index_words": (_I64, [_I64, _I64, _INT, _INT]),
     "bimask_workspace_bytes": (_SZ, [_INT, _I64, _I64, _I64, _INT, _INT, _INT, _INT]),
@@ -307,21 +308,23 @@ class GroupLayer(ctypes.Structure):
     _fields_ = [("W", _PTR), ("I", _I64), ("J", _I64), ("ldw", _I64), ("B_bits", _PTR), ("Wf_values", _PTR),
                 ("Wf_index", _PTR), ("perms", _PTR), ("scores", _PTR), ("best", _PTR), ("best_perm", _PTR),
                 ("workspace", _PTR), ("workspace_bytes", _SZ), ("Bbar_bits", _PTR), ("Wb_values", _PTR),
-                ("Wb_index", _PTR)]
+                ("Wb_index", _PTR), ("swaps", _PTR), ("n_swaps", _I64), ("refine_result", _PTR)]
 
 
 def group_layers(entries):
     """A host array of `bimask_group_layer` from dicts of tensors / ints (argument marshalling only).
     Keys: W (2-D tensor), B_bits, Wf_values, Wf_index, perms, scores, best, best_perm, workspace, Bbar_bits,
-    Wb_values, Wb_index -- absent keys stay NULL.  The tensors must outlive the calls that use the array."""
+    Wb_values, Wb_index, swaps (S x 2 int32), refine_result -- absent keys stay NULL.  The tensors must outlive
+    the calls that use the array."""
     arr = (GroupLayer * len(entries))()
     for g, e in zip(arr, entries):
         W = e["W"]
         _need_cuda(*[v for v in e.values() if hasattr(v, "is_cuda")])
         g.W, g.I, g.J, g.ldw = W.data_ptr(), W.shape[0], W.shape[1], _rowmajor(W)
         for key in ("B_bits", "Wf_values", "Wf_index", "perms", "scores", "best", "best_perm", "Bbar_bits",
-                    "Wb_values", "Wb_index"):
+                    "Wb_values", "Wb_index", "swaps", "refine_result"):
             setattr(g, key, _ptr(e.get(key)))
+        g.n_swaps = 0 if e.get("swaps") is None else e["swaps"].shape[0]
         ws = e.get("workspace")
         g.workspace = _ptr(ws)
         g.workspace_bytes = 0 if ws is None else ws.numel() * ws.element_size()
@@ -336,6 +339,11 @@ def bimask_forward_mask_compress_group(layers, dtype: int, N: int, M: int) -> No
 def bimask_perm_search_group(layers, N: int, M: int, K: int) -> None:
     _check("bimask_perm_search_group",
            lib().bimask_perm_search_group(ctypes.cast(layers, _PTR), len(layers), N, M, K, _stream()))
+
+
+def bimask_perm_refine_group(layers, N: int, M: int) -> None:
+    _check("bimask_perm_refine_group",
+           lib().bimask_perm_refine_group(ctypes.cast(layers, _PTR), len(layers), N, M, _stream()))
 
 
 def bimask_backward_mask_compress_group(layers, dtype: int, N: int, M: int) -> None:

@@ -162,6 +162,20 @@ int bimask_perm_search_group(const bimask_group_layer* layers, int n, int N, int
     return launch_perm_search_group(layers, n, N, M, K, as_stream(stream));
 }
 
+int bimask_perm_refine_group(const bimask_group_layer* layers, int n, int N, int M, void* stream) {
+    if (!layers) return BIMASK_ERR_NULL;
+    if (n <= 0) return BIMASK_ERR_SHAPE;
+    if (int rc = check_nm(N, M)) return rc;
+    for (int l = 0; l < n; ++l) {
+        const bimask_group_layer& a = layers[l];
+        if (!a.B_bits || !a.best_perm || !a.refine_result || (a.n_swaps > 0 && !a.swaps)) return BIMASK_ERR_NULL;
+        if (a.I <= 0 || a.J <= 0 || a.n_swaps < 0 || a.I % M || a.J % M) return BIMASK_ERR_SHAPE;
+        if (a.I > 0x7FFFFFFFll || a.J > 0x7FFFFFFFll || (a.I / M) * a.J > 0x7FFFFFFFll) return BIMASK_ERR_SHAPE;
+        if (!aligned4(a.best_perm) || !aligned4(a.swaps) || !aligned4(a.refine_result)) return BIMASK_ERR_ALIGN;
+    }
+    return launch_perm_refine_group(layers, n, N, M, as_stream(stream));
+}
+
 int bimask_backward_mask_compress_group(const bimask_group_layer* layers, int n, int dtype, int N, int M,
                                         void* stream) {
     if (!layers) return BIMASK_ERR_NULL;

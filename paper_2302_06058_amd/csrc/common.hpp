@@ -148,6 +148,7 @@ int launch_gemm_sp24_rowres(const void* A, const uint32_t* meta, int64_t Adim, i
 constexpr int64_t kRefineMaxRows = 32768;
 int launch_perm_refine(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perm_in,
                        const int32_t* swaps, int64_t S, int32_t* perm_out, int32_t* result, hipStream_t s);
+int launch_perm_refine_group(const bimask_group_layer* L, int n, int N, int M, hipStream_t s);
 bool gemm_bwd_needs_gather(int64_t I, int64_t J, int dtype, int N, int M);
 // Shapes (output rows Adim, contraction K) the row-resident backward kernel takes.
 bool gemm_sp24_rowres_shape(int64_t Adim, int64_t K);

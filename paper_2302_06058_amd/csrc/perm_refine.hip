@@ -148,10 +148,9 @@ template <int M> struct RefineShape {
 };
 
 template <int M>
-__global__ void __launch_bounds__(kRefineThreads)
-k_perm_refine(const uint32_t* __restrict__ Bm, int I, int words, int N, const int32_t* __restrict__ perm_in,
-              const int32_t* __restrict__ swaps, int64_t S, int32_t* __restrict__ perm_out,
-              int32_t* __restrict__ result) {
+__device__ __forceinline__ void
+perm_refine_body(const uint32_t* __restrict__ Bm, int I, int words, int N, const int32_t* perm_in,
+                 const int32_t* __restrict__ swaps, int64_t S, int32_t* perm_out, int32_t* __restrict__ result) {
     constexpr int PPW = RefineShape<M>::PPW, ROUND = RefineShape<M>::ROUND;
     extern __shared__ int32_t sP[];                      // the permutation, I entries
     __shared__ int32_t sSw[2 * kRefineChunk];
@@ -251,18 +250,70 @@ k_perm_refine(const uint32_t* __restrict__ Bm, int I, int words, int N, const in
 }
 
 template <int M>
+__global__ void __launch_bounds__(kRefineThreads)
+k_perm_refine(const uint32_t* __restrict__ Bm, int I, int words, int N, const int32_t* perm_in,
+              const int32_t* __restrict__ swaps, int64_t S, int32_t* perm_out, int32_t* __restrict__ result) {
+    perm_refine_body<M>(Bm, I, words, N, perm_in, swaps, S, perm_out, result);
+}
+
+// Many layers at once: workgroup b refines layer b (in place), the argument table travels in the kernel arguments.
+struct RefineEntry {
+    const uint32_t* B;
+    int32_t* perm;
+    const int32_t* swaps;
+    int32_t* result;
+    int64_t S;
+    int I, words;
+};
+constexpr int kRefineGroupCap = 64;
+struct RefineGroup { RefineEntry e[kRefineGroupCap]; };
+static_assert(sizeof(RefineGroup) <= 3840, "argument table must fit the kernel arguments");
+
+template <int M>
+__global__ void __launch_bounds__(kRefineThreads)
+k_perm_refine_group(const RefineGroup g, int N) {
+    const RefineEntry& e = g.e[blockIdx.x];
+    perm_refine_body<M>(e.B, e.I, e.words, N, e.perm, e.swaps, e.S, e.perm, e.result);
+}
+
+template <int M>
+int set_refine_lds(const void* kern, size_t lds, std::atomic<bool>& done) {
+    if (lds > 48 * 1024 && !done.load(std::memory_order_relaxed)) {
+        if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            return BIMASK_ERR_HIP;
+        }
+        done.store(true, std::memory_order_relaxed);
+    }
+    return BIMASK_OK;
+}
+
+template <int M>
+int run_refine_group(const bimask_group_layer* L, int n, int N, hipStream_t s) {
+    static std::atomic<bool> attr_set{false};
+    for (int first = 0; first < n; first += kRefineGroupCap) {
+        const int cnt = n - first < kRefineGroupCap ? n - first : kRefineGroupCap;
+        RefineGroup g;
+        size_t lds = 0;
+        for (int l = 0; l < cnt; ++l) {
+            const bimask_group_layer& a = L[first + l];
+            g.e[l] = RefineEntry{a.B_bits, a.best_perm, a.swaps, a.refine_result, a.n_swaps, static_cast<int>(a.I),
+                                 static_cast<int>(ceil_div(a.J, 32))};
+            lds = lds > static_cast<size_t>(a.I) * 4 ? lds : static_cast<size_t>(a.I) * 4;
+        }
+        if (int rc = set_refine_lds<M>(reinterpret_cast<const void*>(k_perm_refine_group<M>), lds, attr_set)) return rc;
+        hipLaunchKernelGGL(k_perm_refine_group<M>, dim3(cnt), dim3(kRefineThreads), lds, s, g, N);
+        if (int rc = check_launch()) return rc;
+    }
+    return BIMASK_OK;
+}
+
+template <int M>
 int run_refine(const uint32_t* B_bits, int64_t I, int64_t J, int N, const int32_t* perm_in, const int32_t* swaps,
                int64_t S, int32_t* perm_out, int32_t* result, hipStream_t s) {
     static std::atomic<bool> attr_set{false};
     const size_t lds = static_cast<size_t>(I) * 4;
-    if (lds > 48 * 1024 && !attr_set.load(std::memory_order_relaxed)) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_perm_refine<M>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024) != hipSuccess) {
-            (void)hipGetLastError();
-            return BIMASK_ERR_HIP;
-        }
-        attr_set.store(true, std::memory_order_relaxed);
-    }
+    if (int rc = set_refine_lds<M>(reinterpret_cast<const void*>(k_perm_refine<M>), lds, attr_set)) return rc;
     hipLaunchKernelGGL(k_perm_refine<M>, dim3(1), dim3(kRefineThreads), lds, s, B_bits, static_cast<int>(I),
                        static_cast<int>(ceil_div(J, 32)), N, perm_in, swaps, S, perm_out, result);
     return check_launch();
@@ -277,6 +328,17 @@ int launch_perm_refine(const uint32_t* B_bits, int64_t I, int64_t J, int N, int 
         case 4: return run_refine<4>(B_bits, I, J, N, perm_in, swaps, S, perm_out, result, s);
         case 8: return run_refine<8>(B_bits, I, J, N, perm_in, swaps, S, perm_out, result, s);
         case 16: return run_refine<16>(B_bits, I, J, N, perm_in, swaps, S, perm_out, result, s);
+        default: return BIMASK_ERR_NM;
+    }
+}
+
+int launch_perm_refine_group(const bimask_group_layer* L, int n, int N, int M, hipStream_t s) {
+    for (int l = 0; l < n; ++l)
+        if (L[l].I > kRefineMaxRows || L[l].I * ceil_div(L[l].J, 32) > 0x7FFFFFFFll) return BIMASK_ERR_UNSUPPORTED;
+    switch (M) {
+        case 4: return run_refine_group<4>(L, n, N, s);
+        case 8: return run_refine_group<8>(L, n, N, s);
+        case 16: return run_refine_group<16>(L, n, N, s);
         default: return BIMASK_ERR_NM;
     }
 }

@@ -126,8 +126,9 @@ def test_grouped_calls_validate_every_layer_before_any_launch():
         g = bm.GroupLayer()
         g.W, g.I, g.J, g.ldw = fake, 64, 128, 128
         for f in ("B_bits", "Wf_values", "Wf_index", "perms", "scores", "best", "best_perm", "workspace", "Bbar_bits",
-                  "Wb_values", "Wb_index"):
+                  "Wb_values", "Wb_index", "swaps", "refine_result"):
             setattr(g, f, fake)
+        g.n_swaps = 10
         g.workspace_bytes = 1 << 20
         for k, v in kw.items():
             setattr(g, k, v)
@@ -156,3 +157,16 @@ def test_grouped_calls_validate_every_layer_before_any_launch():
     assert L.bimask_backward_mask_compress_group(p, 2, bm.BF16, 2, 4, None) == 1
     p, keep = arr(layer(Wb_values=0x10002))
     assert L.bimask_backward_mask_compress_group(p, 1, bm.BF16, 2, 4, None) == 7
+    # refinement of many layers
+    p, keep = arr(layer(), layer(best_perm=None))
+    assert L.bimask_perm_refine_group(p, 2, 2, 4, None) == 1
+    p, keep = arr(layer(), layer(swaps=None))
+    assert L.bimask_perm_refine_group(p, 2, 2, 4, None) == 1
+    p, keep = arr(layer(n_swaps=-1))
+    assert L.bimask_perm_refine_group(p, 1, 2, 4, None) == 2
+    p, keep = arr(layer(I=32772))
+    assert L.bimask_perm_refine_group(p, 1, 2, 4, None) == 5
+    p, keep = arr(layer(swaps=0x10002))
+    assert L.bimask_perm_refine_group(p, 1, 2, 4, None) == 7
+    assert L.bimask_perm_refine_group(p, 0, 2, 4, None) == 2
+    assert L.bimask_perm_refine_group(p, 1, 4, 4, None) == 3

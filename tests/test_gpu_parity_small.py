@@ -578,3 +578,39 @@ def test_whole_step_recorded_as_a_hip_graph_replays_like_eager_calls(I, J, T, N,
         assert rel_err(Y.float().cpu().numpy().astype(np.float64), oracle.gemm_fwd(synth.to_f64(Xn, dtype), W64, B_o)) <= TOL[dtype]
         assert rel_err(dX.float().cpu().numpy().astype(np.float64),
                        oracle.gemm_bwd(synth.to_f64(dYn, dtype), W64, Bbar_o, perms_h[best_o])) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (4, 8), (1, 16)])
+def test_perm_refine_group_equals_per_layer_calls(N, M):
+    """Many layers refined by one launch (one workgroup each, permutations refined in place) give what the
+    per-layer call gives, which the tests above tie to the oracle; one layer is checked against it here too."""
+    import torch
+    shapes = [(64, 128), (256, 2304 if M == 4 else 640), (512, 96), (4096, 64), (128, 32 * M), (16 * M, 16 * M)] * 12   # 72 layers: two launches
+    rng = np.random.default_rng(1400 + M)
+    entries, want, keep = [], [], []
+    for n, (I, J) in enumerate(shapes):
+        Bo = _mask_with_n_per_group(I, J, N, M, 1401 + n)
+        B = _pack_mask(Bo)
+        P0 = rng.permutation(I).astype(np.int32)
+        S = int(rng.integers(0, 300)) if n % 7 else 0
+        swaps_h = rng.integers(0, I, size=(S, 2)).astype(np.int32)
+        swaps = i32_dev(swaps_h) if S else None
+        if S:
+            out, res = bm.bimask_perm_refine(B, I, J, N, M, swaps, perm=i32_dev(P0))
+        else:
+            out, res = i32_dev(P0), torch.zeros(2, dtype=torch.int32, device="cuda")
+        want.append((out.cpu().numpy(), res.cpu().numpy()))
+        P = i32_dev(P0)
+        result = torch.full((2,), -7, dtype=torch.int32, device="cuda")
+        keep.append((B, P, swaps, result, Bo, P0, swaps_h))
+        entries.append(dict(W=torch.empty((I, J), dtype=torch.bfloat16, device="cuda"), B_bits=B, best_perm=P, swaps=swaps,
+                            refine_result=result))
+    arr = bm.group_layers(entries)
+    bm.bimask_perm_refine_group(arr, N, M)
+    torch.cuda.synchronize()
+    for (B, P, swaps, result, Bo, P0, swaps_h), (wp, wr) in zip(keep, want):
+        assert (P.cpu().numpy() == wp).all()
+        assert (result.cpu().numpy() == wr).all()
+    B, P, swaps, result, Bo, P0, swaps_h = keep[1]
+    P_o, before, after, kept = oracle.perm_refine(Bo, P0, swaps_h, N, M)
+    assert (P.cpu().numpy() == P_o).all() and result.cpu().numpy().tolist() == [after - before, kept]
