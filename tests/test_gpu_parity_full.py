@@ -168,3 +168,23 @@ def test_config2_whole_output_against_float64_matmul():
         g = from_dev_f64(got, L.dtype)
         err = float(np.abs(g - want).max()) / float(np.abs(want).max())
         assert err <= 2e-2, err
+
+
+@pytest.mark.parametrize("cfg,idx,S", [(5, 0, 48), (5, 1, 80), (4, 6, 400)])
+def test_refinement_at_full_size(cfg, idx, S):
+    # the refinement on the real masks of the largest layers (11008 x 4096: 2752 blocks, 128 words per row;
+    # 4096 x 11008: 344 words per row, six passes of the lanes; DeiT fc1 at 1:4), against the oracle's
+    # full recount per proposal; the proposals revisit a few positions so that rounds meet stale evaluations
+    L = synth.get_config(cfg)[idx]
+    Wh = synth.gen_weights(L)
+    W = to_dev(Wh, L.dtype)
+    B = bm.bimask_forward_mask(W, L.N, L.M)
+    B_o = oracle.forward_mask(synth.to_f64(Wh, L.dtype), L.N, L.M)
+    rng = np.random.default_rng([L.seed, 66])
+    P0 = rng.permutation(L.I).astype(np.int32)
+    hot = rng.integers(0, L.I, size=12)
+    swaps = np.stack([rng.choice(hot, size=S), rng.integers(0, L.I, size=S)], axis=1).astype(np.int32)
+    out, res = bm.bimask_perm_refine(B, L.I, L.J, L.N, L.M, i32_dev(swaps), perm=i32_dev(P0))
+    P_o, before, after, kept = oracle.perm_refine(B_o, P0, swaps, L.N, L.M)
+    assert (out.cpu().numpy() == P_o).all()
+    assert res.cpu().numpy().tolist() == [after - before, kept] and kept > 0
