@@ -95,6 +95,14 @@ def perm_scores(B, perms, N: int, M: int) -> np.ndarray:
     return scores
 
 
+def is_permutation(perms) -> np.ndarray:
+    """Sec. 3.3: P is a permutation of the I row indices.  One flag per candidate row (plain definition:
+    sorted, the row reads 0, 1, ..., I-1)."""
+    perms = np.atleast_2d(np.asarray(perms))
+    I = perms.shape[1]
+    return (np.sort(perms, axis=1) == np.arange(I)[None, :]).all(axis=1).astype(np.int32)
+
+
 def perm_refine(B, P, swaps, N: int, M: int):
     """Limitations (future work): hill climbing on Sec. 3.3's objective by proposed exchanges of two
     positions of P, each kept iff the eligible-block count grows.  Returns (P', score before,

@@ -532,3 +532,13 @@ def test_refine_reaches_a_local_optimum_and_never_beats_the_global_one():
     best = max(brute_scores(B, np.array([list(c) + [i for i in range(I) if i not in c]]), N, M)[0]
                for c in itertools.combinations(range(I), 4) if 0 in c)
     assert here <= best
+
+
+def test_is_permutation_by_cases():
+    good = np.array([3, 0, 2, 1])
+    assert oracle.is_permutation(good).tolist() == [1]
+    bad = np.array([[0, 1, 2, 3], [0, 1, 1, 3], [0, 1, 2, 4], [-1, 1, 2, 3], [3, 2, 1, 0]])
+    assert oracle.is_permutation(bad).tolist() == [1, 0, 0, 0, 1]
+    for P in itertools.permutations(range(5)):
+        assert oracle.is_permutation(np.array(P))[0] == 1
+    assert oracle.is_permutation(np.array(list(itertools.product(range(3), repeat=3)))).sum() == 6   # 3! of 27 triples
