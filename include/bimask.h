@@ -179,6 +179,13 @@ BIMASK_API int bimask_sparse_gemm_bwd(const void *dY, int64_t T, int64_t lddy, c
                            int dtype, int N, int M, void *dX, int64_t lddx,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* Debug helper, off the hot path: the search, the backward mask, the backward GEMM and the
+ * refinement trust that what they are given are permutations of 0 .. I-1 (Sec. 3.3: P is a row
+ * permutation) and read rows through them unchecked.  This call checks K candidates:
+ *   perms  in   K x I int32, device;   ok  out  int32[K], device: 1 = a permutation, 0 = a value
+ *   out of range or repeated.   I <= 2^20 (a bitmap of I bits in LDS), else BIMASK_ERR_UNSUPPORTED. */
+BIMASK_API int bimask_check_perms(const int32_t *perms, int K, int64_t I, int32_t *ok, void *stream);
+
 /* Refinement of a permutation by proposed exchanges.  The paper's Limitations leave "a better
  * permutation than a random one" to future work; this is hill climbing on the objective its
  * search already uses (Sec. 3.3 / Alg. 1: the number of (block of M permuted rows, column)

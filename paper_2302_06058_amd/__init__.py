@@ -24,6 +24,7 @@ _SIGNATURES = {
     "bimask_forward_mask": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR]),
     "bimask_forward_mask_compress": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR, _PTR, _PTR]),
     "bimask_perm_search": (_INT, [_PTR, _I64, _I64, _INT, _INT, _PTR, _INT, _PTR, _PTR, _PTR, _PTR, _SZ, _PTR]),
+    "bimask_check_perms": (_INT, [_PTR, _INT, _I64, _PTR, _PTR]),
     "bimask_perm_refine": (_INT, [_PTR, _I64, _I64, _INT, _INT, _PTR, _PTR, _I64, _PTR, _PTR, _PTR]),
     "bimask_backward_mask": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR, _PTR, _PTR]),
     "bimask_backward_mask_compress": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR, _PTR, _PTR, _PTR, _PTR]),
@@ -203,6 +204,19 @@ def bimask_perm_search(B_bits, I: int, J: int, N: int, M: int, perms, scores=Non
                                     _ptr(best_perm), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                     _stream()))
     return scores, best, best_perm
+
+
+def bimask_check_perms(perms, ok=None):
+    """Debug helper: int32[K] of flags, 1 where the candidate is a permutation of 0 .. I-1."""
+    import torch
+    _need_cuda(perms, ok)
+    if perms.dtype != torch.int32 or not perms.is_contiguous() or perms.dim() != 2:
+        raise ValueError("perms must be a contiguous K x I int32 tensor")
+    K, I = perms.shape
+    if ok is None:
+        ok = _empty((K,), torch.int32, perms)
+    _check("bimask_check_perms", lib().bimask_check_perms(_ptr(perms), K, I, _ptr(ok), _stream()))
+    return ok
 
 
 def bimask_perm_refine(B_bits, I: int, J: int, N: int, M: int, swaps, perm=None, perm_out=None, result=None):

@@ -84,6 +84,13 @@ int bimask_perm_search(const uint32_t* B_bits, int64_t I, int64_t J, int N, int 
     return launch_perm_search(B_bits, I, J, N, M, perms, K, scores, best, best_perm, workspace, as_stream(stream));
 }
 
+int bimask_check_perms(const int32_t* perms, int K, int64_t I, int32_t* ok, void* stream) {
+    if (!perms || !ok) return BIMASK_ERR_NULL;
+    if (K <= 0 || I <= 0) return BIMASK_ERR_SHAPE;
+    if (!aligned4(perms) || !aligned4(ok)) return BIMASK_ERR_ALIGN;
+    return launch_check_perms(perms, K, I, ok, as_stream(stream));
+}
+
 int bimask_perm_refine(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perm_in,
                        const int32_t* swaps, int64_t S, int32_t* perm_out, int32_t* result, void* stream) {
     if (!B_bits || !perm_out || !result || (S > 0 && !swaps)) return BIMASK_ERR_NULL;

@@ -144,6 +144,9 @@ int launch_gemm_sp24_narrow(const void* A, const uint32_t* meta, int64_t Adim, i
 int launch_gemm_sp24_rowres(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc,
                             int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, hipStream_t s);
 // true when the backward GEMM needs the gathered copy of g(Y) in the workspace
+// Debug helper: one flag per candidate, 1 = a permutation of 0 .. I-1 (bitmap of I bits in LDS).
+constexpr int64_t kCheckPermsMaxRows = 1 << 20;
+int launch_check_perms(const int32_t* perms, int K, int64_t I, int32_t* ok, hipStream_t s);
 // Refinement of a permutation by proposed exchanges; the permutation lives in LDS.
 constexpr int64_t kRefineMaxRows = 32768;
 int launch_perm_refine(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perm_in,

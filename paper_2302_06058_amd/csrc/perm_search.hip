@@ -12,6 +12,8 @@
 // from HBM about once.  Partial scores per (slice, row range, candidate) go to scratch; a
 // second one-workgroup kernel sums them, takes the arg-max and copies the winning
 // permutation.  Integer only, no atomics: the result is bit-reproducible.
+#include <atomic>
+
 #include "common.hpp"
 
 namespace bimask {
@@ -375,6 +377,49 @@ int launch_perm_search(const uint32_t* B_bits, int64_t I, int64_t J, int N, int 
     if (rc != BIMASK_OK) return rc;
     hipLaunchKernelGGL(k_perm_final, dim3(1), dim3(kFinalThreads), 0, s, partial, pl.ntiles, K, I, perms, scores, best,
                        best_perm);
+    return check_launch();
+}
+
+namespace {
+
+// Debug helper: is every candidate a permutation of 0 .. I-1?  One workgroup per candidate marks the
+// values it meets in an LDS bitmap; a value out of range or met twice clears the candidate's flag.
+__global__ void __launch_bounds__(kThreads)
+k_check_perms(const int32_t* __restrict__ perms, int64_t I, int32_t* __restrict__ ok) {
+    extern __shared__ uint32_t seen[];
+    const int words = static_cast<int>((I + 31) >> 5);
+    for (int w = threadIdx.x; w < words; w += kThreads) seen[w] = 0u;
+    __syncthreads();
+    const int32_t* P = perms + static_cast<int64_t>(blockIdx.x) * I;
+    int bad = 0;
+    for (int64_t r = threadIdx.x; r < I; r += kThreads) {
+        const int32_t v = P[r];
+        if (v < 0 || v >= I) {
+            bad = 1;
+        } else {
+            const uint32_t bit = 1u << (v & 31);
+            if (atomicOr(&seen[v >> 5], bit) & bit) bad = 1;
+        }
+    }
+    bad = __syncthreads_or(bad);
+    if (threadIdx.x == 0) ok[blockIdx.x] = bad ? 0 : 1;
+}
+
+}  // namespace
+
+int launch_check_perms(const int32_t* perms, int K, int64_t I, int32_t* ok, hipStream_t s) {
+    static std::atomic<bool> attr_set{false};
+    if (I > kCheckPermsMaxRows) return BIMASK_ERR_UNSUPPORTED;
+    const size_t lds = static_cast<size_t>((I + 31) >> 5) * 4;
+    if (lds > 48 * 1024 && !attr_set.load(std::memory_order_relaxed)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_check_perms), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                128 * 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            return BIMASK_ERR_HIP;
+        }
+        attr_set.store(true, std::memory_order_relaxed);
+    }
+    hipLaunchKernelGGL(k_check_perms, dim3(static_cast<unsigned>(K)), dim3(kThreads), lds, s, perms, I, ok);
     return check_launch();
 }
 

@@ -68,6 +68,12 @@ def test_workspace_bytes():
     ("bimask_perm_search", (FAKE, 64, 128, 2, 4, FAKE, 4, FAKE, FAKE, None, None, 0, None), 6),
     ("bimask_perm_search", (FAKE, 64, 128, 2, 4, FAKE, 4, FAKE, FAKE, None, FAKE, 8, None), 6),
     ("bimask_perm_search", (FAKE, 64, 128, 2, 4, ctypes.c_void_p(0x1004), 4, FAKE, FAKE, None, FAKE, 1 << 20, None), 7),
+    # debug helper
+    ("bimask_check_perms", (None, 4, 64, FAKE, None), 1),
+    ("bimask_check_perms", (FAKE, 4, 64, None, None), 1),
+    ("bimask_check_perms", (FAKE, 0, 64, FAKE, None), 2),
+    ("bimask_check_perms", (FAKE, 4, (1 << 20) + 1, FAKE, None), 5),
+    ("bimask_check_perms", (ctypes.c_void_p(0x1002), 4, 64, FAKE, None), 7),
     # refinement
     ("bimask_perm_refine", (None, 64, 128, 2, 4, None, FAKE, 10, FAKE, FAKE, None), 1),
     ("bimask_perm_refine", (FAKE, 64, 128, 2, 4, None, None, 10, FAKE, FAKE, None), 1),

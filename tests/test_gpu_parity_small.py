@@ -614,3 +614,17 @@ def test_perm_refine_group_equals_per_layer_calls(N, M):
     B, P, swaps, result, Bo, P0, swaps_h = keep[1]
     P_o, before, after, kept = oracle.perm_refine(Bo, P0, swaps_h, N, M)
     assert (P.cpu().numpy() == P_o).all() and result.cpu().numpy().tolist() == [after - before, kept]
+
+
+@pytest.mark.parametrize("I,K", [(64, 9), (1000, 5), (11008, 6), (100000, 3), (1 << 20, 2)])
+def test_check_perms_flags(I, K):
+    rng = np.random.default_rng(1500 + K)
+    perms = np.stack([rng.permutation(I) for _ in range(K)]).astype(np.int32)
+    perms[1, I // 3] = perms[1, I // 2]                     # a repeated value
+    if K > 2:
+        perms[2, I - 1] = I                                 # out of range
+    if K > 4:
+        perms[4, 0] = -1
+    ok = bm.bimask_check_perms(i32_dev(perms))
+    assert (ok.cpu().numpy() == oracle.is_permutation(perms)).all()
+    assert ok.cpu().numpy().tolist()[:2] == [1, 0]
