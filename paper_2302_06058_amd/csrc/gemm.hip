@@ -68,8 +68,21 @@ k_gemm_dense_bf16(const uint16_t* __restrict__ A, int64_t Adim, int64_t K, const
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WAVES_M, wn = wave / WAVES_M;
     const int l32 = lane & 31, h = lane >> 5;
-    const int64_t a0 = static_cast<int64_t>(blockIdx.x % tiles_a) * BM;
-    const int64_t t0 = static_cast<int64_t>(blockIdx.x / tiles_a) * BN;
+    // Tile order as in the 2:4 kernel: workgroup ids are dealt round-robin to the 8 XCDs, so XCD x takes a
+    // contiguous chunk of a sequence in which 8 token tiles x all weight tiles run side by side and share
+    // that XCD's L2.
+    constexpr int kGroupT = 8;
+    const int64_t tiles_t = ceil_div(T, BN);
+    const int64_t total = tiles_t * tiles_a;
+    const int64_t per_xcd = ceil_div(total, 8);
+    const int64_t n = static_cast<int64_t>(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (n >= total) return;
+    const int64_t grp = n / (static_cast<int64_t>(kGroupT) * tiles_a);
+    const int64_t first_t = grp * kGroupT;
+    const int64_t gsz = (tiles_t - first_t) < kGroupT ? (tiles_t - first_t) : kGroupT;
+    const int64_t within = n - grp * kGroupT * tiles_a;
+    const int64_t a0 = (within / gsz) * BM;
+    const int64_t t0 = (first_t + within % gsz) * BN;
     const int nk = static_cast<int>(ceil_div(K, BK));
 
     constexpr int NB_ = BN * 8 / kThreads, NA_ = BM * 8 / kThreads;   // 16-byte granules per thread
@@ -384,7 +397,7 @@ int run_dense_t(const void* A, int64_t Adim, int64_t K, const void* Bm, int64_t 
     const bool vecC = aligned16(C) && (ldc * 2) % 16 == 0;
     const int tiles_a = static_cast<int>(ceil_div(Adim, BM));
     const int64_t tiles_t = ceil_div(T, BN);
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(tiles_a * tiles_t)), dim3(kThreads), S::kTotal, s,
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(ceil_div(tiles_a * tiles_t, 8) * 8)), dim3(kThreads), S::kTotal, s,
                        static_cast<const uint16_t*>(A), Adim, K, static_cast<const uint16_t*>(Bm), T, ldb,
                        static_cast<uint16_t*>(C), ldc, tiles_a, vecA, vecB, vecC);
     return check_launch();
