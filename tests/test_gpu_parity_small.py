@@ -628,3 +628,12 @@ def test_check_perms_flags(I, K):
     ok = bm.bimask_check_perms(i32_dev(perms))
     assert (ok.cpu().numpy() == oracle.is_permutation(perms)).all()
     assert ok.cpu().numpy().tolist()[:2] == [1, 0]
+
+
+@pytest.mark.parametrize("I,J,N,M", [(4, 131072, 2, 4), (131072, 4, 2, 4), (16, 65536, 1, 16), (65536, 16, 1, 16),
+                                     (8, 100000, 4, 8), (100000, 8, 4, 8)])
+def test_extreme_aspect_ratios(I, J, N, M):
+    # one block of permuted rows against very long rows, and the transpose of that: the row / column
+    # tilings of every kernel meet their smallest and their longest dimension (few tokens: the GEMMs are
+    # here for their indexing, not their speed)
+    check_layer(I=I, J=J, N=N, M=M, dtype=synth.BF16, K=3, seed=1600 + M, T=9)
