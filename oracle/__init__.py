@@ -36,10 +36,10 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB):
-            build()
+        build()                                   # compiles when the library is missing or older than its source
         _lib = ctypes.CDLL(_LIB)
         _lib.oracle_argmax.restype = ctypes.c_int
+        _lib.oracle_relative_gap.restype = ctypes.c_double
     return _lib
 
 
@@ -238,6 +238,36 @@ def gemm_bwd(dY, W, Bbar, P) -> np.ndarray:
         return dY @ (W * Bbar)
     P = np.asarray(P, dtype=np.int64)
     return dY[:, P] @ (W[P, :] * Bbar)
+
+
+# ---------------------------------------------------------------- gradient gap (Eq. 5 vs Eq. 10)
+def grad_exact_loops(dY, W, B) -> np.ndarray:
+    """Eq. (5): g(X) = g(Y) (B .* W), triple loop.  Small sizes only."""
+    dY, W, B = _f64(dY), _f64(W), _u8(B)
+    T, I = dY.shape
+    J = W.shape[1]
+    gX = np.empty((T, J), dtype=np.float64)
+    _load().oracle_grad_exact(_p(dY), _p(W), _p(B), ctypes.c_int64(T), ctypes.c_int64(I), ctypes.c_int64(J), _p(gX))
+    return gX
+
+
+def grad_exact(dY, W, B) -> np.ndarray:
+    """Eq. (5) as a float64 library matmul on the dense forward-masked weights."""
+    return _f64(dY) @ (_f64(W) * _u8(B))
+
+
+def relative_gap(approx, exact) -> float:
+    """||approx - exact||_F / ||exact||_F for two T x J gradients (Sec. 3.3's gradient gap)."""
+    approx, exact = _f64(approx), _f64(exact)
+    assert approx.shape == exact.shape
+    return float(_load().oracle_relative_gap(_p(approx), _p(exact), ctypes.c_int64(approx.size)))
+
+
+def gradient_gap(dY, W, B, P, N: int, M: int) -> float:
+    """Gap between Eq. (10)'s g-bar(X), with the backward mask of Eq. (11) for permutation P (None =
+    identity: Eq. (8) with Eq. (9)), and Eq. (5)'s g(X)."""
+    Bbar, _ = backward_mask(W, B, P, N, M)
+    return relative_gap(gemm_bwd(dY, W, Bbar, P), grad_exact(dY, W, B))
 
 
 # ---------------------------------------------------------------- whole step

@@ -253,6 +253,34 @@ void oracle_gemm_bwd(const double *dY, const double *W, const uint8_t *Bbar, con
         }
 }
 
+/* Eq. (5), the exact input gradient the approximation of Eq. (8)/(10) stands in for:
+ *   g(X)[t][j] = sum_i g(Y)[t][i] * (B .* W)[i][j]     (the paper writes (B .* W)^T * g(Y)). */
+void oracle_grad_exact(const double *dY, const double *W, const uint8_t *B,
+                       int64_t T, int64_t I, int64_t J, double *gX)
+{
+    for (int64_t t = 0; t < T; ++t)
+        for (int64_t j = 0; j < J; ++j) {
+            double acc = 0.0;
+            for (int64_t i = 0; i < I; ++i)
+                if (B[i * J + j]) acc += dY[t * I + i] * W[i * J + j];
+            gX[t * J + j] = acc;
+        }
+}
+
+/* Gradient gap (Sec. 3.3: what the permutation is chosen to shrink): the Frobenius norm of
+ * approx - exact over the Frobenius norm of exact, both T x J.  0 / 0 counts as 0. */
+double oracle_relative_gap(const double *approx, const double *exact, int64_t n)
+{
+    double num = 0.0, den = 0.0;
+    for (int64_t q = 0; q < n; ++q) {
+        double d = approx[q] - exact[q];
+        num += d * d;
+        den += exact[q] * exact[q];
+    }
+    if (den == 0.0) return num == 0.0 ? 0.0 : INFINITY;
+    return sqrt(num / den);
+}
+
 /* The same two sums evaluated only at listed output coordinates (for sizes where
  * the full triple loop would take minutes). */
 void oracle_gemm_fwd_at(const double *X, const double *W, const uint8_t *B,

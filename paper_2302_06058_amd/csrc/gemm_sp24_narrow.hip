@@ -48,8 +48,9 @@ k_gemm_sp24_narrow(const uint16_t* __restrict__ A_all, const uint32_t* __restric
     const int split = (static_cast<int>(blockIdx.x) >> 3) % nsplit;
     const int64_t wave_id = ((static_cast<int64_t>(blockIdx.x) >> 3) / nsplit) * 8 + (blockIdx.x & 7);
     const int64_t nwaves = gridDim.x / nsplit;
-    const uint16_t* __restrict__ A = A_all + static_cast<int64_t>(split) * TM * NSTG * 2048;
-    const uint32_t* __restrict__ Ameta = Ameta_all + static_cast<int64_t>(split) * TM * NSTG * 128;
+    // row tiles of this split; the last split may own fewer than TM (7 row tiles over 2 x 4): its
+    // surplus tiles re-read the operand's last row tile (loaded, never stored)
+    const int rt_last = (Adim_all + 31) / 32 - 1;
     uint16_t* __restrict__ C = C_all + split * TM * 32;
     const int Adim = Adim_all - split * TM * 32 < TM * 32 ? Adim_all - split * TM * 32 : TM * 32;
     // q / G == (q * invG) >> 22 for q < 64, G <= 64
@@ -94,8 +95,9 @@ k_gemm_sp24_narrow(const uint16_t* __restrict__ A_all, const uint32_t* __restric
     u32x2 rmeta[NSTG][TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const uint16_t* pa = A + (static_cast<int64_t>(i) * NSTG * 256 + lane0) * 8;
-        const uint32_t* pm = Ameta + (static_cast<int64_t>(i) * NSTG * 64 + lane0) * 2;
+        const int rt = split * TM + i < rt_last ? split * TM + i : rt_last;
+        const uint16_t* pa = A_all + (static_cast<int64_t>(rt) * NSTG * 256 + lane0) * 8;
+        const uint32_t* pm = Ameta_all + (static_cast<int64_t>(rt) * NSTG * 64 + lane0) * 2;
 #pragma unroll
         for (int st = 0; st < NSTG; ++st) {
 #pragma unroll

@@ -542,3 +542,71 @@ def test_is_permutation_by_cases():
     for P in itertools.permutations(range(5)):
         assert oracle.is_permutation(np.array(P))[0] == 1
     assert oracle.is_permutation(np.array(list(itertools.product(range(3), repeat=3)))).sum() == 6   # 3! of 27 triples
+
+
+# ---------------------------------------------------------------------------------------------
+# Eq. (5): exact input gradient, and the gap of Eq. (10)'s approximation to it (Sec. 3.3)
+# ---------------------------------------------------------------------------------------------
+def test_grad_exact_is_the_masked_matmul():
+    rng = np.random.default_rng(2101)
+    T, I, J = 9, 12, 20
+    W = rng.standard_normal((I, J))
+    dY = rng.standard_normal((T, I))
+    B = oracle.forward_mask(W, 2, 4)
+    want = dY @ (W * B)                                   # g(Y) (B .* W): the plain definition
+    assert np.allclose(oracle.grad_exact_loops(dY, W, B), want, rtol=0, atol=1e-12)
+    assert np.allclose(oracle.grad_exact(dY, W, B), want, rtol=0, atol=1e-12)
+    # a one-hot g(Y) reads back row i of the masked weights; a transposed operand would read a column
+    e = np.zeros((1, I)); e[0, 5] = 1.0
+    assert (oracle.grad_exact_loops(e, W, B)[0] == (W * B)[5]).all()
+
+
+def test_gradient_gap_hand_case():
+    vals = {}
+    with open(os.path.join(GOLDEN, "gradient_gap_hand_case.txt")) as f:
+        for line in f:
+            if line.startswith("#") or "|" not in line:
+                continue
+            k, v = line.split("|")
+            vals[k.strip()] = np.array([float(x) for x in v.split()])
+    W = np.array([[4, 3, 1, 0], [2, 0, 5, 1], [1, 0, 2, 6], [3, 1, 0, 2]], dtype=np.float64)
+    B = oracle.forward_mask(W, 2, 4)
+    assert B.tolist() == [[1, 1, 0, 0], [1, 0, 1, 0], [0, 0, 1, 1], [1, 0, 0, 1]]
+    dY = np.ones((1, 4))
+    Bbar, _ = oracle.backward_mask(W, B, None, 2, 4)
+    assert (oracle.grad_exact_loops(dY, W, B)[0] == vals["exact"]).all()
+    assert (oracle.gemm_bwd_loops(dY, W, Bbar, None)[0] == vals["approx"]).all()
+    want = float(vals["gap_num"][0]) / np.sqrt(float(vals["gap_den2"][0]))
+    assert abs(oracle.gradient_gap(dY, W, B, None, 2, 4) - want) < 1e-15
+    e0 = np.array([[1.0, 0, 0, 0]])
+    assert oracle.gradient_gap(e0, W, B, None, 2, 4) == 0.0
+
+
+@pytest.mark.parametrize("N,M", NMS)
+def test_gradient_gap_is_zero_when_every_block_is_eligible(N, M):
+    # every column block of B[P,:] already holds at most N ones -> Bbar == B[P,:] (Sec. 3.3, motivation 1)
+    # -> Eq. (10) reproduces Eq. (5) exactly, whatever P is
+    rng = np.random.default_rng(2200 + M)
+    I, J, T = 4 * M, 6 * M, 5
+    B = np.zeros((I, J), dtype=np.uint8)
+    P = rng.permutation(I).astype(np.int32)
+    for k in range(I // M):
+        for l in range(J):
+            on = rng.choice(M, size=rng.integers(0, N + 1), replace=False)
+            B[P[k * M + on], l] = 1
+    W = rng.standard_normal((I, J))
+    dY = rng.standard_normal((T, I))
+    assert oracle.perm_scores(B, P, N, M)[0] == (I // M) * J
+    assert oracle.gradient_gap(dY, W, B, P, N, M) < 1e-14
+    # and it is positive as soon as one block loses an entry
+    B2 = B.copy()
+    B2[P[:M], 0] = 1
+    assert oracle.gradient_gap(dY, W, B2, P, N, M) > 1e-6
+
+
+def test_relative_gap_definition():
+    rng = np.random.default_rng(2301)
+    a, b = rng.standard_normal((7, 5)), rng.standard_normal((7, 5))
+    assert abs(oracle.relative_gap(a, b) - np.linalg.norm(a - b) / np.linalg.norm(b)) < 1e-14
+    assert oracle.relative_gap(b, b) == 0.0
+    assert oracle.relative_gap(np.zeros((2, 2)), np.zeros((2, 2))) == 0.0
