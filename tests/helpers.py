@@ -75,3 +75,37 @@ def untile24(values: np.ndarray, index: np.ndarray, rows: int, cols: int):
         pad_zero = pad_zero and bool(((xr[:, -1] >> np.uint32(tail_bits)) == 0).all())
     pad_zero = pad_zero and bool((x[:rows, wv:] == 0).all())
     return v[:rows, :cols // 2], xr, pad_zero
+
+
+class GemmError:
+    """Running comparison of a GEMM output with its float64 reference, fed chunk by chunk.
+
+    rel      max|got - ref| / max|ref| over everything seen (the stated tolerance is on this figure)
+    excess   max over the elements of |got - ref| / bound, with the element's own rounding budget
+                 bound = 2^-8 |ref| + 8 sqrt(K) 2^-24 S + tiny,   S = sum_k |a_k| |b_k|
+             (bf16 keeps 8 significant bits, so rounding to nearest errs by at most half a unit in the
+             last place = 2^-8 |value|: the first term has no slack, a truncating conversion would show
+             as excess 2; fp32 accumulation of K terms errs by about sqrt(K) 2^-24 S, allowed 8 times
+             that).  A single dropped or misplaced product is about S / K and shows as excess > 1 for
+             the lengths used here; for fp32 outputs (24 significant bits) the first term is 2^-23 |ref|.
+    """
+
+    def __init__(self, K: int, out_bits: int = 8):
+        self.K, self.out_bits = K, out_bits
+        self.max_err = self.max_ref = self.excess = 0.0
+        self.n = 0
+
+    def add(self, got: np.ndarray, ref: np.ndarray, S: np.ndarray):
+        err = np.abs(got - ref)
+        self.max_err = max(self.max_err, float(err.max()))
+        self.max_ref = max(self.max_ref, float(np.abs(ref).max()))
+        bound = np.abs(ref) * 2.0 ** -self.out_bits + S * (8.0 * np.sqrt(self.K) * 2.0 ** -24) + 1e-300
+        self.excess = max(self.excess, float((err / bound).max()))
+        self.n += got.size
+
+    @property
+    def rel(self) -> float:
+        return self.max_err / (self.max_ref if self.max_ref > 0 else 1.0)
+
+    def __repr__(self):
+        return f"rel {self.rel:.2e} excess {self.excess:.2f} over {self.n} outputs"

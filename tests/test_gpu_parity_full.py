@@ -2,13 +2,15 @@
 
 Masks, compressed operands, candidate scores and the chosen permutation are compared bit
 for bit with the CPU oracle over the whole layer.  The GEMM outputs are compared on a
-sample of output coordinates (64 token rows x 64 output columns) that the oracle computes
-one by one in float64, plus a whole-output sanity check (finite, right shape).  Candidate
+sample of output coordinates (64 token rows x 64 output columns) that the oracle's plain
+loops compute one by one in float64, and then element by element over the WHOLE output with
+the oracle's float64 library matmul (in token chunks), both against the stated tolerance and
+against each element's own rounding budget (helpers.GemmError).  Candidate
 scores of the two largest matrices are compared on a sample of the candidates (the oracle
 needs K*I*J steps); the arg-max is always checked against the GPU's own full score vector.
-Layers with very many tokens are run on their first 16384 tokens (the weight-side work,
-which is what differs between layers, is always full size); config 2 -- the configuration
-the benchmark times -- runs at its full token count.
+Here layers with very many tokens are run on their first 16384 tokens (the weight-side work
+is always full size); test_gpu_parity_bigtokens.py runs those layers' GEMMs at their full
+token counts.
 """
 import numpy as np
 import pytest
@@ -16,7 +18,7 @@ import pytest
 import oracle
 import paper_2302_06058_amd as bm
 from paper_2302_06058_amd import synth
-from helpers import to_dev, i32_dev, words, from_dev_f64, raw_bits, f64_to_raw, untile24
+from helpers import to_dev, i32_dev, words, from_dev_f64, raw_bits, f64_to_raw, untile24, GemmError
 
 pytestmark = pytest.mark.gpu
 
@@ -126,6 +128,22 @@ def check_full_layer(layer, t_cap=T_CAP, full_scores_limit=4e8):
     ex = sampled_rel_err(dX, dt, ref_bwd, T, J, L.seed + 12)
     assert ey <= TOL[dt], f"{L.name}: forward GEMM rel err {ey}"
     assert ex <= TOL[dt], f"{L.name}: backward GEMM rel err {ex}"
+
+    # every output element against the float64 library matmul on the dense masked weights, in token chunks
+    chunk = max(256, min(T, (1 << 27) // max(I, J)))
+    Wf64 = W64 * B_o
+    Wb64 = np.ascontiguousarray((W64[P, :] * Bbar_o).T)
+    aWf, aWb = np.abs(Wf64).astype(np.float32), np.abs(Wb64).astype(np.float32)
+    bits = 8 if dt == synth.BF16 else 23
+    wy, wx = GemmError(J, bits), GemmError(I, bits)
+    for c0 in range(0, T, chunk):
+        x64 = synth.to_f64(Xh[c0:c0 + chunk], dt)
+        wy.add(from_dev_f64(Y[c0:c0 + chunk], dt), x64 @ Wf64.T, (np.abs(x64).astype(np.float32) @ aWf.T).astype(np.float64))
+        g64 = synth.to_f64(dYh[c0:c0 + chunk][:, P], dt)
+        wx.add(from_dev_f64(dX[c0:c0 + chunk], dt), g64 @ Wb64.T, (np.abs(g64).astype(np.float32) @ aWb.T).astype(np.float64))
+    print(f"  {L.name}: whole output Y {wy}; dX {wx}", flush=True)
+    assert wy.rel <= TOL[dt] and wx.rel <= TOL[dt], (L.name, wy, wx)
+    assert wy.excess <= 1.0 and wx.excess <= 1.0, (L.name, wy, wx)
 
 
 def test_config1_full():
