@@ -637,3 +637,31 @@ def test_extreme_aspect_ratios(I, J, N, M):
     # tilings of every kernel meet their smallest and their longest dimension (few tokens: the GEMMs are
     # here for their indexing, not their speed)
     check_layer(I=I, J=J, N=N, M=M, dtype=synth.BF16, K=3, seed=1600 + M, T=9)
+
+
+@pytest.mark.parametrize("I,J,T,N,M", [(256, 384, 300, 2, 4), (128, 192, 200, 1, 4), (192, 256, 260, 4, 8)])
+def test_gradient_gap_against_the_oracle(I, J, T, N, M):
+    """Sec. 3.3's gradient gap ||g-bar(X) - g(X)|| / ||g(X)||: g-bar(X) of Eq. (10) from the library's masks, search
+    and backward GEMM, against the oracle's float64 gap for the same permutation; g(X) is Eq. (5) from the oracle.
+    For the identity and for the search's winner; the two must agree to 1e-2 relative (bf16 outputs)."""
+    dtype = synth.BF16
+    Wh = make_w(I, J, dtype, 5001)
+    W64 = synth.to_f64(Wh, dtype)
+    r = np.random.default_rng(5002)
+    dYh = synth.store(r.standard_normal((T, I), dtype=np.float32), dtype)
+    dY64 = synth.to_f64(dYh, dtype)
+    perms = perms_of(I, 16, 5003)
+    W, dY = to_dev(Wh, dtype), to_dev(dYh, dtype)
+    B = bm.bimask_forward_mask(W, N, M)
+    B_o = oracle.forward_mask(W64, N, M)
+    exact = oracle.grad_exact(dY64, W64, B_o)
+    scores, best, P = bm.bimask_perm_search(B, I, J, N, M, i32_dev(perms))
+    gaps = []
+    for P_d, P_h in ((None, None), (P, perms[int(best.item())])):
+        Bbar, vb, ib = bm.bimask_backward_mask_compress(W, N, M, B, P_d)
+        approx = from_dev_f64(bm.bimask_sparse_gemm_bwd(dY, P_d, vb, ib, I, J, N, M), dtype)
+        got = oracle.relative_gap(approx, exact)
+        want = oracle.gradient_gap(dY64, W64, B_o, P_h, N, M)
+        assert 0.05 < want < 1.0                          # a real gap: these masks drop entries
+        assert abs(got - want) <= 1e-2 * want, (got, want)
+        gaps.append(want)
