@@ -42,6 +42,10 @@ def test_argument_validation_under_host_sanitizers(tmp_path):
             run([hipcc] + b.FLAGS + (san if s == "api.hip" else []) + ["-O1", "-g", "-c", os.path.join(b.CSRC, s), "-o", o])
         objs.append(o)
     exe = str(tmp_path / "api_san")
-    run([hipcc, "--offload-arch=gfx950", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
-         "-I", os.path.join(ROOT, "include"), "-x", "c++", os.path.join(HERE, "api_driver.cpp"), "-x", "none"] + objs + ["-o", exe])
+    # the driver is plain host C++: compiled and linked by the host compiler against the HIP runtime library
+    drv = str(tmp_path / "api_driver.o")
+    host = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all"]
+    run(["g++", "-O1", "-g", "-std=c++17"] + host + ["-I", os.path.join(ROOT, "include"), "-c", os.path.join(HERE, "api_driver.cpp"), "-o", drv])
+    rocm_lib = os.path.join(os.path.dirname(os.path.dirname(os.path.realpath(hipcc))), "lib")
+    run(["g++"] + host + [drv] + objs + ["-L", rocm_lib, "-Wl,-rpath," + rocm_lib, "-lamdhip64", "-o", exe])
     assert "clean" in run([exe], env=ENV)
