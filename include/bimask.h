@@ -132,6 +132,22 @@ BIMASK_API int bimask_perm_search(const uint32_t *B_bits, int64_t I, int64_t J, 
                        const int32_t *perms, int K, int32_t *scores, int32_t *best, int32_t *best_perm,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* bimask_perm_search for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus the
+ * workspace) and bit-identical results; the partial scores live in a static device array of
+ * BIMASK_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the process ends).
+ *   - bimask_workspace_bytes(BIMASK_WS_PERM_SEARCH, ...) above that size: BIMASK_ERR_WORKSPACE,
+ *     nothing is launched.
+ *   - Calls no hipMalloc / hipFree and no allocating routine; the array's address is looked up
+ *     (hipGetSymbolAddress) at the first call on each device, so make that first call outside a
+ *     graph capture.
+ *   - All calls on one GPU share the array: two calls that overlap in time on one GPU (different
+ *     streams, or graphs replayed concurrently) race.  Calls on one stream are ordered and safe.   */
+#define BIMASK_STATIC_SCRATCH_BYTES (1u << 20)
+BIMASK_API int bimask_perm_search_static(const uint32_t *B_bits, int64_t I, int64_t J, int N, int M,
+                              const int32_t *perms, int K, int32_t *scores, int32_t *best, int32_t *best_perm,
+                              void *stream);
+
 /* Backward mask, Eq. (11); with perm = NULL (identity) it is Eq. (9).  For every column
  * and every block of M consecutive permuted rows: rank the magnitudes of
  * (B .* W)[P[r], l], select the top N (lowest r first among equals) and AND the selection

@@ -24,6 +24,7 @@ _SIGNATURES = {
     "bimask_forward_mask": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR]),
     "bimask_forward_mask_compress": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR, _PTR, _PTR]),
     "bimask_perm_search": (_INT, [_PTR, _I64, _I64, _INT, _INT, _PTR, _INT, _PTR, _PTR, _PTR, _PTR, _SZ, _PTR]),
+    "bimask_perm_search_static": (_INT, [_PTR, _I64, _I64, _INT, _INT, _PTR, _INT, _PTR, _PTR, _PTR, _PTR]),
     "bimask_check_perms": (_INT, [_PTR, _INT, _I64, _PTR, _PTR]),
     "bimask_perm_refine": (_INT, [_PTR, _I64, _I64, _INT, _INT, _PTR, _PTR, _I64, _PTR, _PTR, _PTR]),
     "bimask_backward_mask": (_INT, [_PTR, _I64, _I64, _I64, _INT, _INT, _INT, _PTR, _PTR, _PTR, _PTR]),
@@ -203,6 +204,19 @@ def bimask_perm_search(B_bits, I: int, J: int, N: int, M: int, perms, scores=Non
            lib().bimask_perm_search(_ptr(B_bits), I, J, N, M, _ptr(perms), K, _ptr(scores), _ptr(best),
                                     _ptr(best_perm), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                     _stream()))
+    return scores, best, best_perm
+
+
+def bimask_perm_search_static(B_bits, I: int, J: int, N: int, M: int, perms, scores, best, best_perm=None):
+    """bimask_perm_search without a workspace and without any allocation: every output is the caller's."""
+    import torch
+    _need_cuda(B_bits, perms, scores, best, best_perm)
+    K = perms.shape[0]
+    if perms.dtype != torch.int32 or not perms.is_contiguous() or perms.shape[1] != I:
+        raise ValueError("perms must be a contiguous K x I int32 tensor")
+    _check("bimask_perm_search_static",
+           lib().bimask_perm_search_static(_ptr(B_bits), I, J, N, M, _ptr(perms), K, _ptr(scores), _ptr(best),
+                                           _ptr(best_perm), _stream()))
     return scores, best, best_perm
 
 

@@ -84,6 +84,17 @@ int bimask_perm_search(const uint32_t* B_bits, int64_t I, int64_t J, int N, int 
     return launch_perm_search(B_bits, I, J, N, M, perms, K, scores, best, best_perm, workspace, as_stream(stream));
 }
 
+int bimask_perm_search_static(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perms, int K,
+                              int32_t* scores, int32_t* best, int32_t* best_perm, void* stream) {
+    if (!B_bits || !perms || !scores || !best) return BIMASK_ERR_NULL;
+    if (int rc = check_nm(N, M)) return rc;
+    if (I <= 0 || J <= 0 || K <= 0 || I % M || J % M) return BIMASK_ERR_SHAPE;
+    if (I > 0x7FFFFFFFll || J > 0x7FFFFFFFll) return BIMASK_ERR_SHAPE;
+    if ((I / M) * J > 0x7FFFFFFFll) return BIMASK_ERR_SHAPE;       // a score must fit int32
+    if (!aligned16(perms)) return BIMASK_ERR_ALIGN;
+    return launch_perm_search_static(B_bits, I, J, N, M, perms, K, scores, best, best_perm, as_stream(stream));
+}
+
 int bimask_check_perms(const int32_t* perms, int K, int64_t I, int32_t* ok, void* stream) {
     if (!perms || !ok) return BIMASK_ERR_NULL;
     if (K <= 0 || I <= 0) return BIMASK_ERR_SHAPE;

@@ -114,6 +114,11 @@ PermPlan plan_perm_search(int64_t I, int64_t J, int K, int M);
 int launch_perm_search(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perms, int K,
                        int32_t* scores, int32_t* best, int32_t* best_perm, void* ws, hipStream_t s);
 
+// the same search with its partial scores in the library's static device array (no workspace argument)
+size_t perm_search_static_capacity();
+int launch_perm_search_static(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perms, int K,
+                              int32_t* scores, int32_t* best, int32_t* best_perm, hipStream_t s);
+
 // grouped variants: n independent layers, few launches (see include/bimask.h); the per-layer argument
 // tables travel in the kernel arguments (kept below 4 KB): this many layers per launch for an entry of
 // `entry_bytes` plus a 4-byte first-workgroup index

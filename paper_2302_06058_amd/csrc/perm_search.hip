@@ -380,6 +380,34 @@ int launch_perm_search(const uint32_t* B_bits, int64_t I, int64_t J, int N, int 
     return check_launch();
 }
 
+// ---- the search for callers that cannot allocate: partial scores in a static device array --------
+// One copy of the array exists per GPU the library runs on, for the life of the process.  In host
+// code the array's name is only a handle for hipGetSymbolAddress: the address the kernels get is
+// looked up once per device, with that device current, and remembered.
+constexpr size_t kStaticScratchBytes = BIMASK_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+size_t perm_search_static_capacity() { return kStaticScratchBytes; }
+
+int launch_perm_search_static(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perms, int K,
+                              int32_t* scores, int32_t* best, int32_t* best_perm, hipStream_t s) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> device_ptr[kMaxDevices];       // zero-initialised: not looked up yet
+    if (plan_perm_search(I, J, K, M).ws_bytes > kStaticScratchBytes) return BIMASK_ERR_WORKSPACE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BIMASK_ERR_HIP;
+    void* ptr = device_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return BIMASK_ERR_HIP;
+        }
+        device_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    // every partial score the second kernel reads is written by the first: nothing to clear
+    return launch_perm_search(B_bits, I, J, N, M, perms, K, scores, best, best_perm, ptr, s);
+}
+
 namespace {
 
 // Debug helper: is every candidate a permutation of 0 .. I-1?  One workgroup per candidate marks the

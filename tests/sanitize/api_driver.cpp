@@ -49,6 +49,10 @@ int main() {
     EXPECT(bimask_perm_search(U, 64, 128, 2, 4, reinterpret_cast<int32_t*>(buf + 4), 4, P, P, nullptr, F, 1 << 20, nullptr), BIMASK_ERR_ALIGN);
     EXPECT(bimask_perm_search(U, int64_t(1) << 30, int64_t(1) << 20, 2, 4, P, 4, P, P, nullptr, F, 1 << 20, nullptr), BIMASK_ERR_SHAPE);
 
+    EXPECT(bimask_perm_search_static(U, 64, 128, 2, 4, nullptr, 4, P, P, nullptr, nullptr), BIMASK_ERR_NULL);
+    EXPECT(bimask_perm_search_static(U, 64, 128, 2, 5, P, 4, P, P, nullptr, nullptr), BIMASK_ERR_NM);
+    EXPECT(bimask_perm_search_static(U, 8, int64_t(1) << 22, 2, 4, P, 100, P, P, nullptr, nullptr), BIMASK_ERR_WORKSPACE);
+
     EXPECT(bimask_check_perms(nullptr, 4, 64, P, nullptr), BIMASK_ERR_NULL);
     EXPECT(bimask_check_perms(P, 0, 64, P, nullptr), BIMASK_ERR_SHAPE);
     EXPECT(bimask_check_perms(P, 4, (1 << 20) + 1, P, nullptr), BIMASK_ERR_UNSUPPORTED);
