@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbimask.so")
-SOURCES = ["api.hip", "mask_kernels.hip", "perm_search.hip", "perm_refine.hip", "gemm.hip", "gemm_sp24.hip",
+SOURCES = ["api.hip", "mask_kernels.hip", "perm_search.hip", "perm_refine.hip", "gemm.hip", "gemm_sp24.hip", "gemm_sp24_big.hip",
            "gemm_sp24_resident.hip", "gemm_sp24_narrow.hip", "gemm_sp24_rowres.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

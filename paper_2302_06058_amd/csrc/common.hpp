@@ -138,6 +138,11 @@ enum class Sp24Tile { k256x64, k128x64, k256x128, k64x64 };
 int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
                      int64_t ldb, void* C, int64_t ldc, Sp24Tile tile, hipStream_t s);
 
+// large problems (thousands of weight rows and tokens): 512 x 128 tiles; BIMASK_ERR_UNSUPPORTED otherwise
+bool gemm_sp24_big_shape(int64_t Adim, int64_t K, int64_t T);
+int launch_gemm_sp24_big(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
+                         int64_t ldb, void* C, int64_t ldc, hipStream_t s);
+
 int launch_gemm_sp24_resident(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc,
                               int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc,
                               hipStream_t s);

@@ -488,6 +488,11 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
                 if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
             }
         }
+        // the largest problems: 512 x 128 tiles, wavefronts of 64 x 128 (fewest L2 and LDS bytes per matrix instruction)
+        if (gemm_sp24_big_shape(Adim, K, T)) {
+            const int rc = launch_gemm_sp24_big(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, s);
+            if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
+        }
         // large problems: 256 x 128 tiles on 8 wavefronts (half the weight traffic per token);
         // otherwise 256 x 64 tiles so that the grid still covers the chip; weight dimensions that
         // would leave a fifth or more of the 256-row tiles empty (384 = 1.5 tiles) take 128-row tiles
