@@ -116,11 +116,15 @@ class LayerRun:
         self.c_gemm_bwd = [bm.prepare("bimask_sparse_gemm_bwd", self.dY[r], T, I, self.P, self.vb, self.xb, I, J,
                                       self.dt, N, M, self.dX[r], J, self.ws_bwd, nbytes(self.ws_bwd), st)
                            for r in range(copies)]
+        # Order of one step: the three weight-side stages first, then the two GEMMs.  Alg. 1 lists the forward
+        # GEMM before the search and the backward mask, but those two depend on W and B only, not on the forward
+        # output, so they may run right after the forward mask -- while W and B are still in the last-level
+        # cache instead of behind the GEMM's output.
         self.stages = [
             ("forward_mask_compress", self.s_fwd_mask),
-            ("sparse_gemm_fwd", self.s_gemm_fwd),
             ("perm_search", self.s_perm),
             ("backward_mask_compress", self.s_bwd_mask),
+            ("sparse_gemm_fwd", self.s_gemm_fwd),
             ("sparse_gemm_bwd", self.s_gemm_bwd),
         ]
 

@@ -15,9 +15,15 @@
 //   * the weight fragments of a stage are not double-buffered as a whole: the registers of sub-step
 //     s4 are re-loaded with the NEXT stage's fragment as soon as the sub-step's matrix instructions
 //     have been issued (one stage of distance at 32 + 8 registers instead of 72);
-//   * token fragments are read one 32-token sub-tile ahead of the matrix instructions that use them.
-// Tiles of 512 x 64 (TN = 2) close the grid: the last, partial round of workgroups over the chip
-// works on half tiles so that no CU idles for more than half a tile.
+//   * the token tile of the next stage goes from registers to the other LDS buffer in the middle of
+//     the current stage's matrix instructions, so one barrier is all that separates two stages;
+//   * token fragments are read three 32-token sub-tiles ahead of the matrix instructions that use them.
+// Measured on the MLP block (11008 x 4096 and 4096 x 11008 weights, 8192 tokens): 1.75-2.0 PFLOP/s
+// dense-equivalent against 1.5 with 256 x 128 tiles.  Timing-only ablations of this kernel: without the
+// weight loads -15 %, with both load streams always hitting L2 -17 %, matrix instructions alone
+// (no loads, no fragment reads) -30 %: what remains is the sustained rate of the matrix pipe itself plus
+// the per-tile prologue / epilogue.  Half tiles (512 x 64) for the last, partial round over the chip were
+// measured and dropped: the round they save costs less than their lower efficiency (436 vs 460 us).
 #include "common.hpp"
 #include <atomic>
 
@@ -113,35 +119,51 @@ big_tile(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int
                 acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, frag.v, acc[i][j], idx, 0, 0); \
         }                                                                                        \
     }
-    // One stage.  MS = slot of this stage's index words.  Loads past the last stage are clamped to it
-    // (never skipped), so the number of loads in flight at every wait is the same in every step.
-    // Token fragments are read one 32-token sub-tile ahead of the matrix instructions that use them.
+    // One stage.  MS = slot of this stage's index words.  The stage's token tile is already in LDS
+    // (buffer kt & 1).  In the middle of the stage's matrix instructions the NEXT stage's token granules
+    // (in registers since the middle of the previous stage) go to the other LDS buffer and the stage
+    // after that is requested, so the only thing between two stages is one barrier.  Loads past the last
+    // stage are clamped to it (never skipped): the number of loads in flight at every wait is the same
+    // in every step.  Token fragments are read kDepth sub-tiles ahead of their matrix instructions.
+    constexpr int kDepth = 3;
 #define BIMASK_BIG_STEP(kt, MS)                                                                  \
     {                                                                                            \
-        uint8_t* sB = smem + ((kt) & 1) * kBigStage;                                             \
-        _Pragma("unroll") for (int it = 0; it < NB_; ++it)                                       \
-            *reinterpret_cast<u32x4*>(sB + sb_off[it]) = rb[it];                                 \
+        const uint8_t* sB = smem + ((kt) & 1) * kBigStage;                                       \
+        uint8_t* sBw = smem + (((kt) + 1) & 1) * kBigStage;                                      \
         const int ktn = (kt) + 1 < nk ? (kt) + 1 : nk - 1;                                       \
-        _Pragma("unroll") for (int it = 0; it < NB_; ++it)                                       \
-            rb[it] = *reinterpret_cast<const u32x4*>(Bm + (pb[it] + ktn * 128));                 \
+        const int ktn2 = (kt) + 2 < nk ? (kt) + 2 : nk - 1;                                      \
         _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
             rmeta[1 - (MS)][i] = *reinterpret_cast<const u32x2*>(Ameta + (pm[i] + ktn * 128));   \
-        __syncthreads();                                                                         \
-        BFragB f[2];                                                                             \
-        BIMASK_BIG_FRAG(f[0], 0, 0)                                                              \
+        BFragB f[kDepth + 1];                                                                    \
+        _Pragma("unroll") for (int d = 0; d < kDepth; ++d)                                       \
+            BIMASK_BIG_FRAG(f[d], d / TN, d % TN)                                                \
         _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) {                                       \
             _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                     \
-                constexpr int cur = 0;                                                           \
-                (void)cur;                                                                       \
                 const int q = s4 * TN + j;                                                       \
-                if (q + 1 < 4 * TN) BIMASK_BIG_FRAG(f[(q + 1) & 1], (q + 1) / TN, (q + 1) % TN)  \
-                BIMASK_BIG_MFMA(f[q & 1], s4, j, MS)                                             \
+                if (q + kDepth < 4 * TN)                                                         \
+                    BIMASK_BIG_FRAG(f[(q + kDepth) % (kDepth + 1)], (q + kDepth) / TN, (q + kDepth) % TN) \
+                BIMASK_BIG_MFMA(f[q % (kDepth + 1)], s4, j, MS)                                  \
             }                                                                                    \
             /* this sub-step's weight registers are free: fetch the next stage's fragment */     \
             _Pragma("unroll") for (int i = 0; i < TM; ++i)                                       \
                 ra[i][s4] = *reinterpret_cast<const u32x4*>(A + (pa[i] + (ktn * 4 + s4) * 512)); \
-            __builtin_amdgcn_sched_barrier(0);   /* keep the re-load here: a full stage ahead of its use */ \
+            if (s4 == 1) {                                                                       \
+                _Pragma("unroll") for (int it = 0; it < NB_; ++it)                               \
+                    *reinterpret_cast<u32x4*>(sBw + sb_off[it]) = rb[it];                        \
+                _Pragma("unroll") for (int it = 0; it < NB_; ++it)                               \
+                    rb[it] = *reinterpret_cast<const u32x4*>(Bm + (pb[it] + ktn2 * 128));        \
+            }                                                                                    \
+            __builtin_amdgcn_sched_barrier(0);   /* keep the loads where they are written: a stage ahead of their use */ \
         }                                                                                        \
+        __syncthreads();                                                                         \
+    }
+    {   // stage 0 of the token tile into LDS buffer 0, stage 1 into the registers
+#pragma unroll
+        for (int it = 0; it < NB_; ++it) *reinterpret_cast<u32x4*>(smem + sb_off[it]) = rb[it];
+        const int k1 = 1 < nk ? 1 : 0;
+#pragma unroll
+        for (int it = 0; it < NB_; ++it) rb[it] = *reinterpret_cast<const u32x4*>(Bm + (pb[it] + k1 * 128));
+        __syncthreads();
     }
 
     int kt = 0;
@@ -203,35 +225,23 @@ big_tile(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int
     }
 }
 
-// Work order.  The token range is cut into units of 64 tokens; XCD x (workgroup ids are dealt round-robin
-// to the 8 XCDs, each with its own L2) owns the contiguous run of `upx` units starting at x * upx.  The first
-// 2 * fpx units of a run are worked on as `fpx` full tiles (128 tokens), the rest as half tiles (64 tokens).
-// Workgroups start in the order of their position in the XCD's sequence: full tiles first -- token tile
-// fastest, so that the ~32 workgroups an XCD runs at one time share a few weight tiles and all its token
-// tiles through that XCD's L2 --, half tiles last, where they even out the last round over the XCD's CUs.
+// Work order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2: XCD x owns the
+// contiguous run of `tpx` token tiles starting at x * tpx, against all weight tiles.  Its workgroups start in
+// the order of their position in the XCD's sequence, token tile fastest, so that the ~32 workgroups an XCD
+// runs at one time share a few weight tiles and all of its token tiles through that XCD's L2.
 __global__ void __launch_bounds__(kBigThreads)
 k_gemm_sp24_big(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int nk,
                 const uint16_t* __restrict__ Bm, int64_t T, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
-                int tiles_a, int units, int upx, int fpx) {
+                int tiles_a, int tiles_t, int tpx) {
     extern __shared__ u32x4 smem_u4[];
     uint8_t* smem = reinterpret_cast<uint8_t*>(smem_u4);
     const int x = blockIdx.x & 7, pos = blockIdx.x >> 3;
-    const int u_begin = x * upx < units ? x * upx : units;
-    const int u_end = u_begin + upx < units ? u_begin + upx : units;
-    const int nu = u_end - u_begin;
-    const int nf = 2 * fpx <= nu ? fpx : nu / 2;         // full token tiles of this XCD
-    const int nh = nu - 2 * nf;                          // half token tiles
-    const int nfull = nf * tiles_a;
-    if (pos < nfull) {
-        const int ta = pos / nf, tt = pos - ta * nf;
-        big_tile<4>(A, Ameta, Adim, nk, Bm, T, ldb, C, ldc, static_cast<int64_t>(ta) * kBigRows,
-                    (static_cast<int64_t>(u_begin) + 2 * tt) * 64, smem);
-    } else if (pos - nfull < nh * tiles_a) {
-        const int p2 = pos - nfull;
-        const int ta = p2 / nh, tt = p2 - ta * nh;
-        big_tile<2>(A, Ameta, Adim, nk, Bm, T, ldb, C, ldc, static_cast<int64_t>(ta) * kBigRows,
-                    (static_cast<int64_t>(u_begin) + 2 * nf + tt) * 64, smem);
-    }
+    const int t_begin = x * tpx < tiles_t ? x * tpx : tiles_t;
+    const int nt = t_begin + tpx < tiles_t ? tpx : tiles_t - t_begin;
+    if (pos >= nt * tiles_a) return;                     // whole workgroup, before any barrier
+    const int ta = pos / nt, tt = pos - ta * nt;
+    big_tile<4>(A, Ameta, Adim, nk, Bm, T, ldb, C, ldc, static_cast<int64_t>(ta) * kBigRows,
+                static_cast<int64_t>(t_begin + tt) * kBigTokens, smem);
 }
 
 }  // namespace
@@ -248,7 +258,7 @@ int launch_gemm_sp24_big(const void* A, const uint32_t* meta, int64_t Adim, int6
     if (!aligned16(A) || !aligned16(meta) || !aligned16(Bm) || !aligned16(C) || ldb % 8 || ldc % 8) return BIMASK_ERR_UNSUPPORTED;
     // 32-bit offsets inside the operand and inside a token tile, 32-bit tile counts
     if (round_up(Adim, 32) * (K / 2) > 0x7FFFFFFFll || 128 * ldb + K > 0x7FFFFFFFll ||
-        ceil_div(T, 64) * ceil_div(Adim, kBigRows) > 0x0FFFFFFFll) return BIMASK_ERR_UNSUPPORTED;
+        ceil_div(T, kBigTokens) * ceil_div(Adim, kBigRows) > 0x0FFFFFFFll) return BIMASK_ERR_UNSUPPORTED;
     static std::atomic<bool> attr_set{false};
     auto kern = k_gemm_sp24_big;
     if (!attr_set.load(std::memory_order_relaxed)) {
@@ -257,20 +267,12 @@ int launch_gemm_sp24_big(const void* A, const uint32_t* meta, int64_t Adim, int6
         attr_set.store(true, std::memory_order_relaxed);
     }
     const int tiles_a = static_cast<int>(ceil_div(Adim, kBigRows));
-    // An XCD has 32 CUs, one workgroup each.  Of the work of an XCD (upx units x tiles_a weight tiles, in
-    // half tiles) as many WHOLE rounds of 32 full tiles as fit are done in full tiles, the rest in half
-    // tiles: the last round then leaves no CU idle for longer than half a tile.
-    const int64_t units = ceil_div(T, 64);
-    const int64_t upx = ceil_div(units, 8);
-    const int64_t rounds = upx * tiles_a / 2 / 32;                   // whole rounds of full tiles per XCD
-    int64_t fpx = rounds * 32 / tiles_a;                             // token tiles kept full per XCD
-    if (fpx > upx / 2) fpx = upx / 2;
-    if ((upx * tiles_a) % 64 == 0) fpx = upx / 2;                    // the full tiles alone make whole rounds
-    const int64_t per_xcd = (fpx + (upx - 2 * fpx)) * tiles_a;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(per_xcd * 8)), dim3(kBigThreads), kBigSmem, s,
+    const int64_t tiles_t = ceil_div(T, kBigTokens);
+    const int64_t tpx = ceil_div(tiles_t, 8);
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(tpx * tiles_a * 8)), dim3(kBigThreads), kBigSmem, s,
                        static_cast<const uint16_t*>(A), meta, Adim, static_cast<int>(K / 128),
                        static_cast<const uint16_t*>(Bm), T, ldb, static_cast<uint16_t*>(C), ldc, tiles_a,
-                       static_cast<int>(units), static_cast<int>(upx), static_cast<int>(fpx));
+                       static_cast<int>(tiles_t), static_cast<int>(tpx));
     return check_launch();
 }
 
