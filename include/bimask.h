@@ -57,10 +57,9 @@
  *
  * Conventions:
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library allocates
- *     nothing, keeps no device state between calls (on the host it only remembers answers of the
- *     runtime's occupancy query and which kernels had their LDS limit raised: both are taken for
- *     the device that was current at the first call, so a process drives ONE device through this
- *     library), and never synchronises: every call only
+ *     nothing, keeps no device state between calls (on the host it only remembers, per device
+ *     ordinal, answers of the runtime's occupancy query and which kernels had their LDS limit raised:
+ *     several devices may be driven from one process), and never synchronises: every call only
  *     enqueues work on `stream` (a hipStream_t passed as void*, NULL = default stream).
  *   - Return value: BIMASK_OK or a bimask_status error.  Argument errors are detected on
  *     the host before anything is launched and leave all outputs untouched.  Nothing

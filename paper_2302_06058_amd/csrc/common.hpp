@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <atomic>
 #include "../../include/bimask.h"
 
 namespace bimask {
@@ -23,6 +24,22 @@ __host__ __device__ inline bool uses_sp24(int N, int M) { return N <= 2 && M % 4
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+
+// Host-side memo of one small answer of the runtime per GPU (an occupancy figure, "this kernel's LDS limit
+// has been raised"): such answers belong to a device, so they are remembered per device ordinal, each as ONE
+// 64-bit word that is read and written atomically (0 = not known yet).  Objects of this type have static
+// storage (zero-initialised).  No other host state is kept between calls.
+constexpr int kMaxDevices = 64;
+struct DeviceMemo {
+    std::atomic<uint64_t> word[kMaxDevices];
+    // ordinal of the current device, or -1 (then nothing is remembered and the runtime is asked every time)
+    static int device() {
+        int d = -1;
+        return hipGetDevice(&d) == hipSuccess && d >= 0 && d < kMaxDevices ? d : -1;
+    }
+    uint64_t get(int d) const { return d < 0 ? 0 : word[d].load(std::memory_order_acquire); }
+    void set(int d, uint64_t x) { if (d >= 0) word[d].store(x, std::memory_order_release); }
+};
 
 inline int check_launch() {
     return hipGetLastError() == hipSuccess ? BIMASK_OK : BIMASK_ERR_HIP;

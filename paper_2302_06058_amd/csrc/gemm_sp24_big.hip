@@ -25,7 +25,6 @@
 // the per-tile prologue / epilogue.  Half tiles (512 x 64) for the last, partial round over the chip were
 // measured and dropped: the round they save costs less than their lower efficiency (436 vs 460 us).
 #include "common.hpp"
-#include <atomic>
 
 namespace bimask {
 namespace {
@@ -246,10 +245,11 @@ k_gemm_sp24_big(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ame
 
 }  // namespace
 
-// Shapes the large-problem kernel takes: whole stages, 16-byte aligned rows, and enough tiles that
-// the chip is covered several times over.
+// Shapes the large-problem kernel takes: whole stages, a contraction long enough (at least 8 stages) that a
+// tile's matrix loop outweighs its prologue and epilogue, and enough tiles that the chip is covered twice over.
 bool gemm_sp24_big_shape(int64_t Adim, int64_t K, int64_t T) {
-    return K % 128 == 0 && Adim >= 1024 && Adim % 8 == 0 && ceil_div(Adim, kBigRows) * ceil_div(T, kBigTokens) >= 512;
+    return K % 128 == 0 && K >= 1024 && Adim >= 1024 && Adim % 8 == 0 &&
+           ceil_div(Adim, kBigRows) * ceil_div(T, kBigTokens) >= 512;
 }
 
 int launch_gemm_sp24_big(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
@@ -259,12 +259,13 @@ int launch_gemm_sp24_big(const void* A, const uint32_t* meta, int64_t Adim, int6
     // 32-bit offsets inside the operand and inside a token tile, 32-bit tile counts
     if (round_up(Adim, 32) * (K / 2) > 0x7FFFFFFFll || 128 * ldb + K > 0x7FFFFFFFll ||
         ceil_div(T, kBigTokens) * ceil_div(Adim, kBigRows) > 0x0FFFFFFFll) return BIMASK_ERR_UNSUPPORTED;
-    static std::atomic<bool> attr_set{false};
+    static DeviceMemo attr_set;
+    const int dev = DeviceMemo::device();
     auto kern = k_gemm_sp24_big;
-    if (!attr_set.load(std::memory_order_relaxed)) {
+    if (!attr_set.get(dev)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kBigSmem) != hipSuccess)
             return BIMASK_ERR_HIP;
-        attr_set.store(true, std::memory_order_relaxed);
+        attr_set.set(dev, 1);
     }
     const int tiles_a = static_cast<int>(ceil_div(Adim, kBigRows));
     const int64_t tiles_t = ceil_div(T, kBigTokens);

@@ -15,7 +15,6 @@
 // distinct banks.  Rows whose byte length is no multiple of 16 (K or Adim = 8 m + 4) must be
 // contiguous in memory; a 32-token tile is then one 16-byte-aligned block.
 #include "common.hpp"
-#include <atomic>
 
 namespace bimask {
 namespace {
@@ -321,15 +320,16 @@ int run_narrow(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, con
     if (lds > 48 * 1024) return BIMASK_ERR_UNSUPPORTED;
     // wavefronts per CU by LDS and registers; the grid is a multiple of the CU count in which every
     // wavefront gets the same number of tiles (+-1)
-    // (the answer depends on the kernel and the LDS size only: remembered per instantiation)
-    static std::atomic<int> known_lds{-1}, known_wpc{0};
-    int wpc = known_lds.load(std::memory_order_acquire) == lds ? known_wpc.load(std::memory_order_relaxed) : 0;
+    // (the answer depends on the kernel, the LDS size and the device: remembered per instantiation and device,
+    // LDS size and answer in one word)
+    static DeviceMemo memo;
+    const int dev = DeviceMemo::device();
+    const uint64_t known = memo.get(dev);
+    int wpc = (known >> 32) == static_cast<uint64_t>(lds) ? static_cast<int>(known & 0xFFFFFFFFu) : 0;
     if (wpc < 1) {
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&wpc, reinterpret_cast<const void*>(kern), 64, static_cast<size_t>(lds)) != hipSuccess || wpc < 1)
             return BIMASK_ERR_HIP;
-        known_lds.store(-1, std::memory_order_release);
-        known_wpc.store(wpc, std::memory_order_relaxed);
-        known_lds.store(lds, std::memory_order_release);
+        memo.set(dev, (static_cast<uint64_t>(lds) << 32) | static_cast<uint32_t>(wpc));
     }
     if (wpc > 16) wpc = 16;
     const int nsplit = static_cast<int>(ceil_div(Adim, TM * 32));

@@ -14,7 +14,6 @@
 // streaming stores (one barrier per weight tile).
 // Token tiles have a run-time height (<= BN) so that the grid can be cut to the CU count.
 #include "common.hpp"
-#include <atomic>
 
 namespace bimask {
 namespace {
@@ -306,13 +305,14 @@ int run_resident(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, c
     if (PERSIST) {
         unsigned cap = kPersistGrid;
         if (BM > 128) {                              // large tiles: as many workgroups as stay resident
-            static std::atomic<int> known_occ{0};        // per instantiation: kernel and LDS size are fixed
-            int occ = known_occ.load(std::memory_order_relaxed);
+            static DeviceMemo memo;                  // per instantiation (kernel and LDS size are fixed) and device
+            const int dev = DeviceMemo::device();
+            int occ = static_cast<int>(memo.get(dev));
             if (occ < 1) {
                 if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void*>(kern), 64 * WAVES_M,
                                                                  static_cast<size_t>(S::kTotal)) != hipSuccess || occ < 1)
                     return BIMASK_ERR_HIP;
-                known_occ.store(occ, std::memory_order_relaxed);
+                memo.set(dev, static_cast<uint64_t>(occ));
             }
             cap = 256u * static_cast<unsigned>(occ);
         }

@@ -15,7 +15,6 @@
 // (row pitch = 2 I + 8 bytes: 32 lanes hit 64 distinct banks).  The output tile is regrouped
 // through the same LDS area and leaves as whole rows.
 #include "common.hpp"
-#include <atomic>
 
 namespace bimask {
 namespace {
@@ -267,12 +266,13 @@ int launch_gemm_sp24_rowres(const void* A, const uint32_t* meta, int64_t Adim, i
     const unsigned grid = static_cast<unsigned>(ceil_div(T, best_rpt));
 #define BIMASK_ROWRES(TM_, NP_)                                                                              \
     {                                                                                                        \
-        static std::atomic<bool> attr_set{false};                                                            \
+        static DeviceMemo attr_set;                                                                          \
+        const int dev = DeviceMemo::device();                                                                \
         auto kern = k_gemm_sp24_rowres<TM_, NP_>;                                                            \
-        if (!attr_set.load(std::memory_order_relaxed)) {                                                     \
+        if (!attr_set.get(dev)) {                                                                            \
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                     160 * 1024) != hipSuccess) return BIMASK_ERR_HIP;                        \
-            attr_set.store(true, std::memory_order_relaxed);                                                 \
+            attr_set.set(dev, 1);                                                                            \
         }                                                                                                    \
         hipLaunchKernelGGL(kern, dim3(grid), dim3(kRowResThreads), best_lds, s, static_cast<const uint16_t*>(A), meta, \
                            static_cast<int>(Adim), static_cast<int>(K), static_cast<const uint16_t*>(Bsrc), ldb, perm, T, \

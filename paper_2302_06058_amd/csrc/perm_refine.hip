@@ -277,20 +277,21 @@ k_perm_refine_group(const RefineGroup g, int N) {
 }
 
 template <int M>
-int set_refine_lds(const void* kern, size_t lds, std::atomic<bool>& done) {
-    if (lds > 48 * 1024 && !done.load(std::memory_order_relaxed)) {
+int set_refine_lds(const void* kern, size_t lds, DeviceMemo& done) {
+    const int dev = DeviceMemo::device();
+    if (lds > 48 * 1024 && !done.get(dev)) {
         if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024) != hipSuccess) {
             (void)hipGetLastError();
             return BIMASK_ERR_HIP;
         }
-        done.store(true, std::memory_order_relaxed);
+        done.set(dev, 1);
     }
     return BIMASK_OK;
 }
 
 template <int M>
 int run_refine_group(const bimask_group_layer* L, int n, int N, hipStream_t s) {
-    static std::atomic<bool> attr_set{false};
+    static DeviceMemo attr_set;
     for (int first = 0; first < n; first += kRefineGroupCap) {
         const int cnt = n - first < kRefineGroupCap ? n - first : kRefineGroupCap;
         RefineGroup g;
@@ -311,7 +312,7 @@ int run_refine_group(const bimask_group_layer* L, int n, int N, hipStream_t s) {
 template <int M>
 int run_refine(const uint32_t* B_bits, int64_t I, int64_t J, int N, const int32_t* perm_in, const int32_t* swaps,
                int64_t S, int32_t* perm_out, int32_t* result, hipStream_t s) {
-    static std::atomic<bool> attr_set{false};
+    static DeviceMemo attr_set;
     const size_t lds = static_cast<size_t>(I) * 4;
     if (int rc = set_refine_lds<M>(reinterpret_cast<const void*>(k_perm_refine<M>), lds, attr_set)) return rc;
     hipLaunchKernelGGL(k_perm_refine<M>, dim3(1), dim3(kRefineThreads), lds, s, B_bits, static_cast<int>(I),

@@ -391,7 +391,6 @@ size_t perm_search_static_capacity() { return kStaticScratchBytes; }
 
 int launch_perm_search_static(const uint32_t* B_bits, int64_t I, int64_t J, int N, int M, const int32_t* perms, int K,
                               int32_t* scores, int32_t* best, int32_t* best_perm, hipStream_t s) {
-    constexpr int kMaxDevices = 64;
     static std::atomic<void*> device_ptr[kMaxDevices];       // zero-initialised: not looked up yet
     if (plan_perm_search(I, J, K, M).ws_bytes > kStaticScratchBytes) return BIMASK_ERR_WORKSPACE;
     int dev = -1;
@@ -436,16 +435,17 @@ k_check_perms(const int32_t* __restrict__ perms, int64_t I, int32_t* __restrict_
 }  // namespace
 
 int launch_check_perms(const int32_t* perms, int K, int64_t I, int32_t* ok, hipStream_t s) {
-    static std::atomic<bool> attr_set{false};
+    static DeviceMemo attr_set;
     if (I > kCheckPermsMaxRows) return BIMASK_ERR_UNSUPPORTED;
     const size_t lds = static_cast<size_t>((I + 31) >> 5) * 4;
-    if (lds > 48 * 1024 && !attr_set.load(std::memory_order_relaxed)) {
+    const int dev = DeviceMemo::device();
+    if (lds > 48 * 1024 && !attr_set.get(dev)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_check_perms), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 128 * 1024) != hipSuccess) {
             (void)hipGetLastError();
             return BIMASK_ERR_HIP;
         }
-        attr_set.store(true, std::memory_order_relaxed);
+        attr_set.set(dev, 1);
     }
     hipLaunchKernelGGL(k_check_perms, dim3(static_cast<unsigned>(K)), dim3(kThreads), lds, s, perms, I, ok);
     return check_launch();

@@ -94,8 +94,8 @@ SP24_SHAPES = [
     (1024, 1028, 300),   # streaming, ragged last stage / separate gather
     (2560, 1024, 2600),  # streaming 256 x 128 both ways (the tile of the largest layers), separate gather
     (4096, 2048, 8200),  # forward: 512 x 128 tiles (8 x 65 tiles, the last token tile ragged) / separate gather, streaming 256 x 128
-    (3200, 1152, 22037), # 512 x 128 tiles both ways: 6.25 and 2.25 weight tiles, ragged tokens, full and half tiles in the grid
-    (1024, 1152, 65600), # 512 x 128 tiles: two weight tiles, 1025 token units (an odd unit at the end of the last XCD's run)
+    (3200, 1152, 22037), # 512 x 128 tiles both ways (the backward one behind the separate gather): 6.25 and 2.25 weight tiles, ragged last token tile
+    (1024, 1152, 65600), # 512 x 128 tiles: two / three weight tiles, 513 token tiles (65 per XCD, the last XCD's run shorter)
 ]
 
 
