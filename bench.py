@@ -61,6 +61,9 @@ def parse():
                     help="refinement of every layer's permutation: one call per layer against the grouped call")
     ap.add_argument("--search-table", action="store_true",
                     help="permutation search over all ResNet-50 layers for 2:4, 4:8, 1:4, 2:8, 1:16 (the shape of the paper's Table 6)")
+    ap.add_argument("--only-stage", default=None,
+                    help="diagnostic: repeat ONE stage of the step (forward_mask_compress, perm_search, backward_mask_compress, "
+                         "sparse_gemm_fwd, sparse_gemm_bwd) back to back, `steps` times per matrix: its stand-alone time")
     ap.add_argument("--delta-t", type=int, default=100,
                     help="steps between two permutation searches (Sec. 4.1) for the amortised secondary figure")
     return ap.parse_args()
@@ -662,6 +665,35 @@ def search_table(args):
                       "note": "the paper does not say how many searches its figure covers"}), flush=True)
 
 
+def only_stage(args):
+    """One stage repeated back to back (operands warm in the last-level cache where they fit): the stand-alone
+    figure beside the in-sequence one of the step.  Microseconds per call, per matrix."""
+    import torch
+    from paper_2302_06058_amd import synth
+    out = {}
+    for L in pick_layers(args.config, args.layer):
+        run = LayerRun(L, synth.gen_layer(L), 2)
+        run.step(0)
+        fn = dict(run.stages)[args.only_stage]
+        for i in range(args.warmup):
+            fn(i % 2)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(args.steps):
+            fn(i % 2)
+        b.record()
+        torch.cuda.synchronize()
+        alg = algorithmic(L)[args.only_stage]
+        us = a.elapsed_time(b) * 1e3 / args.steps
+        out[L.name] = {"us": round(us, 2), "algorithmic_GBs": round(alg["bytes"] / us / 1e3, 1),
+                       "dense_equiv_TFLOPs": round(alg["flops"] / us / 1e6, 1)}
+        del run
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": f"stand-alone repeats of stage {args.only_stage}", "config": args.config, "steps": args.steps,
+                      "matrices": out}), flush=True)
+
+
 def pick_layers(config, layer):
     """Layers that make up one step: all layers of configs 1, 2 and 5 (config 5 = the two matrices of the MLP
     block), one layer of configs 3 and 4 (their whole-network steps are --network-step / --all-layers)."""
@@ -832,6 +864,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
+    if args.only_stage:
+        if args.config is None:
+            args.config = 5
+        return only_stage(args)
     headline = not (args.all_layers or args.search_table or args.grouped or args.gradient_gap or args.refine
                     or args.refine_network or args.network_step)
     if args.config is None:

@@ -45,6 +45,26 @@ def build_lib(verbose: bool = False, only=None) -> str:
     return LIB
 
 
+TOOLS = ["l2_gather_ceiling"]     # stand-alone measurement programs under csrc/tools/ (not part of the library)
+BIN = os.path.join(HERE, "bin")
+
+
+def build_tools(verbose: bool = False):
+    """Compiles the measurement tools into bin/ (each a self-contained HIP program with its own main)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(BIN, exist_ok=True)
+    out = []
+    for t in TOOLS:
+        exe = os.path.join(BIN, t)
+        _run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+              os.path.join(CSRC, "tools", t + ".hip"), "-o", exe], verbose)
+        out.append(exe)
+    return out
+
+
 if __name__ == "__main__":
     names = [a for a in sys.argv[1:] if a.endswith(".hip")]
-    print(build_lib(verbose="-v" in sys.argv, only=names or None))
+    if "--tools" in sys.argv:
+        print("\n".join(build_tools(verbose="-v" in sys.argv)))
+    else:
+        print(build_lib(verbose="-v" in sys.argv, only=names or None))

@@ -692,9 +692,10 @@ __device__ __forceinline__ void backward24_tile(
         for (int m = 0; m < 4; ++m)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const uint32_t lo = 0u - ((X[o2] >> (8 * m + 2 * j)) & 1u);
-                const uint32_t hi = 0u - ((X[o2] >> (8 * m + 2 * j + 1)) & 1u);
-                w[m][o2][j] &= (lo & 0x0000FFFFu) | (hi & 0xFFFF0000u);
+                // mask bit -> 0 / all ones by a signed one-bit field extract, the two halves merged by a bit-field insert
+                const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_sbfe(static_cast<int>(X[o2]), 8 * m + 2 * j, 1));
+                const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_sbfe(static_cast<int>(X[o2]), 8 * m + 2 * j + 1, 1));
+                w[m][o2][j] &= (lo & 0x0000FFFFu) | (hi & ~0x0000FFFFu);
             }
         nib[o2] = 0;
         R[o2] = 0;
@@ -708,7 +709,8 @@ __device__ __forceinline__ void backward24_tile(
             select_compress4_bf16(e01, e23, N, b4, n4, ow);              // top N of the column's 4 masked weights
             nib[o2] |= n4 << (4 * q);
             // byte m: columns that select row m
-            R[o2] |= ((b4 & 1u) | ((b4 & 2u) << 7) | ((b4 & 4u) << 14) | ((b4 & 8u) << 21)) << q;
+            // (bit m of b4 to bit 8 m: one 24-bit multiply spreads the four bits 7 apart, the mask keeps bit 0 of each byte)
+            R[o2] |= (__umul24(b4, 0x00204081u) & 0x01010101u) << q;
             // output row = this column; slots 2kb, 2kb+1 of the stage (kb = row block in the stage)
             const int ul = ul0 + o2 * 128 + q;
             lds32[((ul ^ ((ul >> 4) & 7)) << 2) + (k & 3)] = ow;
