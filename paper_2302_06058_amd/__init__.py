@@ -128,8 +128,8 @@ def operand_index_words(rows: int, cols: int, N: int, M: int) -> int:
 
 
 def _values_shape(rows: int, cols: int, N: int, M: int):
-    """N <= 2: flat fragment-major buffer (see include/bimask.h); else the dense rows x cols matrix."""
-    return (operand_elems(rows, cols, N, M),) if N <= 2 else (rows, cols)
+    """Flat fragment-major buffer (see include/bimask.h): 2-of-4 compressed for N <= 2, dense masked for N > 2."""
+    return (operand_elems(rows, cols, N, M),)
 
 
 def _index_shape(rows: int, cols: int, N: int, M: int):

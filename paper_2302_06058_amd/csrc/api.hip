@@ -38,7 +38,7 @@ int check_gemm(const void* act, int64_t T, int64_t ldact, int64_t kdim, const vo
     if (int rc = check_nm(N, M)) return rc;
     if (T <= 0 || I <= 0 || J <= 0 || I % M || J % M || ldact < kdim || ldout < outdim) return BIMASK_ERR_SHAPE;
     if (uses_sp24(N, M) && !index) return BIMASK_ERR_NULL;
-    if (uses_sp24(N, M) && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
+    if (!aligned16(values) || (uses_sp24(N, M) && !aligned16(index))) return BIMASK_ERR_ALIGN;
     if (dtype == BIMASK_BF16) {
         // rows are read in 4-byte units at least
         if (ldact % 2 || ldout % 2) return BIMASK_ERR_ALIGN;
@@ -66,7 +66,7 @@ int bimask_forward_mask_compress(const void* W, int64_t I, int64_t J, int64_t ld
     if (!B_bits || !values) return BIMASK_ERR_NULL;
     if (uses_sp24(N, M) && !index) return BIMASK_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(values) % esize(dtype)) return BIMASK_ERR_ALIGN;
-    if (uses_sp24(N, M) && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
+    if (!aligned16(values) || (uses_sp24(N, M) && !aligned16(index))) return BIMASK_ERR_ALIGN;
     return launch_forward(W, I, J, ldw, dtype, N, M, nullptr, B_bits, values, index, true, as_stream(stream));
 }
 
@@ -127,7 +127,7 @@ int bimask_backward_mask_compress(const void* W, int64_t I, int64_t J, int64_t l
     if (!B_bits || !Bbar_bits || !values) return BIMASK_ERR_NULL;
     if (uses_sp24(N, M) && !index) return BIMASK_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(values) % esize(dtype)) return BIMASK_ERR_ALIGN;
-    if (uses_sp24(N, M) && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
+    if (!aligned16(values) || (uses_sp24(N, M) && !aligned16(index))) return BIMASK_ERR_ALIGN;
     return launch_backward(W, I, J, ldw, dtype, N, M, B_bits, nullptr, perm, Bbar_bits, values, index, true,
                            as_stream(stream));
 }
@@ -139,7 +139,7 @@ int bimask_compress_nm(const void* W, int64_t I, int64_t J, int64_t ldw, int dty
     if (!mask_bits || !values) return BIMASK_ERR_NULL;
     if (uses_sp24(N, M) && !index) return BIMASK_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(values) % esize(dtype)) return BIMASK_ERR_ALIGN;
-    if (uses_sp24(N, M) && (!aligned16(values) || !aligned16(index))) return BIMASK_ERR_ALIGN;
+    if (!aligned16(values) || (uses_sp24(N, M) && !aligned16(index))) return BIMASK_ERR_ALIGN;
     if (transposed != 0 && transposed != 1) return BIMASK_ERR_SHAPE;
     if (!transposed) {
         if (perm) return BIMASK_ERR_UNSUPPORTED;                     // rows of the forward operand are not permuted
@@ -159,7 +159,7 @@ int bimask_forward_mask_compress_group(const bimask_group_layer* layers, int n, 
         if (!a.B_bits || !a.Wf_values) return BIMASK_ERR_NULL;
         if (uses_sp24(N, M) && !a.Wf_index) return BIMASK_ERR_NULL;
         if (reinterpret_cast<uintptr_t>(a.Wf_values) % esize(dtype)) return BIMASK_ERR_ALIGN;
-        if (uses_sp24(N, M) && (!aligned16(a.Wf_values) || !aligned16(a.Wf_index))) return BIMASK_ERR_ALIGN;
+        if (!aligned16(a.Wf_values) || (uses_sp24(N, M) && !aligned16(a.Wf_index))) return BIMASK_ERR_ALIGN;
     }
     return launch_forward_group(layers, n, dtype, N, M, as_stream(stream));
 }
@@ -204,7 +204,7 @@ int bimask_backward_mask_compress_group(const bimask_group_layer* layers, int n,
         if (!a.B_bits || !a.Bbar_bits || !a.Wb_values) return BIMASK_ERR_NULL;
         if (uses_sp24(N, M) && !a.Wb_index) return BIMASK_ERR_NULL;
         if (reinterpret_cast<uintptr_t>(a.Wb_values) % esize(dtype)) return BIMASK_ERR_ALIGN;
-        if (uses_sp24(N, M) && (!aligned16(a.Wb_values) || !aligned16(a.Wb_index))) return BIMASK_ERR_ALIGN;
+        if (!aligned16(a.Wb_values) || (uses_sp24(N, M) && !aligned16(a.Wb_index))) return BIMASK_ERR_ALIGN;
     }
     return launch_backward_group(layers, n, dtype, N, M, as_stream(stream));
 }
@@ -246,7 +246,7 @@ int bimask_sparse_gemm_bwd(const void* dY, int64_t T, int64_t lddy, const int32_
 int64_t bimask_operand_elems(int64_t rows, int64_t cols, int N, int M) {
     if (rows <= 0 || cols <= 0) return 0;
     if (uses_sp24(N, M)) return round_up(rows, 32) * (round_up(cols, 128) / 2);
-    return rows * cols;
+    return round_up(rows, 32) * round_up(cols, 128);
 }
 
 int64_t bimask_operand_index_words(int64_t rows, int64_t cols, int N, int M) {

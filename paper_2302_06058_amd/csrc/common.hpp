@@ -101,6 +101,15 @@ __host__ __device__ inline int64_t tiled_idx_word(int64_t r, int64_t g, int64_t 
     return (((r >> 5) * ks + st) * 64 + (r & 31) + 32 * (q >> 4)) * 2 + ((q >> 3) & 1);
 }
 
+// Fragment-major layout of a DENSE masked operand (ratios with N > 2; see include/bimask.h): element offset of
+// entry (r, k); ks = padded cols / 128.  The 8 entries k .. k+7 (k a multiple of 8) are contiguous, and the 64
+// granules lane l = r % 32 + 32 ((k % 16) / 8) of one 32x32x16 matrix instruction's A operand follow each other.
+__host__ __device__ inline int64_t tiled_dense_off(int64_t r, int64_t k, int64_t ks) {
+    const int64_t st = k >> 7;
+    const int kk = static_cast<int>(k & 127);
+    return ((((((r >> 5) * ks + st) * 4 + ((kk & 63) >> 4)) * 2 + (kk >> 6)) * 64 + (r & 31) + 32 * ((kk & 15) >> 3)) << 3) + (kk & 7);
+}
+
 // Two fp32 accumulators -> packed bf16 (round to nearest even) with the gfx950 conversion
 // instruction; the low half holds `lo`.
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {

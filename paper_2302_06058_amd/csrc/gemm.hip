@@ -49,9 +49,10 @@ struct Smem {
     static constexpr int kTotal = (2 * kStage > kC) ? 2 * kStage : kC;
 };
 
-// Dense bf16 GEMM on masked weights (N:M ratios other than 2:4).  Workgroup tile BM (weight
-// rows a) x BN (tokens t); both operands go global -> registers -> padded LDS -> MFMA
-// fragments, one stage prefetched in registers.
+// Dense bf16 GEMM on masked weights (N:M ratios with N > 2), general fallback (any alignment, any
+// contraction length).  Workgroup tile BM (weight rows a) x BN (tokens t); both operands go global ->
+// registers -> padded LDS -> MFMA fragments, one stage prefetched in registers; the weight granules
+// come from the fragment-major dense operand.
 // FAST: K is a multiple of BK and all rows start 16-byte aligned: unconditional 16-byte loads.
 template <bool FAST, int BM, int BN, int WAVES_M, int WAVES_N>
 __global__ void __launch_bounds__(kThreads)
@@ -88,7 +89,7 @@ k_gemm_dense_bf16(const uint16_t* __restrict__ A, int64_t Adim, int64_t K, const
     constexpr int NB_ = BN * 8 / kThreads, NA_ = BM * 8 / kThreads;   // 16-byte granules per thread
     u32x4 rb[NB_], ra[NA_];
     const uint16_t* pb[NB_];
-    const uint16_t* pa[NA_];
+    int64_t arow[NA_];                                   // weight row of each of this thread's granules (clamped)
 #pragma unroll
     for (int it = 0; it < NB_; ++it) {
         int64_t t = t0 + ((tid + kThreads * it) >> 3);
@@ -97,8 +98,9 @@ k_gemm_dense_bf16(const uint16_t* __restrict__ A, int64_t Adim, int64_t K, const
 #pragma unroll
     for (int it = 0; it < NA_; ++it) {
         int64_t a = a0 + ((tid + kThreads * it) >> 3);
-        pa[it] = A + (a < Adim ? a : Adim - 1) * K;
+        arow[it] = a < Adim ? a : Adim - 1;
     }
+    const int64_t ksA = ceil_div(K, 128);                // stages of the padded fragment-major weight operand
     const int g8 = (tid & 7) * 8;                        // this thread's k offset inside a stage
 
 #define BIMASK_DENSE_LOAD(kt)                                                                     \
@@ -108,10 +110,9 @@ k_gemm_dense_bf16(const uint16_t* __restrict__ A, int64_t Adim, int64_t K, const
             if constexpr (FAST) rb[it] = *reinterpret_cast<const u32x4*>(pb[it] + k);             \
             else rb[it] = load_granule(pb[it], k, K, vecB);                                       \
         }                                                                                         \
-        _Pragma("unroll") for (int it = 0; it < NA_; ++it) {                                      \
-            if constexpr (FAST) ra[it] = *reinterpret_cast<const u32x4*>(pa[it] + k);             \
-            else ra[it] = load_granule(pa[it], k, K, vecA);                                       \
-        }                                                                                         \
+        /* the weight operand is padded to whole stages: every granule exists (zeros beyond K) */ \
+        _Pragma("unroll") for (int it = 0; it < NA_; ++it)                                        \
+            ra[it] = *reinterpret_cast<const u32x4*>(A + tiled_dense_off(arow[it], k, ksA));      \
     }
 #define BIMASK_DENSE_STORE(buf)                                                                   \
     {                                                                                             \
@@ -224,7 +225,7 @@ k_gemm_f32(const float* __restrict__ A, const uint32_t* __restrict__ Ameta, int6
                         if (pos == p0) va = A[tiled_val_off(a, 2 * g, ks)];
                         else if (pos == p1) va = A[tiled_val_off(a, 2 * g + 1, ks)];
                     } else {
-                        va = A[a * K + gk];
+                        va = A[tiled_dense_off(a, gk, ks)];
                     }
                 }
             }

@@ -112,6 +112,7 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
           typename DT::raw* __restrict__ values, uint32_t* __restrict__ index, int mode,
           int wpr, int cpr, int64_t rows_pad, bool vec_in, bool vec_out) {
     using raw = typename DT::raw;
+    (void)vec_out;
     constexpr int NV = CH / 8;                 // 8-element vectors per chunk
     constexpr int PW = Pack<DT>::kWords;
     const int64_t id = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
@@ -154,7 +155,9 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
     }
 
     if (mode == 2) {
-        raw* dst = values + i * J + j0;
+        // dense masked operand, fragment-major: every 8-entry granule of the padded matrix is written whole
+        // (rows >= I and columns >= J: zeros)
+        const int64_t ks = static_cast<int64_t>(cpr) * CH / 128;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             uint32_t o[PW];
@@ -167,15 +170,9 @@ k_forward(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int64_t 
                 if constexpr (sizeof(raw) == 2) o[q >> 1] |= x << (16 * (q & 1));
                 else o[q] = x;
             }
-            if (vec_out && j0 + 8 * v + 8 <= J) {
-                uint4* p = reinterpret_cast<uint4*>(dst + 8 * v);
+            uint4* p = reinterpret_cast<uint4*>(values + tiled_dense_off(i, j0 + 8 * v, ks));
 #pragma unroll
-                for (int u = 0; u < PW / 4; ++u) p[u] = make_uint4(o[4 * u], o[4 * u + 1], o[4 * u + 2], o[4 * u + 3]);
-            } else {
-#pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    if (j0 + 8 * v + q < J) dst[8 * v + q] = static_cast<raw>(elem<DT>(o, q));
-            }
+            for (int u = 0; u < PW / 4; ++u) p[u] = make_uint4(o[4 * u], o[4 * u + 1], o[4 * u + 2], o[4 * u + 3]);
         }
     }
 }
@@ -424,6 +421,10 @@ backward_body(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int6
         constexpr int kZeroWords = (img_elems<TC>() * (int)sizeof(raw) + TC * 32) / 16;
         for (int it = threadIdx.x; it < kZeroWords; it += kThreads) lds_u4[it] = make_uint4(0, 0, 0, 0);
         __syncthreads();
+    } else if (mode == 2) {                             // rows beyond I and columns beyond J of the tile: zeros
+        constexpr int kZeroWords = TC * S2 * (int)sizeof(raw) / 16;
+        for (int it = threadIdx.x; it < kZeroWords; it += kThreads) lds_u4[it] = make_uint4(0, 0, 0, 0);
+        __syncthreads();
     }
 
     for (int kb = threadIdx.x / CPT; kb < NB; kb += kThreads / CPT) {
@@ -503,6 +504,7 @@ backward_body(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int6
     if (mode == 0) return;
     __syncthreads();
 
+    (void)vec_out;
     const int64_t rows_valid = (I - r0) < kTR ? (I - r0) : kTR;       // multiple of M
     const int64_t cols_valid = (J - c0) < TC ? (J - c0) : TC;
     if (mode == 1) {
@@ -525,21 +527,18 @@ backward_body(const typename DT::raw* __restrict__ W, int64_t I, int64_t J, int6
             index[((c0 / 32 + rtl) * ks + stage) * 128 + lane * 2 + wd] = word;
         }
     } else {
-        if (vec_out && rows_valid == kTR) {
-            constexpr int EPG = 16 / sizeof(raw);
-            constexpr int GPC = kTR / EPG;
-            for (int it = threadIdx.x; it < TC * GPC; it += kThreads) {
-                const int col = it / GPC, g = it % GPC;
-                if (col >= cols_valid) continue;
-                const uint4 v = *reinterpret_cast<const uint4*>(lds_val + col * S2 + g * EPG);
-                *reinterpret_cast<uint4*>(values + (c0 + col) * I + r0 + g * EPG) = v;
-            }
-        } else {
-            for (int64_t it = threadIdx.x; it < TC * rows_valid; it += kThreads) {
-                const int col = static_cast<int>(it / rows_valid), e = static_cast<int>(it % rows_valid);
-                if (col >= cols_valid) continue;
-                values[(c0 + col) * I + r0 + e] = lds_val[col * S2 + e];
-            }
+        // dense masked operand, fragment-major: the tile is stage r0 / 128 of the output rows c0 .. c0 + TC - 1;
+        // whole 32-row tiles are written (output rows beyond J are zero padding), 8 entries at a time
+        (void)rows_valid;
+        const int64_t ks = ceil_div(I, 128);
+        const int rows_out = static_cast<int>((cols_valid + 31) / 32) * 32;
+        constexpr int V = 8 * (int)sizeof(raw) / 16;                  // 16-byte vectors per granule
+        for (int it = threadIdx.x; it < rows_out * 16; it += kThreads) {
+            const int g = it / rows_out, col = it - g * rows_out;     // consecutive threads: consecutive output rows
+            const uint4* src = reinterpret_cast<const uint4*>(lds_val + col * S2 + g * 8);
+            uint4* dst = reinterpret_cast<uint4*>(values + tiled_dense_off(c0 + col, r0 + 8 * g, ks));
+#pragma unroll
+            for (int u = 0; u < V; ++u) dst[u] = src[u];
         }
     }
 }
@@ -832,10 +831,12 @@ int run_forward(const void* W, int64_t I, int64_t J, int64_t ldw, int N, const u
                            static_cast<size_t>(I) * J * sizeof(raw) / 2 > kL2Keep);
         return check_launch();
     }
-    const int cpr = wpr * 32 / CH;
-    const int64_t rows_pad = I;
+    // mask only: threads cover the mask words; dense operand: the padded matrix (rows to 32, columns to 128)
+    const int cpr = mode == 2 ? static_cast<int>(round_up(J, 128) / CH) : wpr * 32 / CH;
+    const int64_t rows_pad = mode == 2 ? round_up(I, 32) : I;
+    if (mode == 2 && !aligned16(values)) return BIMASK_ERR_ALIGN;
     const bool vec_in = aligned16(W) && (ldw * sizeof(raw)) % 16 == 0;
-    const bool vec_out = values && aligned16(values) && J % 8 == 0;
+    const bool vec_out = true;
     const int64_t total = rows_pad * cpr;
     const unsigned grid = static_cast<unsigned>(ceil_div(total, kThreads));
     hipLaunchKernelGGL((k_forward<DT, M, CH>), dim3(grid), dim3(kThreads), 0, s,
@@ -857,7 +858,7 @@ int run_backward_t(const void* W, int64_t I, int64_t J, int64_t ldw, int N, cons
         if (!aligned16(values) || !aligned16(index)) return BIMASK_ERR_ALIGN;
         lds = static_cast<size_t>(img_elems<TC>()) * sizeof(raw) + TC * 32;
     } else if (mode == 2) {
-        vec_out = aligned16(values) && (I * sizeof(raw)) % 16 == 0;
+        if (!aligned16(values)) return BIMASK_ERR_ALIGN;
         lds = static_cast<size_t>(TC) * lds_stride_m2<DT>() * sizeof(raw);
     }
     auto kern = k_backward<DT, M, TC>;

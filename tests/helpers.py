@@ -77,6 +77,18 @@ def untile24(values: np.ndarray, index: np.ndarray, rows: int, cols: int):
     return v[:rows, :cols // 2], xr, pad_zero
 
 
+def untile_dense(values: np.ndarray, rows: int, cols: int):
+    """Fragment-major DENSE operand buffer (ratios with N > 2; layout stated in include/bimask.h) -> row-major
+    [rows, cols] entries, plus a flag telling whether all padding (rows >= rows, cols >= cols) is zero.
+    Pure index permutation."""
+    Rp, Cp = -(-rows // 32) * 32, -(-cols // 128) * 128
+    ks = Cp // 128
+    v = values.reshape(Rp // 32, ks, 4, 2, 2, 32, 8)        # [rt][st][s4][x][hs][r%32][e]
+    v = v.transpose(0, 5, 1, 3, 2, 4, 6).reshape(Rp, Cp)     # k = st*128 + x*64 + s4*16 + hs*8 + e
+    pad_zero = bool((v[rows:] == 0).all() and (v[:, cols:] == 0).all())
+    return v[:rows, :cols], pad_zero
+
+
 class GemmError:
     """Running comparison of a GEMM output with its float64 reference, fed chunk by chunk.
 

@@ -18,7 +18,7 @@ import pytest
 import oracle
 import paper_2302_06058_amd as bm
 from paper_2302_06058_amd import synth
-from helpers import to_dev, i32_dev, words, from_dev_f64, raw_bits, f64_to_raw, untile24, GemmError
+from helpers import to_dev, i32_dev, words, from_dev_f64, raw_bits, f64_to_raw, untile24, untile_dense, GemmError
 
 pytestmark = pytest.mark.gpu
 
@@ -68,7 +68,8 @@ def check_full_layer(layer, t_cap=T_CAP, full_scores_limit=4e8):
         assert same_bits(gv, f64_to_raw(val_o, dt), dt), f"{L.name}: forward values"
         del val_o, idx_o, gv, gi
     else:
-        assert same_bits(raw_bits(vals, dt), f64_to_raw(W64 * B_o, dt), dt), f"{L.name}: forward values"
+        gv, pz = untile_dense(raw_bits(vals, dt), I, J)
+        assert pz and same_bits(gv, f64_to_raw(W64 * B_o, dt), dt), f"{L.name}: forward values"
 
     # permutation search
     Pd = i32_dev(perms)
@@ -102,7 +103,8 @@ def check_full_layer(layer, t_cap=T_CAP, full_scores_limit=4e8):
         del valb_o, idxb_o, gv, gi
     else:
         want = f64_to_raw(np.ascontiguousarray((W64[P, :] * Bbar_o).T), dt)
-        assert same_bits(raw_bits(vb, dt), want, dt), f"{L.name}: backward values"
+        gv, pz = untile_dense(raw_bits(vb, dt), J, I)
+        assert pz and same_bits(gv, want, dt), f"{L.name}: backward values"
 
     # GEMMs on sampled outputs
     Xh = synth.gen_activations(L, T)

@@ -9,7 +9,7 @@ import pytest
 import oracle
 import paper_2302_06058_amd as bm
 from paper_2302_06058_amd import synth
-from helpers import to_dev, i32_dev, words, from_dev_f64, raw_bits, f64_to_raw, rel_err, untile24
+from helpers import to_dev, i32_dev, words, from_dev_f64, raw_bits, f64_to_raw, rel_err, untile24, untile_dense
 
 pytestmark = pytest.mark.gpu
 
@@ -70,6 +70,9 @@ def check_layer(I, J, N, M, dtype, K, seed, kind="normal", T=0):
         assert (got_i == want_i).all() and (got_is == want_i).all(), "forward index"
     else:
         want_v = f64_to_raw(W64 * B_o, dtype)
+        got_v, pz = untile_dense(got_v, I, J)
+        got_vs, pzs = untile_dense(got_vs, I, J)
+        assert pz and pzs, "forward operand padding must be zero"
     # -0.0 weights: a kept -0 stays -0, a dropped slot is +0 -> compare bit patterns of the oracle's
     # exact values, treating +-0 alike
     def same_bits(a, b):
@@ -112,6 +115,9 @@ def check_layer(I, J, N, M, dtype, K, seed, kind="normal", T=0):
         else:
             Wp = W64 if P_h is None else W64[P_h, :]
             want_vb = f64_to_raw(np.ascontiguousarray((Wp * Bbar_o).T), dtype)
+            got_vb, pz = untile_dense(got_vb, J, I)
+            got_vbs, pzs = untile_dense(got_vbs, J, I)
+            assert pz and pzs, "backward operand padding must be zero"
         assert same_bits(got_vb, want_vb), "fused backward values"
         assert same_bits(got_vbs, want_vb), "stand-alone backward values"
 
