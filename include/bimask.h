@@ -51,8 +51,11 @@
  *             q%8 (bits [4(q%8)+3 : 4(q%8)]) of word
  *             ((r/32 * KS + st) * 64 + r%32 + 32*(q/16)) * 2 + (q/8)%2.
  *     Both buffers must be 16-byte aligned.
- *   for N > 2 (4:8, ...): values is the dense masked matrix rows x cols, row-major
- *     (zeros where the mask is 0), and index is not written (may be NULL).
+ *   for N > 2 (4:8, ...): values is the dense masked matrix (zeros where the mask is 0), also
+ *     fragment-major, for the dense 32x32x16 matrix instruction; index is not written (may be NULL).
+ *     Rp * Cp elements; entry (r, k): with st = k / 128, kk = k % 128, element
+ *     ((((( r/32 * KS + st) * 4 + (kk%64)/16) * 2 + kk/64) * 64 + r%32 + 32*((kk%16)/8)) * 8 + kk%8.
+ *     Rows >= rows and columns >= cols are zero padding.  values must be 16-byte aligned.
  *   bimask_operand_elems / bimask_operand_index_words give the buffer sizes.
  *
  * Conventions:
@@ -188,8 +191,9 @@ BIMASK_API int bimask_sparse_gemm_fwd(const void *X, int64_t T, int64_t ldx, con
  *   dY  in  T x I (lddy >= I);   dX  out  T x J (lddx >= J).
  *   workspace: bimask_workspace_bytes(BIMASK_WS_GEMM_BWD, ...) bytes (holds dY[:,P] when the
  *   gather is not fused into the GEMM; 0 = none needed).  bf16 with N <= 2 fuses it for
- *   I <= 512 and for 512 < I <= 2048 with J <= min(I, 512), I and J multiples of 8; the
- *   second range moves rows in 16-byte pieces: dY, dX 16-byte aligned, lddy, lddx
+ *   I <= 512 and for 512 < I <= 2048 with J <= min(I, 512), I and J multiples of 8; bf16 with
+ *   N > 2 for 128 < I <= 2048 with J <= min(I, 512), I and J multiples of 8.  Apart from the
+ *   N <= 2, I <= 512 range these move rows in 16-byte pieces: dY, dX 16-byte aligned, lddy, lddx
  *   multiples of 8, else BIMASK_ERR_ALIGN.                                               */
 BIMASK_API int bimask_sparse_gemm_bwd(const void *dY, int64_t T, int64_t lddy, const int32_t *perm,
                            const void *Wb_values, const uint32_t *Wb_index, int64_t I, int64_t J,

@@ -226,11 +226,11 @@ int bimask_sparse_gemm_bwd(const void* dY, int64_t T, int64_t lddy, const int32_
     const void* act = dY;
     int64_t ldact = lddy;
     if (perm && !gemm_bwd_needs_gather(I, J, dtype, N, M)) {
-        if (I <= 512)      // short contraction: the column gather is fused into the GEMM's token-tile load
+        if (sp && I <= 512)      // short contraction: the column gather is fused into the GEMM's token-tile load
             return launch_gemm_sp24_resident(Wb_values, Wb_index, J, I, dY, lddy, perm, T, dX, lddx, as_stream(stream));
-        // longer rows of g(Y) that still fit LDS whole: gather fused as well, rows move in 16-byte pieces
+        // rows of g(Y) that fit LDS whole: gather fused as well, rows move in 16-byte pieces
         if (!aligned16(dY) || !aligned16(dX) || lddy % 8 || lddx % 8) return BIMASK_ERR_ALIGN;
-        return launch_gemm_sp24_rowres(Wb_values, Wb_index, J, I, dY, lddy, perm, T, dX, lddx, as_stream(stream));
+        return launch_gemm_sp24_rowres(Wb_values, Wb_index, J, I, dY, lddy, perm, T, dX, lddx, as_stream(stream), !sp);
     }
     if (perm) {
         const size_t need = bimask_workspace_bytes(BIMASK_WS_GEMM_BWD, I, J, T, 0, dtype, N, M);

@@ -164,6 +164,10 @@ enum class Sp24Tile { k256x64, k128x64, k256x128, k64x64 };
 int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
                      int64_t ldb, void* C, int64_t ldc, Sp24Tile tile, hipStream_t s);
 
+// dense masked weights (N > 2) on the streaming kernel; BIMASK_ERR_UNSUPPORTED for unaligned operands
+int launch_gemm_dense_frag(const void* A, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb, void* C,
+                           int64_t ldc, hipStream_t s);
+
 // large problems (thousands of weight rows and tokens): 512 x 128 tiles; BIMASK_ERR_UNSUPPORTED otherwise
 bool gemm_sp24_big_shape(int64_t Adim, int64_t K, int64_t T);
 int launch_gemm_sp24_big(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T,
@@ -177,8 +181,10 @@ int launch_gemm_sp24_narrow(const void* A, const uint32_t* meta, int64_t Adim, i
                             int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, hipStream_t s);
 // backward GEMM with whole rows of g(Y) resident in LDS (512 < K <= 2048, Adim <= 512): gather fused;
 // BIMASK_ERR_UNSUPPORTED otherwise
+// (dense: the weight operand is the dense masked matrix of a ratio with N > 2, meta unused)
 int launch_gemm_sp24_rowres(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc,
-                            int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, hipStream_t s);
+                            int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, hipStream_t s,
+                            bool dense = false);
 // true when the backward GEMM needs the gathered copy of g(Y) in the workspace
 // Debug helper: one flag per candidate, 1 = a permutation of 0 .. I-1 (bitmap of I bits in LDS).
 constexpr int64_t kCheckPermsMaxRows = 1 << 20;
@@ -191,5 +197,7 @@ int launch_perm_refine_group(const bimask_group_layer* L, int n, int N, int M, h
 bool gemm_bwd_needs_gather(int64_t I, int64_t J, int dtype, int N, int M);
 // Shapes (output rows Adim, contraction K) the row-resident backward kernel takes.
 bool gemm_sp24_rowres_shape(int64_t Adim, int64_t K);
+// The same for dense masked weights (N > 2), which have no other fused path: 128 < K <= 2048, Adim <= min(K, 512).
+bool gemm_dense_rowres_shape(int64_t Adim, int64_t K);
 
 }  // namespace bimask

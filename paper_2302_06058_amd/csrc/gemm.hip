@@ -461,7 +461,8 @@ int launch_gather_cols(const void* dY, int64_t T, int64_t ld, const int32_t* per
 }
 
 bool gemm_bwd_needs_gather(int64_t I, int64_t J, int dtype, int N, int M) {
-    if (dtype != BIMASK_BF16 || !uses_sp24(N, M)) return true;
+    if (dtype != BIMASK_BF16) return true;
+    if (!uses_sp24(N, M)) return !gemm_dense_rowres_shape(J, I);
     return !(I <= 512 || gemm_sp24_rowres_shape(J, I));
 }
 
@@ -505,6 +506,10 @@ int launch_gemm(const void* A_values, const uint32_t* A_index, int64_t Adim, int
         const Sp24Tile tile = Adim <= 64 ? Sp24Tile::k64x64
                             : (narrow || underfilled ? Sp24Tile::k128x64 : (big ? Sp24Tile::k256x128 : Sp24Tile::k256x64));
         return launch_gemm_sp24(A_values, A_index, Adim, K, Bm, T, ldb, C, ldc, tile, s);
+    }
+    {   // dense masked weights: the streaming kernel on the fragment-major operand; else the general kernel
+        const int rc = launch_gemm_dense_frag(A_values, Adim, K, Bm, T, ldb, C, ldc, s);
+        if (rc != BIMASK_ERR_UNSUPPORTED) return rc;
     }
     return run_dense(A_values, Adim, K, Bm, T, ldb, C, ldc, s);
 }

@@ -64,7 +64,10 @@ __device__ __forceinline__ u32x4 load_guarded(const uint16_t* row, int64_t k, in
 // token rows come from HBM, the weights from L2; a wavefront's loads complete in order, so weight
 // loads queued behind token loads inherit their latency -- with BHALF half of the wavefronts
 // carry nothing but L2 hits.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD, bool BHALF, bool KTAIL>
+// DENSE: the weight operand is the dense masked matrix of a ratio with N > 2 in its fragment-major layout
+// (two 16-byte A fragments per sub-step instead of one compressed fragment plus index bits) and every
+// sparse 32x32x32 instruction becomes two dense 32x32x16 ones on the same token fragment halves.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD, bool BHALF, bool KTAIL, bool DENSE>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int64_t K,
             const uint16_t* __restrict__ Bm, int64_t T, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
@@ -110,8 +113,8 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
     for (int i = 0; i < TM; ++i) {
         int64_t rt = (a0 + wm * WM + i * 32) >> 5;
         rt = rt < rt_last ? rt : rt_last;
-        pa[i] = A + (rt * nk * 256 + lane) * 8;
-        pm[i] = Ameta + (rt * nk * 64 + lane) * 2;
+        pa[i] = A + (rt * nk * (DENSE ? 512 : 256) + lane) * 8;
+        pm[i] = DENSE ? nullptr : Ameta + (rt * nk * 64 + lane) * 2;
     }
     const uint16_t* pb[NB_];
     int sb_off[NB_];
@@ -125,8 +128,9 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
         sb_off[it] = row * kRowBytes + ((g ^ (row & 15)) << 4);
     }
 
-    u32x4 ra[NBUF][TM][4];
-    u32x2 rmeta[NBUF][TM];
+    constexpr int NA = DENSE ? 8 : 4;                   // 16-byte weight fragments per row tile and stage
+    u32x4 ra[NBUF][TM][NA];
+    u32x2 rmeta[NBUF][DENSE ? 1 : TM];
     u32x4 rb[NBUF][NB_];
 
     f32x16 acc[TM][TN];
@@ -151,9 +155,9 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
                 rb[slot][it] = *reinterpret_cast<const u32x4*>(pb[it] + kk);                     \
         }                                                                                        \
         _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                         \
-            _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                     \
-                ra[slot][i][s4] = *reinterpret_cast<const u32x4*>(pa[i] + (kk * 4 + s4 * SK) * 4); \
-            rmeta[slot][i] = *reinterpret_cast<const u32x2*>(pm[i] + kk);                        \
+            _Pragma("unroll") for (int g = 0; g < NA; ++g)                                       \
+                ra[slot][i][g] = *reinterpret_cast<const u32x4*>(pa[i] + (kk * NA + g * SK) * 4); \
+            if constexpr (!DENSE) rmeta[slot][i] = *reinterpret_cast<const u32x2*>(pm[i] + kk);  \
         }                                                                                        \
     }
 
@@ -188,14 +192,26 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
         _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) {                                       \
             if (s4 < 3) BIMASK_READ_FRAGS(bf[(s4 + 1) & 1], s4 + 1)                              \
             _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                     \
-                AFrag af;                                                                        \
-                af.q = ra[u][i][s4];                                                             \
-                const int idx = static_cast<int>(s4 < 2 ? rmeta[u][i].x : rmeta[u][i].y);        \
-                _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                 \
-                    if (s4 & 1)                                                                  \
-                        acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[s4 & 1][j].v, acc[i][j], idx, 0, 1); \
-                    else                                                                         \
-                        acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[s4 & 1][j].v, acc[i][j], idx, 0, 0); \
+                if constexpr (DENSE) {                                                           \
+                    _Pragma("unroll") for (int x = 0; x < 2; ++x) {                              \
+                        AFrag af;                                                                \
+                        af.q = ra[u][i][s4 * 2 + x];                                             \
+                        _Pragma("unroll") for (int j = 0; j < TN; ++j) {                         \
+                            AFrag bh;                                                            \
+                            bh.q = bf[s4 & 1][j].q[x];                                           \
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bh.v, acc[i][j], 0, 0, 0); \
+                        }                                                                        \
+                    }                                                                            \
+                } else {                                                                         \
+                    AFrag af;                                                                    \
+                    af.q = ra[u][i][s4];                                                         \
+                    const int idx = static_cast<int>(s4 < 2 ? rmeta[u][i].x : rmeta[u][i].y);    \
+                    _Pragma("unroll") for (int j = 0; j < TN; ++j) {                             \
+                        if (s4 & 1)                                                              \
+                            acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[s4 & 1][j].v, acc[i][j], idx, 0, 1); \
+                        else                                                                     \
+                            acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf[s4 & 1][j].v, acc[i][j], idx, 0, 0); \
+                    }                                                                            \
                 }                                                                                \
             }                                                                                    \
         }                                                                                        \
@@ -271,11 +287,11 @@ k_gemm_sp24(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, 
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD, bool BHALF, bool KTAIL = false>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool BGUARD, bool BHALF, bool KTAIL = false, bool DENSE = false>
 int run_sp24_t(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb,
              void* C, int64_t ldc, hipStream_t s) {
     using S = SpSmem<BM, BN>;
-    auto kern = k_gemm_sp24<BM, BN, WAVES_M, WAVES_N, PF, BGUARD, BHALF, KTAIL>;
+    auto kern = k_gemm_sp24<BM, BN, WAVES_M, WAVES_N, PF, BGUARD, BHALF, KTAIL, DENSE>;
     if (S::kTotal > 48 * 1024) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 S::kTotal) != hipSuccess) return BIMASK_ERR_HIP;
@@ -299,6 +315,15 @@ int run_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const
     return run_sp24_t<BM, BN, WAVES_M, WAVES_N, 1, true, false>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
 }
 
+// dense masked weights: aligned token rows and a contraction that is a multiple of 8 only (the caller
+// takes the general dense kernel otherwise)
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF>
+int run_dense_frag(const void* A, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb, void* C, int64_t ldc,
+                   hipStream_t s) {
+    if (K % SK == 0) return run_sp24_t<BM, BN, WAVES_M, WAVES_N, PF, false, false, false, true>(A, nullptr, Adim, K, Bm, T, ldb, C, ldc, s);
+    return run_sp24_t<BM, BN, WAVES_M, WAVES_N, PF, false, false, true, true>(A, nullptr, Adim, K, Bm, T, ldb, C, ldc, s);
+}
+
 }  // namespace
 
 // 2:4 GEMM on the fragment-major weight operand.
@@ -316,6 +341,24 @@ int launch_gemm_sp24(const void* A, const uint32_t* meta, int64_t Adim, int64_t 
         case Sp24Tile::k64x64: return run_sp24<64, 64, 2, 2, 2>(A, meta, Adim, K, Bm, T, ldb, C, ldc, s);
     }
     return BIMASK_ERR_UNSUPPORTED;
+}
+
+// The same streaming kernel on the dense masked operand of a ratio with N > 2 (dense 32x32x16 matrix
+// instructions).  BIMASK_ERR_UNSUPPORTED when the token rows are not 16-byte aligned or the contraction is no
+// multiple of 8: the caller then takes the general dense kernel.
+//   128 x 64, 4 wavefronts, 2 stages prefetched; 256 x 128, 8 wavefronts, for large problems; 64 x 64 for at
+//   most 64 weight rows.  (256 x 64 with two row tiles per wavefront would need 128 registers of weight
+//   fragments per stage in flight.)
+int launch_gemm_dense_frag(const void* A, int64_t Adim, int64_t K, const void* Bm, int64_t T, int64_t ldb, void* C,
+                           int64_t ldc, hipStream_t s) {
+    if (!aligned16(A) || !aligned16(Bm) || (ldb * 2) % 16 != 0 || K % 8 != 0) return BIMASK_ERR_UNSUPPORTED;
+    if (Adim <= 64) return run_dense_frag<64, 64, 2, 2, 2>(A, Adim, K, Bm, T, ldb, C, ldc, s);
+    const bool big = ceil_div(Adim, 256) * ceil_div(T, 128) >= 190;
+    // weight dimensions that would leave a fifth or more of the 256-row tiles empty (384 = 1.5 tiles) take 128-row tiles
+    const int64_t w256 = round_up(Adim, 256), w128 = round_up(Adim, 128);
+    const bool wasteful = (w256 - w128) * 5 >= w256;
+    if (big && !wasteful) return run_dense_frag<256, 128, 8, 1, 1>(A, Adim, K, Bm, T, ldb, C, ldc, s);
+    return run_dense_frag<128, 64, 4, 1, 2>(A, Adim, K, Bm, T, ldb, C, ldc, s);
 }
 
 }  // namespace bimask

@@ -32,12 +32,15 @@ constexpr int kRowResThreads = 256;
 
 // TM weight-row tiles (32 rows each) per wavefront pass, NP passes per wavefront: 4 wavefronts cover
 // 4 * NP * TM * 32 weight rows (256 / 384 / 512 for <2,1> / <3,1> / <2,2>)
-template <int TM, int NP>
+// DENSE: the weight operand is the dense masked matrix of a ratio with N > 2 (fragment-major): two 16-byte
+// fragments per sub-step and two dense 32x32x16 instructions instead of one sparse 32x32x32; one stage ahead.
+template <int TM, int NP, bool DENSE>
 __global__ void __launch_bounds__(kRowResThreads, 2)
 k_gemm_sp24_rowres(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int Adim, int K,
                    const uint16_t* __restrict__ Bsrc, int64_t ldb, const int32_t* __restrict__ perm, int64_t T,
                    uint16_t* __restrict__ C, int64_t ldc, int rpt, bool stream_out) {
-    constexpr int PF = 2, NBUF = PF + 1;                 // weight stages in flight beyond the current one
+    constexpr int PF = DENSE ? 1 : 2, NBUF = PF + 1;     // weight stages in flight beyond the current one
+    constexpr int NA = DENSE ? 8 : 4;                    // 16-byte weight fragments per row tile and stage
     extern __shared__ u32x4 smem_u4[];
     uint8_t* smem = reinterpret_cast<uint8_t*>(smem_u4);
     uint16_t* sInv = reinterpret_cast<uint16_t*>(smem);                  // position of column c in a permuted row
@@ -55,14 +58,14 @@ k_gemm_sp24_rowres(const uint16_t* __restrict__ A, const uint32_t* __restrict__ 
     const int ntr = (Adim + 31) >> 5;                                    // 32-row tiles of the weight operand
     const uint16_t* pa[TM];
     const uint32_t* pm[TM];
-    u32x4 ra[NBUF][TM][4];
-    u32x2 rmeta[NBUF][TM];
+    u32x4 ra[NBUF][TM][NA];
+    u32x2 rmeta[NBUF][DENSE ? 1 : TM];
 #define BIMASK_RR_LOAD(slot, st)                                                                 \
     {                                                                                            \
         _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                         \
-            _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                     \
-                ra[slot][i][s4] = *reinterpret_cast<const u32x4*>(pa[i] + ((st) * 4 + s4) * 512); \
-            rmeta[slot][i] = *reinterpret_cast<const u32x2*>(pm[i] + (st) * 128);                \
+            _Pragma("unroll") for (int g = 0; g < NA; ++g)                                       \
+                ra[slot][i][g] = *reinterpret_cast<const u32x4*>(pa[i] + ((st) * NA + g) * 512); \
+            if constexpr (!DENSE) rmeta[slot][i] = *reinterpret_cast<const u32x2*>(pm[i] + (st) * 128); \
         }                                                                                        \
     }
 #define BIMASK_RR_SETUP(ps)                                                                      \
@@ -70,8 +73,8 @@ k_gemm_sp24_rowres(const uint16_t* __restrict__ A, const uint32_t* __restrict__ 
         const int rt0_ = (wave + 4 * (ps)) * TM;                                                 \
         _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                         \
             int rt = rt0_ + i < ntr ? rt0_ + i : ntr - 1;    /* clamped: computed, never stored */ \
-            pa[i] = A + (static_cast<int64_t>(rt) * nks * 256 + lane) * 8;                       \
-            pm[i] = Ameta + (static_cast<int64_t>(rt) * nks * 64 + lane) * 2;                    \
+            pa[i] = A + (static_cast<int64_t>(rt) * nks * (DENSE ? 512 : 256) + lane) * 8;       \
+            pm[i] = DENSE ? nullptr : Ameta + (static_cast<int64_t>(rt) * nks * 64 + lane) * 2;  \
         }                                                                                        \
         _Pragma("unroll") for (int s = 0; s < PF; ++s) {                                         \
             const int stl = s < nks ? s : nks - 1;                                               \
@@ -161,13 +164,22 @@ k_gemm_sp24_rowres(const uint16_t* __restrict__ A, const uint32_t* __restrict__ 
                     bf.q[x] = o;                                                                 \
                 }                                                                                \
                 _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                 \
-                    AFragW af;                                                                   \
-                    af.q = ra[u][i][s4];                                                         \
-                    const int idx = static_cast<int>(s4 < 2 ? rmeta[u][i].x : rmeta[u][i].y);    \
-                    if (s4 & 1)                                                                  \
-                        acc[ps][i] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf.v, acc[ps][i], idx, 0, 1); \
-                    else                                                                         \
-                        acc[ps][i] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf.v, acc[ps][i], idx, 0, 0); \
+                    if constexpr (DENSE) {                                                       \
+                        _Pragma("unroll") for (int x = 0; x < 2; ++x) {                          \
+                            AFragW af, bh;                                                       \
+                            af.q = ra[u][i][s4 * 2 + x];                                         \
+                            bh.q = bf.q[x];                                                      \
+                            acc[ps][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bh.v, acc[ps][i], 0, 0, 0); \
+                        }                                                                        \
+                    } else {                                                                     \
+                        AFragW af;                                                               \
+                        af.q = ra[u][i][s4];                                                     \
+                        const int idx = static_cast<int>(s4 < 2 ? rmeta[u][i].x : rmeta[u][i].y); \
+                        if (s4 & 1)                                                              \
+                            acc[ps][i] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf.v, acc[ps][i], idx, 0, 1); \
+                        else                                                                     \
+                            acc[ps][i] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, bf.v, acc[ps][i], idx, 0, 0); \
+                    }                                                                            \
                 }                                                                                \
             }                                                                                    \
         }
@@ -239,11 +251,12 @@ bool rowres_takes(int64_t Adim, int64_t K) {
 }  // namespace
 
 bool gemm_sp24_rowres_shape(int64_t Adim, int64_t K) { return K > 512 && rowres_takes(Adim, K); }
+bool gemm_dense_rowres_shape(int64_t Adim, int64_t K) { return rowres_takes(Adim, K); }
 
 // Returns BIMASK_ERR_UNSUPPORTED when the shape / alignment is outside this kernel (the caller then
 // gathers g(Y)[:, P] into the workspace and runs the streaming kernel).
 int launch_gemm_sp24_rowres(const void* A, const uint32_t* meta, int64_t Adim, int64_t K, const void* Bsrc,
-                            int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, hipStream_t s) {
+                            int64_t ldb, const int32_t* perm, int64_t T, void* C, int64_t ldc, hipStream_t s, bool dense) {
     if (!perm || T < 1) return BIMASK_ERR_UNSUPPORTED;
     if (!rowres_takes(Adim, K)) return BIMASK_ERR_UNSUPPORTED;
     if (!aligned16(A) || !aligned16(meta) || !aligned16(Bsrc) || !aligned16(C) || ldb % 8 != 0 || ldc % 8 != 0)
@@ -264,11 +277,11 @@ int launch_gemm_sp24_rowres(const void* A, const uint32_t* meta, int64_t Adim, i
     if (best_rpt == 0) return BIMASK_ERR_UNSUPPORTED;
     const bool stream_out = (Adim * 2) % 128 == 0 && ldc % 64 == 0 && (reinterpret_cast<uintptr_t>(C) & 127u) == 0;
     const unsigned grid = static_cast<unsigned>(ceil_div(T, best_rpt));
-#define BIMASK_ROWRES(TM_, NP_)                                                                              \
+#define BIMASK_ROWRES(TM_, NP_, DENSE_)                                                                      \
     {                                                                                                        \
         static DeviceMemo attr_set;                                                                          \
         const int dev = DeviceMemo::device();                                                                \
-        auto kern = k_gemm_sp24_rowres<TM_, NP_>;                                                            \
+        auto kern = k_gemm_sp24_rowres<TM_, NP_, DENSE_>;                                                    \
         if (!attr_set.get(dev)) {                                                                            \
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                     160 * 1024) != hipSuccess) return BIMASK_ERR_HIP;                        \
@@ -278,9 +291,12 @@ int launch_gemm_sp24_rowres(const void* A, const uint32_t* meta, int64_t Adim, i
                            static_cast<int>(Adim), static_cast<int>(K), static_cast<const uint16_t*>(Bsrc), ldb, perm, T, \
                            static_cast<uint16_t*>(C), ldc, best_rpt, stream_out);                            \
     }
-    if (Adim <= 256) BIMASK_ROWRES(2, 1)
-    else if (Adim <= 384) BIMASK_ROWRES(3, 1)
-    else BIMASK_ROWRES(2, 2)
+    if (dense) {
+        if (Adim <= 256) BIMASK_ROWRES(2, 1, true)
+        else BIMASK_ROWRES(2, 2, true)
+    } else if (Adim <= 256) BIMASK_ROWRES(2, 1, false)
+    else if (Adim <= 384) BIMASK_ROWRES(3, 1, false)
+    else BIMASK_ROWRES(2, 2, false)
 #undef BIMASK_ROWRES
     return check_launch();
 }

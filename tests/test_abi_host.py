@@ -33,7 +33,9 @@ def test_workspace_bytes():
     assert bm.workspace_bytes(bm.WS_GEMM_BWD, 4096, 256, 12544, 0, bm.BF16, 2, 4) == 12544 * 4096 * 2
     assert bm.workspace_bytes(bm.WS_GEMM_BWD, 1024, 1024, 12544, 0, bm.BF16, 2, 4) == 12544 * 1024 * 2
     assert bm.workspace_bytes(bm.WS_GEMM_BWD, 1024, 256, 12544, 0, bm.BF16, 2, 4) == 0
-    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 1024, 256, 12544, 0, bm.BF16, 4, 8) == 12544 * 1024 * 2
+    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 1024, 256, 12544, 0, bm.BF16, 4, 8) == 0        # dense weights: fused as well
+    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 384, 1536, 25216, 0, bm.BF16, 4, 8) == 25216 * 384 * 2   # more in- than out-features
+    assert bm.workspace_bytes(bm.WS_GEMM_BWD, 128, 64, 1000, 0, bm.BF16, 4, 8) == 1000 * 128 * 2       # short rows: dense takes the gather pass
     assert bm.workspace_bytes(bm.WS_GEMM_BWD, 256, 2304, 12544, 0, bm.BF16, 2, 4) == 0
     assert bm.workspace_bytes(bm.WS_GEMM_BWD, 256, 2304, 12544, 0, bm.BF16, 1, 4) == 0       # N <= 2: sparse cores too
     assert bm.workspace_bytes(bm.WS_GEMM_BWD, 256, 2304, 12544, 0, bm.BF16, 4, 8) == 12544 * 256 * 2
