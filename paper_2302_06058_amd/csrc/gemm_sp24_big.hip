@@ -39,48 +39,101 @@ constexpr int kBigThreads = 512;        // 8 wavefronts
 constexpr int kBigRows = 512;           // weight rows per workgroup tile
 constexpr int kBigTokens = 128;         // tokens per full tile
 constexpr int kBigStage = kBigTokens * 256;          // LDS bytes of one token stage (128 k = 256 B per token)
-constexpr int kBigSmem = 2 * kBigStage;              // 64 KB: two stages; the output passes reuse it
+constexpr int kBigOut = kBigTokens * 512;            // LDS bytes of the output staging area (one pass of 256 weight rows)
+constexpr int kBigSmem = 2 * kBigStage + kBigOut;    // 128 KB: two token stages + output staging
 
 union BFragB { bf16x16 v; u32x4 q[2]; };
 union AFragB { bf16x8 v; u32x4 q; };
 
-// One workgroup tile: weight rows [a0, a0 + 512) x tokens [t0, t0 + 32 TN).
-template <int TN>
-__device__ __forceinline__ void
-big_tile(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int nk,
-         const uint16_t* __restrict__ Bm, int64_t T, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
-         int64_t a0, int64_t t0, uint8_t* smem) {
-    constexpr int NT = kBigThreads, BN = 32 * TN, TM = 2;
-    constexpr int NB_ = BN * 16 / NT;                    // 16-byte token granules per thread and stage (4 or 2)
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// Work order.  One workgroup per CU, persistent: 256 workgroups, dealt round-robin to the 8 XCDs (each with its own
+// L2).  XCD x owns the contiguous run of `tpx` token tiles starting at x * tpx, against all weight tiles; the tiles
+// of an XCD form a sequence, token tile fastest, and workgroup w of the XCD (w = 0 .. 31) works on tiles w, w + 32,
+// w + 64, ... of it: the 32 workgroups of an XCD are always on 32 consecutive tiles, which share a few weight tiles
+// and all of the XCD's token tiles through its L2.
+//
+// The stages of a workgroup's tiles form ONE sequence kk = 0, 1, 2, ...: the loads that run one and two stages
+// ahead simply run into the next tile's first stages, so a tile's epilogue (accumulators -> LDS staging -> memory)
+// is the only thing between the last matrix instruction of one tile and the first of the next; the next tile's
+// operands are already in registers / LDS by then.
+__global__ void __launch_bounds__(kBigThreads)
+k_gemm_sp24_big(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int nk,
+                const uint16_t* __restrict__ Bm, int64_t T, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
+                int tiles_a, int tiles_t, int tpx) {
+    constexpr int NT = kBigThreads, TN = 4, BN = 32 * TN, TM = 2;
+    constexpr int NB_ = BN * 16 / NT;                    // 16-byte token granules per thread and stage
+    extern __shared__ u32x4 smem_u4[];
+    uint8_t* smem = reinterpret_cast<uint8_t*>(smem_u4);
+    uint8_t* sOut = smem + 2 * kBigStage;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
     const int l32 = lane & 31, h = lane >> 5;
-    const int64_t rt_last = ceil_div(Adim, 32) - 1;
+    const int rt_last = static_cast<int>(ceil_div(Adim, 32)) - 1;
 
-    // weight fragments: per-lane source pointers (row tiles clamped at the edge: loaded, never stored)
-    // (32-bit element offsets from the operands' bases, which sit in scalar registers: the host checks the sizes)
-    int pa[TM], pm[TM];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        int64_t rt = (a0 >> 5) + wave * TM + i;
+    // this workgroup's tiles
+    const int x = blockIdx.x & 7, w = blockIdx.x >> 3, per_xcd = gridDim.x >> 3;
+    const int t_begin = x * tpx < tiles_t ? x * tpx : tiles_t;
+    const int nt = t_begin + tpx < tiles_t ? tpx : tiles_t - t_begin;
+    const int ntiles = nt * tiles_a;                     // tiles of this XCD
+    if (w >= ntiles) return;                             // whole workgroup, before any barrier
+    const int n_mine = (ntiles - w + per_xcd - 1) / per_xcd;
+
+    // Load cursors.  The weight loads run one stage ahead of the matrix instructions and the token loads two; each
+    // has a cursor (tile position in the XCD's sequence, stage inside the tile) that steps through the stages of
+    // ALL of the workgroup's tiles, so the loads run over tile boundaries by themselves (after the last tile they
+    // stay on it: loads that nobody uses).  Everything a cursor determines is uniform and lives in scalar
+    // registers: the addresses are a scalar base plus one per-lane offset that never changes (weights, index
+    // words) or is re-derived per stage from the thread's row (tokens: rows past T are clamped to the last one).
+    struct Cursor { int pos, stage; };
+    auto advance = [&](Cursor& c) {
+        const bool wrap = c.stage + 1 == nk;
+        c.stage = wrap ? 0 : c.stage + 1;
+        c.pos = wrap && c.pos + per_xcd < ntiles ? c.pos + per_xcd : c.pos;
+    };
+    const uint32_t lane16 = lane * 16, lane8 = lane * 8;
+    auto weight_base = [&](const Cursor& c, int i) -> const uint8_t* {       // fragment block (row tile, stage), bytes
+        int rt = (c.pos / nt) * (kBigRows / 32) + wave * TM + i;
+        rt = rt < rt_last ? rt : rt_last;                                     // clamped at the edge: loaded, never stored
+        return reinterpret_cast<const uint8_t*>(A) + (static_cast<int64_t>(rt) * nk + c.stage) * 4096;
+    };
+    auto index_base = [&](const Cursor& c, int i) -> const uint8_t* {
+        int rt = (c.pos / nt) * (kBigRows / 32) + wave * TM + i;
         rt = rt < rt_last ? rt : rt_last;
-        pa[i] = static_cast<int>((rt * nk * 256 + lane) * 8);
-        pm[i] = static_cast<int>((rt * nk * 64 + lane) * 2);
-    }
-    // token tile: thread -> (row, granule) of a stage
-    Bm += t0 * ldb;                                      // the tile's first token row
-    int pb[NB_];
-    int sb_off[NB_];
+        return reinterpret_cast<const uint8_t*>(Ameta) + (static_cast<int64_t>(rt) * nk + c.stage) * 512;
+    };
+    const int row16 = tid >> 4;                          // this thread's token row inside each 32-row group
+    const uint32_t g16 = (tid & 15) * 16;                // and its 16-byte granule of the 256-byte stage row
+    u32x4 rb[NB_];                   // token granules of the next stage
+    auto load_tokens = [&](const Cursor& c) {
+        const int64_t t0 = static_cast<int64_t>(t_begin + c.pos % nt) * kBigTokens;
+        const int last = static_cast<int>(T - t0 < kBigTokens ? T - t0 : kBigTokens) - 1;   // last valid row of the tile
+        const uint8_t* base = reinterpret_cast<const uint8_t*>(Bm + (t0 * ldb + c.stage * 128));
+        const uint32_t ldb2 = static_cast<uint32_t>(2 * ldb);
+#pragma unroll
+        for (int it = 0; it < NB_; ++it) {
+            // row 32 it + row16, clamped to `last`: the group's first row goes into the (scalar) base, the rest
+            // is min(row16, rows of the group that exist - 1); a group with no row at all reads row `last`
+            const int s_it = last - 32 * it;
+            const uint8_t* gb = base + static_cast<int64_t>(s_it >= 0 ? 32 * it : last) * ldb2;
+            const int r = row16 < (s_it > 0 ? s_it : 0) ? row16 : (s_it > 0 ? s_it : 0);
+            rb[it] = *reinterpret_cast<const u32x4*>(gb + (static_cast<uint32_t>(r) * ldb2 + g16));
+        }
+    };
+    // LDS byte offsets, all toggled between the two stage buffers by one XOR per stage: where this thread writes
+    // its token granules (the buffer NOT being read), and where this lane reads token fragments: fo[s4][c] is the
+    // granule of k = 32 s4 + 8 h + 64 c .. + 8 in the row of token l32 (granules are XOR-swizzled by the row).
+    int sb_off[NB_], fo[4][2];
 #pragma unroll
     for (int it = 0; it < NB_; ++it) {
         const int q = tid + NT * it, row = q >> 4, g = q & 15;
-        const int64_t r = t0 + row < T ? row : T - 1 - t0;
-        pb[it] = static_cast<int>(r * ldb + 8 * g);
         sb_off[it] = row * 256 + ((g ^ (row & 15)) << 4);
     }
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) fo[s4][c] = l32 * 256 + (((8 * c + 2 * s4 + h) ^ (l32 & 15)) << 4);
 
     u32x4 ra[TM][4];                 // weight fragments of the current stage, re-loaded sub-step by sub-step
-    u32x2 rmeta[2][TM];              // index words: current and next stage
-    u32x4 rb[NB_];                   // token granules of the next stage
+    u32x2 rmeta[TM], rmeta_next[TM]; // index words: current and next stage
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -89,158 +142,149 @@ big_tile(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int
 #pragma unroll
             for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
-    // prologue: stage 0 of everything
-#pragma unroll
-    for (int it = 0; it < NB_; ++it) rb[it] = *reinterpret_cast<const u32x4*>(Bm + pb[it]);
+    // prologue of the first tile: stage 0 of everything, token stage 0 into LDS buffer 0, token stage 1 requested
+    Cursor cw{w, 0}, ct{w, 0};
+    load_tokens(ct);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        const uint8_t* wb = weight_base(cw, i);
 #pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) ra[i][s4] = *reinterpret_cast<const u32x4*>(A + (pa[i] + s4 * 512));
-        rmeta[0][i] = *reinterpret_cast<const u32x2*>(Ameta + pm[i]);
+        for (int s4 = 0; s4 < 4; ++s4) ra[i][s4] = *reinterpret_cast<const u32x4*>(wb + lane16 + s4 * 1024);
+        rmeta[i] = *reinterpret_cast<const u32x2*>(index_base(cw, i) + lane8);
     }
+#pragma unroll
+    for (int it = 0; it < NB_; ++it) {
+        *reinterpret_cast<u32x4*>(smem + sb_off[it]) = rb[it];
+        sb_off[it] ^= kBigStage;
+    }
+    advance(ct);
+    load_tokens(ct);
+    __syncthreads();
 
-    // token fragment (32 tokens x 32 k of sub-step s4v, token sub-tile j) from the stage buffer sB
+    // token fragment (32 tokens x 32 k of sub-step s4v, token sub-tile j) from the current stage buffer
 #define BIMASK_BIG_FRAG(dst, s4v, j)                                                             \
     {                                                                                            \
-        const uint8_t* base = sB + ((j) * 32 + l32) * 256;                                       \
-        dst.q[0] = *reinterpret_cast<const u32x4*>(base + (((2 * (s4v) + h) ^ (l32 & 15)) << 4));     \
-        dst.q[1] = *reinterpret_cast<const u32x4*>(base + (((8 + 2 * (s4v) + h) ^ (l32 & 15)) << 4)); \
+        dst.q[0] = *reinterpret_cast<const u32x4*>(smem + (fo[s4v][0] + (j) * 8192));            \
+        dst.q[1] = *reinterpret_cast<const u32x4*>(smem + (fo[s4v][1] + (j) * 8192));            \
     }
-#define BIMASK_BIG_MFMA(frag, s4v, j, MS)                                                        \
+#define BIMASK_BIG_MFMA(frag, s4v, j)                                                            \
     {                                                                                            \
         _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                         \
             AFragB af;                                                                           \
             af.q = ra[i][s4v];                                                                   \
-            const int idx = static_cast<int>((s4v) < 2 ? rmeta[MS][i].x : rmeta[MS][i].y);       \
+            const int idx = static_cast<int>((s4v) < 2 ? rmeta[i].x : rmeta[i].y);               \
             if ((s4v) & 1)                                                                       \
                 acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, frag.v, acc[i][j], idx, 0, 1); \
             else                                                                                 \
                 acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(af.v, frag.v, acc[i][j], idx, 0, 0); \
         }                                                                                        \
     }
-    // One stage.  MS = slot of this stage's index words.  The stage's token tile is already in LDS
-    // (buffer kt & 1).  In the middle of the stage's matrix instructions the NEXT stage's token granules
-    // (in registers since the middle of the previous stage) go to the other LDS buffer and the stage
-    // after that is requested, so the only thing between two stages is one barrier.  Loads past the last
-    // stage are clamped to it (never skipped): the number of loads in flight at every wait is the same
-    // in every step.  Token fragments are read kDepth sub-tiles ahead of their matrix instructions.
-    constexpr int kDepth = 3;
-#define BIMASK_BIG_STEP(kt, MS)                                                                  \
+
+    // Epilogue of one tile.  A lane holds 4 consecutive weight rows of one token per accumulator quad; a swap
+    // between the two lane halves gives it 8 consecutive bf16 (16 bytes) of its token's output row.  The tile
+    // leaves through the LDS staging area in two passes of 256 weight rows (wavefronts 0-3, then 4-7) as whole
+    // 512-byte row segments with streaming stores; the accumulators start the next tile at zero.
+    constexpr int UPR = 32;                              // 16-byte units per 256-row segment
+#define BIMASK_BIG_EPILOGUE()                                                                    \
     {                                                                                            \
-        const uint8_t* sB = smem + ((kt) & 1) * kBigStage;                                       \
-        uint8_t* sBw = smem + (((kt) + 1) & 1) * kBigStage;                                      \
-        const int ktn = (kt) + 1 < nk ? (kt) + 1 : nk - 1;                                       \
-        const int ktn2 = (kt) + 2 < nk ? (kt) + 2 : nk - 1;                                      \
-        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
-            rmeta[1 - (MS)][i] = *reinterpret_cast<const u32x2*>(Ameta + (pm[i] + ktn * 128));   \
-        BFragB f[kDepth + 1];                                                                    \
-        _Pragma("unroll") for (int d = 0; d < kDepth; ++d)                                       \
-            BIMASK_BIG_FRAG(f[d], d / TN, d % TN)                                                \
-        _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) {                                       \
-            _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                     \
-                const int q = s4 * TN + j;                                                       \
-                if (q + kDepth < 4 * TN)                                                         \
-                    BIMASK_BIG_FRAG(f[(q + kDepth) % (kDepth + 1)], (q + kDepth) / TN, (q + kDepth) % TN) \
-                BIMASK_BIG_MFMA(f[q % (kDepth + 1)], s4, j, MS)                                  \
+        const int ta = pos / nt, tt = pos - ta * nt;                                             \
+        const int64_t a0 = static_cast<int64_t>(ta) * kBigRows;                                  \
+        const int64_t t0 = static_cast<int64_t>(t_begin + tt) * kBigTokens;                      \
+        _Pragma("unroll 1") for (int pass = 0; pass < 2; ++pass) {                               \
+            __syncthreads();                             /* the previous pass has been read */   \
+            if ((wave >> 2) == pass) {                                                           \
+                _Pragma("unroll") for (int i = 0; i < TM; ++i)                                   \
+                    _Pragma("unroll") for (int j = 0; j < TN; ++j) {                             \
+                        const int t = j * 32 + l32;                                              \
+                        _Pragma("unroll") for (int p = 0; p < 2; ++p) {                          \
+                            const uint32_t xlo = pack_bf16(acc[i][j][8 * p + 0], acc[i][j][8 * p + 1]); \
+                            const uint32_t xhi = pack_bf16(acc[i][j][8 * p + 2], acc[i][j][8 * p + 3]); \
+                            const uint32_t ylo = pack_bf16(acc[i][j][8 * p + 4], acc[i][j][8 * p + 5]); \
+                            const uint32_t yhi = pack_bf16(acc[i][j][8 * p + 6], acc[i][j][8 * p + 7]); \
+                            const auto slo = __builtin_amdgcn_permlane32_swap(xlo, ylo, false, false); \
+                            const auto shi = __builtin_amdgcn_permlane32_swap(xhi, yhi, false, false); \
+                            const u32x4 v = {slo[0], shi[0], slo[1], shi[1]};                    \
+                            const int u = ((wave & 3) * 64 + i * 32 + 16 * p + 8 * h) >> 3;      \
+                            *reinterpret_cast<u32x4*>(sOut + t * 512 + ((u ^ ((2 * t) & (UPR - 1))) << 4)) = v; \
+                        }                                                                        \
+                    }                                                                            \
             }                                                                                    \
-            /* this sub-step's weight registers are free: fetch the next stage's fragment */     \
-            _Pragma("unroll") for (int i = 0; i < TM; ++i)                                       \
-                ra[i][s4] = *reinterpret_cast<const u32x4*>(A + (pa[i] + (ktn * 4 + s4) * 512)); \
-            if (s4 == 1) {                                                                       \
-                _Pragma("unroll") for (int it = 0; it < NB_; ++it)                               \
-                    *reinterpret_cast<u32x4*>(sBw + sb_off[it]) = rb[it];                        \
-                _Pragma("unroll") for (int it = 0; it < NB_; ++it)                               \
-                    rb[it] = *reinterpret_cast<const u32x4*>(Bm + (pb[it] + ktn2 * 128));        \
+            __syncthreads();                                                                     \
+            _Pragma("unroll") for (int it = 0; it < BN * UPR / NT; ++it) {                       \
+                const int q = tid + NT * it, t = q / UPR, u = q % UPR;                           \
+                const u32x4 v = *reinterpret_cast<const u32x4*>(sOut + t * 512 + ((u ^ ((2 * t) & (UPR - 1))) << 4)); \
+                const int64_t a = a0 + pass * 256 + 8 * u;                                       \
+                if (t0 + t < T && a < Adim)              /* Adim is a multiple of 8: whole 16-byte pieces */ \
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(C + (t0 + t) * ldc + a)); \
             }                                                                                    \
-            __builtin_amdgcn_sched_barrier(0);   /* keep the loads where they are written: a stage ahead of their use */ \
         }                                                                                        \
-        __syncthreads();                                                                         \
-    }
-    {   // stage 0 of the token tile into LDS buffer 0, stage 1 into the registers
-#pragma unroll
-        for (int it = 0; it < NB_; ++it) *reinterpret_cast<u32x4*>(smem + sb_off[it]) = rb[it];
-        const int k1 = 1 < nk ? 1 : 0;
-#pragma unroll
-        for (int it = 0; it < NB_; ++it) rb[it] = *reinterpret_cast<const u32x4*>(Bm + (pb[it] + k1 * 128));
-        __syncthreads();
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                       \
+                _Pragma("unroll") for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;               \
     }
 
-    int kt = 0;
+    // The stages of all of the workgroup's tiles, one after the other.  A stage's token tile is already in LDS.  In
+    // the middle of the stage's matrix instructions the NEXT stage's token granules (in registers since the middle
+    // of the previous stage) go to the other LDS buffer and the stage after that is requested; the weight registers
+    // of sub-step s4 are re-loaded with the next stage's fragment as soon as the sub-step's matrix instructions have
+    // been issued.  Token fragments are read kDepth sub-tiles ahead of their matrix instructions.  A stage has no
+    // branch: the matrix instructions of one stage and the next are only separated by the barrier.
+    constexpr int kDepth = 3;
+    int pos = w, kin = 0, left = n_mine;                 // current tile, stage inside it, tiles still to finish
 #pragma unroll 1
-    for (; kt + 2 <= nk; kt += 2) {
-        BIMASK_BIG_STEP(kt, 0)
-        BIMASK_BIG_STEP(kt + 1, 1)
+    for (;;) {
+        advance(cw);
+        // (re-defined per stage so that the per-lane offsets stay 32-bit next to the scalar bases)
+        uint32_t l16 = lane16, l8 = lane8;
+        asm volatile("" : "+v"(l16), "+v"(l8));
+        const uint8_t* wb[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            wb[i] = weight_base(cw, i);
+            rmeta_next[i] = *reinterpret_cast<const u32x2*>(index_base(cw, i) + l8);
+        }
+        BFragB f[kDepth + 1];
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) BIMASK_BIG_FRAG(f[d], d / TN, d % TN)
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int q = s4 * TN + j;
+                if (q + kDepth < 4 * TN) BIMASK_BIG_FRAG(f[(q + kDepth) % (kDepth + 1)], (q + kDepth) / TN, (q + kDepth) % TN)
+                BIMASK_BIG_MFMA(f[q % (kDepth + 1)], s4, j)
+                __builtin_amdgcn_sched_barrier(0);       // fragment reads stay kDepth sub-tiles ahead, in this order
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i) ra[i][s4] = *reinterpret_cast<const u32x4*>(wb[i] + l16 + s4 * 1024);
+            if (s4 == 1) {
+#pragma unroll
+                for (int it = 0; it < NB_; ++it) {
+                    *reinterpret_cast<u32x4*>(smem + sb_off[it]) = rb[it];
+                    sb_off[it] ^= kBigStage;
+                }
+                advance(ct);
+                load_tokens(ct);
+            }
+            __builtin_amdgcn_sched_barrier(0);           // keep the loads where they are written: a stage ahead of their use
+        }
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) fo[s4][c] ^= kBigStage;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) rmeta[i] = rmeta_next[i];
+        __syncthreads();
+        if (++kin == nk) {
+            BIMASK_BIG_EPILOGUE()
+            if (--left == 0) break;
+            pos += per_xcd;
+            kin = 0;
+        }
     }
-    if (kt < nk) BIMASK_BIG_STEP(kt, 0)
-#undef BIMASK_BIG_STEP
+#undef BIMASK_BIG_EPILOGUE
 #undef BIMASK_BIG_MFMA
 #undef BIMASK_BIG_FRAG
-
-    // Epilogue.  A lane holds 4 consecutive weight rows of one token per accumulator quad; a swap
-    // between the two lane halves gives it 8 consecutive bf16 (16 bytes) of its token's output row.
-    // The tile leaves through LDS in two passes of 256 weight rows (wavefronts 0-3, then 4-7) as whole
-    // 512-byte row segments with streaming stores.
-    constexpr int UPR = 32;                              // 16-byte units per 256-row segment
-#pragma unroll 1
-    for (int pass = 0; pass < 2; ++pass) {
-        __syncthreads();                                 // the stage buffers / the previous pass are free
-        if ((wave >> 2) == pass) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const int t = j * 32 + l32;
-#pragma unroll
-                    for (int p = 0; p < 2; ++p) {
-                        const uint32_t xlo = pack_bf16(acc[i][j][8 * p + 0], acc[i][j][8 * p + 1]);
-                        const uint32_t xhi = pack_bf16(acc[i][j][8 * p + 2], acc[i][j][8 * p + 3]);
-                        const uint32_t ylo = pack_bf16(acc[i][j][8 * p + 4], acc[i][j][8 * p + 5]);
-                        const uint32_t yhi = pack_bf16(acc[i][j][8 * p + 6], acc[i][j][8 * p + 7]);
-                        const auto slo = __builtin_amdgcn_permlane32_swap(xlo, ylo, false, false);
-                        const auto shi = __builtin_amdgcn_permlane32_swap(xhi, yhi, false, false);
-                        const u32x4 v = {slo[0], shi[0], slo[1], shi[1]};
-                        const int u = ((wave & 3) * 64 + i * 32 + 16 * p + 8 * h) >> 3;
-                        *reinterpret_cast<u32x4*>(smem + t * 512 + ((u ^ ((2 * t) & (UPR - 1))) << 4)) = v;
-                    }
-                }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int it = 0; it < BN * UPR / NT; ++it) {
-            const int q = tid + NT * it, t = q / UPR, u = q % UPR;
-            const u32x4 v = *reinterpret_cast<const u32x4*>(smem + t * 512 + ((u ^ ((2 * t) & (UPR - 1))) << 4));
-            const int64_t a = a0 + pass * 256 + 8 * u;
-            if (t0 + t < T && a < Adim) {
-                uint16_t* dst = C + (t0 + t) * ldc + a;
-                if (a + 8 <= Adim) {
-                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (a + e < Adim) dst[e] = static_cast<uint16_t>(v[e >> 1] >> (16 * (e & 1)));
-                }
-            }
-        }
-    }
-}
-
-// Work order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2: XCD x owns the
-// contiguous run of `tpx` token tiles starting at x * tpx, against all weight tiles.  Its workgroups start in
-// the order of their position in the XCD's sequence, token tile fastest, so that the ~32 workgroups an XCD
-// runs at one time share a few weight tiles and all of its token tiles through that XCD's L2.
-__global__ void __launch_bounds__(kBigThreads)
-k_gemm_sp24_big(const uint16_t* __restrict__ A, const uint32_t* __restrict__ Ameta, int64_t Adim, int nk,
-                const uint16_t* __restrict__ Bm, int64_t T, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc,
-                int tiles_a, int tiles_t, int tpx) {
-    extern __shared__ u32x4 smem_u4[];
-    uint8_t* smem = reinterpret_cast<uint8_t*>(smem_u4);
-    const int x = blockIdx.x & 7, pos = blockIdx.x >> 3;
-    const int t_begin = x * tpx < tiles_t ? x * tpx : tiles_t;
-    const int nt = t_begin + tpx < tiles_t ? tpx : tiles_t - t_begin;
-    if (pos >= nt * tiles_a) return;                     // whole workgroup, before any barrier
-    const int ta = pos / nt, tt = pos - ta * nt;
-    big_tile<4>(A, Ameta, Adim, nk, Bm, T, ldb, C, ldc, static_cast<int64_t>(ta) * kBigRows,
-                static_cast<int64_t>(t_begin + tt) * kBigTokens, smem);
 }
 
 }  // namespace
@@ -256,9 +300,12 @@ int launch_gemm_sp24_big(const void* A, const uint32_t* meta, int64_t Adim, int6
                          int64_t ldb, void* C, int64_t ldc, hipStream_t s) {
     if (!gemm_sp24_big_shape(Adim, K, T)) return BIMASK_ERR_UNSUPPORTED;
     if (!aligned16(A) || !aligned16(meta) || !aligned16(Bm) || !aligned16(C) || ldb % 8 || ldc % 8) return BIMASK_ERR_UNSUPPORTED;
-    // 32-bit offsets inside the operand and inside a token tile, 32-bit tile counts
-    if (round_up(Adim, 32) * (K / 2) > 0x7FFFFFFFll || 128 * ldb + K > 0x7FFFFFFFll ||
-        ceil_div(T, kBigTokens) * ceil_div(Adim, kBigRows) > 0x0FFFFFFFll) return BIMASK_ERR_UNSUPPORTED;
+    const int tiles_a = static_cast<int>(ceil_div(Adim, kBigRows));
+    const int64_t tiles_t = ceil_div(T, kBigTokens);
+    const int64_t tpx = ceil_div(tiles_t, 8);
+    // 32-bit element offsets inside the weight operand and inside the token matrix, 32-bit tile counts
+    if (round_up(Adim, 32) * (K / 2) > 0x7FFFFFFFll || T * ldb + K > 0x7FFFFFFFll || tiles_t * tiles_a > 0x0FFFFFFFll)
+        return BIMASK_ERR_UNSUPPORTED;
     static DeviceMemo attr_set;
     const int dev = DeviceMemo::device();
     auto kern = k_gemm_sp24_big;
@@ -267,10 +314,8 @@ int launch_gemm_sp24_big(const void* A, const uint32_t* meta, int64_t Adim, int6
             return BIMASK_ERR_HIP;
         attr_set.set(dev, 1);
     }
-    const int tiles_a = static_cast<int>(ceil_div(Adim, kBigRows));
-    const int64_t tiles_t = ceil_div(T, kBigTokens);
-    const int64_t tpx = ceil_div(tiles_t, 8);
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(tpx * tiles_a * 8)), dim3(kBigThreads), kBigSmem, s,
+    // 256 persistent workgroups: one per CU (128 KB of LDS and 256 registers per wavefront leave room for one)
+    hipLaunchKernelGGL(kern, dim3(256), dim3(kBigThreads), kBigSmem, s,
                        static_cast<const uint16_t*>(A), meta, Adim, static_cast<int>(K / 128),
                        static_cast<const uint16_t*>(Bm), T, ldb, static_cast<uint16_t*>(C), ldc, tiles_a,
                        static_cast<int>(tiles_t), static_cast<int>(tpx));
