@@ -22,8 +22,9 @@
 // dense-equivalent against 1.5 with 256 x 128 tiles.  Timing-only ablations of this kernel: without the
 // weight loads -15 %, with both load streams always hitting L2 -17 %, matrix instructions alone
 // (no loads, no fragment reads) -30 %: what remains is the sustained rate of the matrix pipe itself plus
-// the per-tile prologue / epilogue.  Half tiles (512 x 64) for the last, partial round over the chip were
-// measured and dropped: the round they save costs less than their lower efficiency (436 vs 460 us).
+// the per-tile epilogue.  Half tiles (512 x 64, and 256 x 128 inside the persistent loop) for the last,
+// partial round over the chip were measured and dropped: the half round they save costs less than their
+// lower efficiency and the second copy of the stage code.
 #include "common.hpp"
 
 namespace bimask {
