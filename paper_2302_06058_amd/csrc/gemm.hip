@@ -373,6 +373,125 @@ k_gather_cols_lds(const raw* __restrict__ in, int64_t T, int64_t ld, const int32
     }
 }
 
+// The same gather for bf16 rows that are 16-byte aligned and a multiple of 8 long, with R = 2, 4 or 8 token rows
+// per tile INTERLEAVED in LDS: element (column c, row r) sits at 2 (c R + r), so one LDS read of 2 R bytes at
+// a permuted column returns that column for all R rows (R times fewer LDS reads than row-major tiles).  A
+// thread owns the same CPT chunks of 8 columns in every tile, for the load (R global 16-byte loads per chunk,
+// an 8 x R transpose of half-words in registers, R contiguous 16-byte LDS writes) and for the emit (8 LDS
+// reads, the transpose back, R 16-byte stores), and keeps the chunks' permutation entries in registers as
+// LDS byte offsets.  Persistent grid; the loads of the next tile are in flight while a tile is emitted.
+// Measured at 8192 tokens: 8 KB rows (R = 8) 29 us against 38 us row-major, 22 KB rows (R = 2) 87 us against
+// 92 us; a plain device-to-device copy of the same arrays takes 24 / 64 us.
+template <int R> struct GatherVec;
+template <> struct GatherVec<2> { using type = uint32_t; };
+template <> struct GatherVec<4> { using type = uint2; };
+template <> struct GatherVec<8> { using type = uint4; };
+
+template <int R, int CPT>
+__global__ void __launch_bounds__(kThreads)
+k_gather_cols_rows(const uint16_t* __restrict__ in, int64_t T, int64_t ld, const int32_t* __restrict__ perm, int I,
+                   uint16_t* __restrict__ out) {
+    using vec = typename GatherVec<R>::type;
+    constexpr int W = R / 2;                             // dwords per column group
+    extern __shared__ uint4 gather_smem[];
+    uint8_t* buf = reinterpret_cast<uint8_t*>(gather_smem);
+    const int chunks = I / 8;
+    const int64_t ntiles = ceil_div(T, R);
+    int p[CPT][8];
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+        const int c = threadIdx.x + kThreads * k;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) p[k][e] = c < chunks ? perm[c * 8 + e] * (2 * R) : 0;
+    }
+    // the loads of a tile are issued before the previous tile is emitted: they are in flight during its LDS reads and stores
+    uint4 v[CPT][R];
+    auto load_tile = [&](int64_t tile) {
+        const int64_t t0 = tile * R;
+#pragma unroll
+        for (int k = 0; k < CPT; ++k) {
+            const int c = threadIdx.x + kThreads * k;
+            if (c < chunks) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const int64_t t = t0 + r < T ? t0 + r : T - 1;      // rows beyond T repeat the last row (never stored)
+                    v[k][r] = *reinterpret_cast<const uint4*>(in + t * ld + c * 8);
+                }
+            }
+        }
+    };
+    if (static_cast<int64_t>(blockIdx.x) < ntiles) load_tile(blockIdx.x);
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t t0 = tile * R;
+        __syncthreads();                                 // the previous tile has been emitted
+#pragma unroll
+        for (int k = 0; k < CPT; ++k) {
+            const int c = threadIdx.x + kThreads * k;
+            if (c < chunks) {
+                // 8 columns x R rows: column e of the chunk -> R half-words (rows 0 .. R-1)
+                uint32_t o[8][W];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+#pragma unroll
+                    for (int w = 0; w < W; ++w) {
+                        const uint32_t a = reinterpret_cast<const uint32_t*>(&v[k][2 * w])[e >> 1];
+                        const uint32_t b = reinterpret_cast<const uint32_t*>(&v[k][2 * w + 1])[e >> 1];
+                        o[e][w] = (e & 1) ? __builtin_amdgcn_perm(b, a, 0x07060302u) : __builtin_amdgcn_perm(b, a, 0x05040100u);
+                    }
+                uint32_t* dst = reinterpret_cast<uint32_t*>(buf + static_cast<size_t>(c) * (16 * R));
+#pragma unroll
+                for (int q = 0; q < 8 * W; ++q)          // R 16-byte writes: 8 columns x W dwords
+                    if ((q & 3) == 0)
+                        *reinterpret_cast<uint4*>(dst + q) = make_uint4(o[(q + 0) / W][(q + 0) % W], o[(q + 1) / W][(q + 1) % W],
+                                                                        o[(q + 2) / W][(q + 2) % W], o[(q + 3) / W][(q + 3) % W]);
+            }
+        }
+        __syncthreads();
+        if (tile + gridDim.x < ntiles) load_tile(tile + gridDim.x);
+#pragma unroll
+        for (int k = 0; k < CPT; ++k) {
+            const int c = threadIdx.x + kThreads * k;
+            if (c < chunks) {
+                uint32_t g[8][W];                        // permuted column e of the chunk, R rows
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const vec x = *reinterpret_cast<const vec*>(buf + p[k][e]);
+#pragma unroll
+                    for (int w = 0; w < W; ++w) g[e][w] = reinterpret_cast<const uint32_t*>(&x)[w];
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    if (t0 + r < T) {
+                        uint32_t wd[4];
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            const uint32_t a = g[2 * d][r >> 1], b = g[2 * d + 1][r >> 1];
+                            wd[d] = (r & 1) ? __builtin_amdgcn_perm(b, a, 0x07060302u) : __builtin_amdgcn_perm(b, a, 0x05040100u);
+                        }
+                        typedef unsigned int gv4 __attribute__((ext_vector_type(4)));
+                        const gv4 pk = {wd[0], wd[1], wd[2], wd[3]};
+                        __builtin_nontemporal_store(pk, reinterpret_cast<gv4*>(out + (t0 + r) * I + c * 8));
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int R, int CPT>
+int run_gather_rows(const void* dY, int64_t T, int64_t ld, const int32_t* perm, int64_t I, void* out, hipStream_t s) {
+    auto kern = k_gather_cols_rows<R, CPT>;
+    const size_t lds = static_cast<size_t>(I) * 2 * R;
+    if (lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess) return BIMASK_ERR_HIP;
+    const int64_t ntiles = ceil_div(T, R);
+    const int64_t per_cu = static_cast<int64_t>(160 * 1024 / lds) < 4 ? static_cast<int64_t>(160 * 1024 / lds) : 4;
+    const unsigned grid = static_cast<unsigned>(ntiles < 256 * per_cu ? ntiles : 256 * per_cu);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, static_cast<const uint16_t*>(dY), T, ld, perm,
+                       static_cast<int>(I), static_cast<uint16_t*>(out));
+    return check_launch();
+}
+
 template <typename raw, int CPT>
 int run_gather_lds(const void* dY, int64_t T, int64_t ld, const int32_t* perm, int64_t I, void* out, int rows,
                    size_t lds, unsigned grid, bool vec_in, bool vec_out, hipStream_t s) {
@@ -428,6 +547,20 @@ int launch_gather_cols(const void* dY, int64_t T, int64_t ld, const int32_t* per
         const bool vec_out = aligned16(out) && (I * esz) % 16 == 0;
         const int64_t ntiles = ceil_div(T, rows);
         const int64_t cpt = ceil_div(ceil_div(I, E), kThreads);      // 16-byte output columns per thread
+        // long aligned bf16 rows with enough of them: row-interleaved tiles
+        if (dtype == BIMASK_BF16 && vec_in && vec_out && I % 8 == 0 && cpt >= 2 && cpt <= 6 && T >= 2048 && row_bytes * 2 <= 64 * 1024) {
+            const int R = row_bytes * 8 <= 64 * 1024 ? 8 : row_bytes * 4 <= 64 * 1024 ? 4 : 2;
+#define BIMASK_GATHER_ROWS(RR)                                                                  \
+            {                                                                                    \
+                if (cpt <= 2) return run_gather_rows<RR, 2>(dY, T, ld, perm, I, out, s);        \
+                if (cpt <= 4) return run_gather_rows<RR, 4>(dY, T, ld, perm, I, out, s);        \
+                return run_gather_rows<RR, 6>(dY, T, ld, perm, I, out, s);                      \
+            }
+            if (R == 8) BIMASK_GATHER_ROWS(8)
+            if (R == 4) BIMASK_GATHER_ROWS(4)
+            BIMASK_GATHER_ROWS(2)
+#undef BIMASK_GATHER_ROWS
+        }
         // long rows: persistent grid (3 workgroups per CU), permutation entries in registers
         const bool persistent = cpt >= 2 && cpt <= 8;
         const unsigned grid = static_cast<unsigned>(persistent && ntiles > 768 ? 768 : ntiles);

@@ -96,6 +96,8 @@ SP24_SHAPES = [
     (4096, 2048, 8200),  # forward: 512 x 128 tiles (8 x 65 tiles, the last token tile ragged) / separate gather, streaming 256 x 128
     (3200, 1152, 22037), # 512 x 128 tiles both ways (the backward one behind the separate gather): 6.25 and 2.25 weight tiles, ragged last token tile
     (1024, 1152, 65600), # 512 x 128 tiles: two / three weight tiles, 513 token tiles (65 per XCD, the last XCD's run shorter)
+    (4352, 256, 2051),   # ... / separate gather with four token rows interleaved per tile (8.5 KB rows), ragged last tile
+    (8704, 128, 2305),   # ... / separate gather with two token rows interleaved per tile (17 KB rows), one row in the last tile
     (4224, 1024, 11200), # 512 x 128 tiles whose left-over does not fit one round of half tiles: 24 full + 11 half items after the whole rounds
 ]
 
