@@ -98,7 +98,7 @@ SP24_SHAPES = [
     (1024, 1152, 65600), # 512 x 128 tiles: two / three weight tiles, 513 token tiles (65 per XCD, the last XCD's run shorter)
     (4352, 256, 2051),   # ... / separate gather with four token rows interleaved per tile (8.5 KB rows), ragged last tile
     (8704, 128, 2305),   # ... / separate gather with two token rows interleaved per tile (17 KB rows), one row in the last tile
-    (4224, 1024, 11200), # 512 x 128 tiles whose left-over does not fit one round of half tiles: 24 full + 11 half items after the whole rounds
+    (4224, 1024, 11200), # 512 x 128 tiles: nine weight tiles (the last with 128 rows) x 88 token tiles, 99 tiles per XCD on 32 workgroups (3 or 4 each)
 ]
 
 
