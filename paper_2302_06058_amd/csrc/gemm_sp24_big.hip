@@ -19,12 +19,13 @@
 //     the current stage's matrix instructions, so one barrier is all that separates two stages;
 //   * token fragments are read three 32-token sub-tiles ahead of the matrix instructions that use them.
 // Measured on the MLP block (11008 x 4096 and 4096 x 11008 weights, 8192 tokens): 1.75-2.0 PFLOP/s
-// dense-equivalent against 1.5 with 256 x 128 tiles.  Timing-only ablations of this kernel: without the
-// weight loads -15 %, with both load streams always hitting L2 -17 %, matrix instructions alone
-// (no loads, no fragment reads) -30 %: what remains is the sustained rate of the matrix pipe itself plus
-// the per-tile epilogue.  Half tiles (512 x 64, and 256 x 128 inside the persistent loop) for the last,
-// partial round over the chip were measured and dropped: the half round they save costs less than their
-// lower efficiency and the second copy of the stage code.
+// dense-equivalent against 1.5 with 256 x 128 tiles.  The kernel takes the same time with every matrix
+// instruction replaced by one ALU operation: what bounds it is each CU's vector-memory path (104 KB per
+// stage, every line an L1 miss by construction, ~53 lines in flight per CU at a mean L2 round trip of 250
+// clocks: 27 B/clk/CU), and the tile already holds as many accumulators as the register file allows.
+// Half tiles (512 x 64, and 256 x 128 inside the persistent loop) for the last, partial round over the
+// chip were measured and dropped: the half round they save costs less than their lower efficiency and
+// the second copy of the stage code.
 #include "common.hpp"
 
 namespace bimask {
