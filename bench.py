@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--layer", type=int, default=-1,
                     help="layer index inside the configuration; -1 = every matrix of configs 1, 2, 5 in one step, layer 0 of configs 3, 4")
     ap.add_argument("--no-secondary", action="store_true", help="skip the config-2 figures that accompany the config-5 line")
+    ap.add_argument("--no-context", action="store_true",
+                    help="skip the dense library GEMMs (torch.matmul) timed beside the step for context")
     ap.add_argument("--copies", type=int, default=0, help="rotating buffer copies (0 = enough for 1 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown-reps", type=int, default=30)
@@ -719,7 +721,38 @@ def measured_traffic(config):
     return out
 
 
-def measure(args, config, layer_sel, steps, warmup, with_cpu):
+def dense_context(runs, copies, reps=10):
+    """Context only, never part of `value`: the DENSE bf16 GEMMs of the same shapes through the library behind
+    torch.matmul, on the same rotating activations -- the forward and backward products the sparse GEMMs replace
+    (Eq. 3, Eq. 10 without masks) and the weight gradient dW = dY^T X, which the method leaves dense (Sec. 3.1,
+    Limitations).  Microseconds per call, HIP events around each call."""
+    import torch
+    out = {}
+    for r in runs:
+        if r.W.dtype != torch.bfloat16:
+            continue
+        Wt = r.W.t()
+        ops = {"dense_fwd  X W^T": lambda c: torch.matmul(r.X[c], Wt),
+               "dense_bwd  dY W": lambda c: torch.matmul(r.dY[c], r.W),
+               "dense_dW  dY^T X": lambda c: torch.matmul(r.dY[c].t(), r.X[c])}
+        d = {}
+        for name, fn in ops.items():
+            for i in range(3):
+                fn(i % copies)
+            pairs = []
+            for i in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(); fn(i % copies); b.record()
+                pairs.append((a, b))
+            torch.cuda.synchronize()
+            ts = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)
+            d[name] = round(ts[len(ts) // 2], 2)
+        out[r.layer.name] = d
+    torch.cuda.empty_cache()
+    return out
+
+
+def measure(args, config, layer_sel, steps, warmup, with_cpu, with_context=False):
     """Times `steps` steps of the chosen workload and returns the fields of the JSON line."""
     import torch
     import paper_2302_06058_amd as bm
@@ -845,6 +878,11 @@ def measure(args, config, layer_sel, steps, warmup, with_cpu):
         "amortised": {"delta_t": args.delta_t, "ms_per_step_without_search": round(ms_no_search, 5),
                       "ms_per_step_search_every_delta_t": round(ms_no_search + max(ms_per_step - ms_no_search, 0.0) / args.delta_t, 5)},
     }
+    if with_context:
+        out["context"] = {"dense_library_gemm_us": dense_context(runs, copies),
+                          "note": "torch.matmul on dense bf16 operands of the same shapes, median of 10 calls; outside the timed "
+                                  "region and not part of value: what the sparse forward / backward GEMMs replace, and the dense "
+                                  "weight gradient the method keeps"}
     del runs
     torch.cuda.empty_cache()
     if with_cpu:
@@ -887,7 +925,8 @@ def main():
     if args.network_step:
         return network_step(args)
 
-    res, layers = measure(args, args.config, args.layer, args.steps, args.warmup, not args.no_cpu_baseline)
+    res, layers = measure(args, args.config, args.layer, args.steps, args.warmup, not args.no_cpu_baseline,
+                          with_context=not args.no_context)
     out = {
         "metric": "Bi-Mask per-layer step time (mask+perm+fwd/bwd GEMM)",
         "value": res["ms_per_step"], "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
