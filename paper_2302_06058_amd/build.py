@@ -45,7 +45,9 @@ def build_lib(verbose: bool = False, only=None) -> str:
     return LIB
 
 
-TOOLS = ["l2_gather_ceiling"]     # stand-alone measurement programs under csrc/tools/ (not part of the library)
+# stand-alone measurement programs under csrc/tools/ (not part of the library): source file, extra link arguments
+TOOLS = {"l2_gather_ceiling": ("l2_gather_ceiling.hip", []),
+         "vendor_sparse_gemm": ("vendor_sparse_gemm.cpp", ["-L/opt/rocm/lib", "-lhipsparselt"])}
 BIN = os.path.join(HERE, "bin")
 
 
@@ -54,10 +56,10 @@ def build_tools(verbose: bool = False):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(BIN, exist_ok=True)
     out = []
-    for t in TOOLS:
+    for t, (src, link) in TOOLS.items():
         exe = os.path.join(BIN, t)
         _run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-              os.path.join(CSRC, "tools", t + ".hip"), "-o", exe], verbose)
+              os.path.join(CSRC, "tools", src), "-o", exe] + link, verbose)
         out.append(exe)
     return out
 
