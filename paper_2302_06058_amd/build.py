@@ -58,8 +58,15 @@ def build_tools(verbose: bool = False):
     out = []
     for t, (src, link) in TOOLS.items():
         exe = os.path.join(BIN, t)
-        _run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-              os.path.join(CSRC, "tools", src), "-o", exe] + link, verbose)
+        try:
+            _run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                  os.path.join(CSRC, "tools", src), "-o", exe] + link, verbose)
+        except RuntimeError as e:
+            if not link:
+                raise
+            # a context tool that needs a vendor library this machine does not have: the library itself is unaffected
+            print(f"skipping tool {t}: {str(e).splitlines()[-1]}", file=sys.stderr)
+            continue
         out.append(exe)
     return out
 
