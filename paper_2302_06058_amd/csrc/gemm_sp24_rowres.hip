@@ -56,6 +56,9 @@ k_gemm_sp24_rowres(const uint16_t* __restrict__ A, const uint32_t* __restrict__ 
     // ---- weight fragments of this wavefront's first pass: requested before anything else, they do
     // not depend on the token rows
     const int ntr = (Adim + 31) >> 5;                                    // 32-row tiles of the weight operand
+    // With few token tiles the launcher splits the weight rows over blockIdx.y: this workgroup takes the row tiles
+    // [rtb, rtb + 4 NP TM) and writes the matching columns of its output rows.
+    const int rtb = blockIdx.y * (4 * NP * TM);
     const uint16_t* pa[TM];
     const uint32_t* pm[TM];
     u32x4 ra[NBUF][TM][NA];
@@ -70,7 +73,7 @@ k_gemm_sp24_rowres(const uint16_t* __restrict__ A, const uint32_t* __restrict__ 
     }
 #define BIMASK_RR_SETUP(ps)                                                                      \
     {                                                                                            \
-        const int rt0_ = (wave + 4 * (ps)) * TM;                                                 \
+        const int rt0_ = rtb + (wave + 4 * (ps)) * TM;                                           \
         _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                         \
             int rt = rt0_ + i < ntr ? rt0_ + i : ntr - 1;    /* clamped: computed, never stored */ \
             pa[i] = A + (static_cast<int64_t>(rt) * nks * (DENSE ? 512 : 256) + lane) * 8;       \
@@ -139,7 +142,7 @@ k_gemm_sp24_rowres(const uint16_t* __restrict__ A, const uint32_t* __restrict__ 
 
 #pragma unroll
     for (int ps = 0; ps < NP; ++ps) {
-        const int rt0 = (wave + 4 * ps) * TM;                            // first row tile of this pass
+        const int rt0 = rtb + (wave + 4 * ps) * TM;                      // first row tile of this pass
         if (rt0 >= ntr) break;                                           // wave-uniform
         if (ps > 0) BIMASK_RR_SETUP(ps)
         // one stage = 128 contraction indices: 4 x TM sparse matrix instructions; loads past the
@@ -202,10 +205,12 @@ k_gemm_sp24_rowres(const uint16_t* __restrict__ A, const uint32_t* __restrict__ 
     // ---- 4. output: a lane holds 4 consecutive weight rows of its token per accumulator quad; a swap
     // between the lane halves gives it 8 consecutive bf16 of the token's output row (16 bytes, two
     // 8-byte LDS stores); the tile then leaves as whole rows
-    const int pitchC = 2 * Adim + 8;
+    const int a_base = rtb * 32;                                         // first weight row (= output column) of this workgroup
+    const int width = Adim - a_base < 4 * NP * TM * 32 ? Adim - a_base : 4 * NP * TM * 32;
+    const int pitchC = 2 * width + 8;
 #pragma unroll
     for (int ps = 0; ps < NP; ++ps) {
-        const int rt0 = (wave + 4 * ps) * TM;
+        const int rt0 = rtb + (wave + 4 * ps) * TM;
         if (rt0 >= ntr) break;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -219,7 +224,7 @@ k_gemm_sp24_rowres(const uint16_t* __restrict__ A, const uint32_t* __restrict__ 
                 const auto shi = __builtin_amdgcn_permlane32_swap(xhi, yhi, false, false);
                 const int a0 = (rt0 + i) * 32 + 16 * p + 8 * h;          // first of this lane's 8 weight rows
                 if (l32 < rows && a0 + 8 <= Adim) {                      // Adim is a multiple of 8
-                    u32x2* d = reinterpret_cast<u32x2*>(rowsA + l32 * pitchC + 2 * a0);
+                    u32x2* d = reinterpret_cast<u32x2*>(rowsA + l32 * pitchC + 2 * (a0 - a_base));
                     d[0] = (u32x2){slo[0], shi[0]};
                     d[1] = (u32x2){slo[1], shi[1]};
                 }
@@ -227,14 +232,14 @@ k_gemm_sp24_rowres(const uint16_t* __restrict__ A, const uint32_t* __restrict__ 
     }
     __syncthreads();
     {
-        const int UPR = Adim >> 3;
+        const int UPR = width >> 3;
         const int total = rows * UPR;
         for (int c = tid; c < total; c += kRowResThreads) {
             const int t = c / UPR, u = c - t * UPR;
             const u32x2* p = reinterpret_cast<const u32x2*>(rowsA + t * pitchC + 16 * u);
             const u32x2 lo = p[0], hi = p[1];
             const u32x4 o = {lo.x, lo.y, hi.x, hi.y};
-            u32x4* dst = reinterpret_cast<u32x4*>(C + (t0 + t) * ldc + 8 * u);
+            u32x4* dst = reinterpret_cast<u32x4*>(C + (t0 + t) * ldc + a_base + 8 * u);
             if (stream_out) __builtin_nontemporal_store(o, dst);
             else *dst = o;
         }
@@ -277,6 +282,12 @@ int launch_gemm_sp24_rowres(const void* A, const uint32_t* meta, int64_t Adim, i
     if (best_rpt == 0) return BIMASK_ERR_UNSUPPORTED;
     const bool stream_out = (Adim * 2) % 128 == 0 && ldc % 64 == 0 && (reinterpret_cast<uintptr_t>(C) & 127u) == 0;
     const unsigned grid = static_cast<unsigned>(ceil_div(T, best_rpt));
+    // Few token tiles (less than half the CUs busy) and more than 256 weight rows: every workgroup would stream the
+    // whole weight operand through one CU for its 32 tokens.  Split the rows over blockIdx.y in pieces of 256:
+    // twice (or three, four times) the workgroups, each streaming a half (third, quarter) of the weights; the token
+    // rows are gathered once per piece, from L2 after the first.
+    const bool split = !dense && grid <= 128 && Adim > 256;
+    const unsigned nsplit = split ? static_cast<unsigned>(ceil_div(Adim, 256)) : 1u;
 #define BIMASK_ROWRES(TM_, NP_, DENSE_)                                                                      \
     {                                                                                                        \
         static DeviceMemo attr_set;                                                                          \
@@ -287,14 +298,14 @@ int launch_gemm_sp24_rowres(const void* A, const uint32_t* meta, int64_t Adim, i
                                     160 * 1024) != hipSuccess) return BIMASK_ERR_HIP;                        \
             attr_set.set(dev, 1);                                                                            \
         }                                                                                                    \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kRowResThreads), best_lds, s, static_cast<const uint16_t*>(A), meta, \
+        hipLaunchKernelGGL(kern, dim3(grid, nsplit), dim3(kRowResThreads), best_lds, s, static_cast<const uint16_t*>(A), meta, \
                            static_cast<int>(Adim), static_cast<int>(K), static_cast<const uint16_t*>(Bsrc), ldb, perm, T, \
                            static_cast<uint16_t*>(C), ldc, best_rpt, stream_out);                            \
     }
     if (dense) {
         if (Adim <= 256) BIMASK_ROWRES(2, 1, true)
         else BIMASK_ROWRES(2, 2, true)
-    } else if (Adim <= 256) BIMASK_ROWRES(2, 1, false)
+    } else if (Adim <= 256 || split) BIMASK_ROWRES(2, 1, false)
     else if (Adim <= 384) BIMASK_ROWRES(3, 1, false)
     else BIMASK_ROWRES(2, 2, false)
 #undef BIMASK_ROWRES
