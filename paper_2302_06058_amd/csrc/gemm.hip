@@ -547,19 +547,12 @@ int launch_gather_cols(const void* dY, int64_t T, int64_t ld, const int32_t* per
         const bool vec_out = aligned16(out) && (I * esz) % 16 == 0;
         const int64_t ntiles = ceil_div(T, rows);
         const int64_t cpt = ceil_div(ceil_div(I, E), kThreads);      // 16-byte output columns per thread
-        // long aligned bf16 rows with enough of them: row-interleaved tiles
-        if (dtype == BIMASK_BF16 && vec_in && vec_out && I % 8 == 0 && cpt >= 2 && cpt <= 6 && T >= 2048 && row_bytes * 2 <= 64 * 1024) {
-            const int R = row_bytes * 8 <= 64 * 1024 ? 8 : row_bytes * 4 <= 64 * 1024 ? 4 : 2;
-#define BIMASK_GATHER_ROWS(RR)                                                                  \
-            {                                                                                    \
-                if (cpt <= 2) return run_gather_rows<RR, 2>(dY, T, ld, perm, I, out, s);        \
-                if (cpt <= 4) return run_gather_rows<RR, 4>(dY, T, ld, perm, I, out, s);        \
-                return run_gather_rows<RR, 6>(dY, T, ld, perm, I, out, s);                      \
-            }
-            if (R == 8) BIMASK_GATHER_ROWS(8)
-            if (R == 4) BIMASK_GATHER_ROWS(4)
-            BIMASK_GATHER_ROWS(2)
-#undef BIMASK_GATHER_ROWS
+        // long aligned bf16 rows with enough of them: row-interleaved tiles.  Rows of 4-8 KB (2 chunks of 8 columns
+        // per thread) fit 8 to a tile, of 8-16 KB (3-4 chunks) 4, of 16-24 KB (5-6 chunks) 2.
+        if (dtype == BIMASK_BF16 && vec_in && vec_out && I % 8 == 0 && cpt >= 2 && cpt <= 6 && T >= 2048) {
+            if (cpt <= 2) return run_gather_rows<8, 2>(dY, T, ld, perm, I, out, s);
+            if (cpt <= 4) return run_gather_rows<4, 4>(dY, T, ld, perm, I, out, s);
+            return run_gather_rows<2, 6>(dY, T, ld, perm, I, out, s);
         }
         // long rows: persistent grid (3 workgroups per CU), permutation entries in registers
         const bool persistent = cpt >= 2 && cpt <= 8;
