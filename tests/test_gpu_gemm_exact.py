@@ -125,3 +125,33 @@ def test_dense_core_gemms_4of8_are_exact(I, J, T, perm):
 def test_fp32_gemms_are_exact(N, M):
     exact_layer(64, 128, 40, N, M, synth.F32, 7400 + M)
     exact_layer(136, 264, 300, N, M, synth.F32, 7500 + M)
+
+
+def test_large_shapes_with_padded_leading_dimensions():
+    """The 512 x 128 forward kernel and the row-interleaved gather of the backward pass on activations whose rows
+    are longer than the matrices (ldx > J, lddy > I, ldy > I, lddx > J): the outputs must equal those of the
+    packed call (which the exact tests above compare with the oracle), and the padding must stay untouched."""
+    import torch
+    I, J, T, pad = 4096, 1024, 16400, 8
+    rng = np.random.default_rng(515)
+    Wh = synth.store(int_weights(I, J, rng), synth.BF16)
+    Xh = synth.store(sparse_rows(T, J, rng), synth.BF16)
+    dYh = synth.store(sparse_rows(T, I, rng), synth.BF16)
+    W, X, dY = to_dev(Wh, synth.BF16), to_dev(Xh, synth.BF16), to_dev(dYh, synth.BF16)
+    P = i32_dev(rng.permutation(I).astype(np.int32))
+    B, vals, index = bm.bimask_forward_mask_compress(W, 2, 4)
+    _, vb, ib = bm.bimask_backward_mask_compress(W, 2, 4, B, P)
+    Y = bm.bimask_sparse_gemm_fwd(X, vals, index, I, J, 2, 4)
+    dX = bm.bimask_sparse_gemm_bwd(dY, P, vb, ib, I, J, 2, 4)
+    fill = -3.0
+    Xp = torch.full((T, J + pad), fill, dtype=torch.bfloat16, device=X.device)
+    dYp = torch.full((T, I + pad), fill, dtype=torch.bfloat16, device=X.device)
+    Xp[:, :J], dYp[:, :I] = X, dY
+    Yp = torch.full((T, I + pad), fill, dtype=torch.bfloat16, device=X.device)
+    dXp = torch.full((T, J + pad), fill, dtype=torch.bfloat16, device=X.device)
+    bm.bimask_sparse_gemm_fwd(Xp[:, :J], vals, index, I, J, 2, 4, Y=Yp[:, :I])
+    bm.bimask_sparse_gemm_bwd(dYp[:, :I], P, vb, ib, I, J, 2, 4, dX=dXp[:, :J])
+    torch.cuda.synchronize()
+    assert torch.equal(Yp[:, :I], Y) and torch.equal(dXp[:, :J], dX)
+    assert bool((Yp[:, I:] == fill).all()) and bool((dXp[:, J:] == fill).all())
+    assert float(Y.float().abs().max()) > 0 and float(dX.float().abs().max()) > 0
